@@ -1,0 +1,225 @@
+"""ctypes front end of the CPU oracle (``fs_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The product package never imports this module, and this
+module never imports the product package.
+
+``build()`` compiles ``fs_oracle.c`` with gcc into ``liboracle.so`` next to this file;
+``lib()`` loads it (building it first if it is missing).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fs_oracle.c")
+_SO = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle.  Plain x86-64 code (no -march=native): the .so travels between hosts."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+_u16p = np.ctypeslib.ndpointer(dtype=np.uint16, flags="C_CONTIGUOUS")
+_f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
+_i64p = np.ctypeslib.ndpointer(dtype=np.int64, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_u32p = np.ctypeslib.ndpointer(dtype=np.uint32, flags="C_CONTIGUOUS")
+
+
+def lib():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    L = C.CDLL(_SO)
+    L.fso_philox4x32_10.argtypes = [_u32p, _u32p, _u32p]
+    L.fso_philox4x32_10.restype = None
+    L.fso_random_word.argtypes = [C.c_uint64, C.c_int64, C.c_int64]
+    L.fso_random_word.restype = C.c_uint32
+    L.fso_uniform_x.argtypes = [C.c_uint32]
+    L.fso_uniform_x.restype = C.c_float
+    L.fso_gumbel_from_word.argtypes = [C.c_uint32]
+    L.fso_gumbel_from_word.restype = C.c_double
+    L.fso_gumbel.argtypes = [C.c_uint64, C.c_int64, C.c_int64]
+    L.fso_gumbel.restype = C.c_double
+    L.fso_logit.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64]
+    L.fso_logit.restype = C.c_double
+    L.fso_logits.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f64p]
+    L.fso_logits.restype = C.c_int
+    L.fso_gumbel_max_row.argtypes = [_f64p, C.c_int64, C.c_double, C.c_uint64, C.c_int64, C.c_int64,
+                                     C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    L.fso_gumbel_max_row.restype = None
+    L.fso_score_at.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                               C.c_uint64, C.c_int64, C.c_int64]
+    L.fso_score_at.restype = C.c_double
+    L.fso_sample.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                             C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, _i32p, _f32p, _f64p,
+                             _i64p, _f64p]
+    L.fso_sample.restype = C.c_int
+    L.fso_sample_tiled.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                                   C.c_void_p, C.c_int64, C.c_int64, C.c_int64, _f64p, _i64p,
+                                   _i32p, _f32p]
+    L.fso_sample_tiled.restype = C.c_int
+    L.fso_draw_counts.argtypes = [_f64p, C.c_int64, C.c_double, C.c_uint64, C.c_int64, C.c_int64,
+                                  C.c_int, _i64p, C.c_void_p]
+    L.fso_draw_counts.restype = None
+    L.fso_softmax.argtypes = [_f64p, C.c_int64, C.c_double, _f64p, C.POINTER(C.c_double)]
+    L.fso_softmax.restype = None
+    L.fso_gumbel_from_words.argtypes = [_u32p, C.c_int64, _f64p, C.c_void_p]
+    L.fso_gumbel_from_words.restype = None
+    L.fso_random_words.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, _u32p]
+    L.fso_random_words.restype = None
+    L.fso_num_threads.argtypes = []
+    L.fso_num_threads.restype = C.c_int
+    _lib = L
+    return L
+
+
+# ----------------------------------------------------------------------------- numpy wrappers
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    ctr = np.ascontiguousarray(ctr, dtype=np.uint32)
+    key = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().fso_philox4x32_10(ctr, key, out)
+    return out
+
+
+def random_word(seed: int, row: int, vocab_id: int) -> int:
+    return int(lib().fso_random_word(seed, row, vocab_id))
+
+
+def random_words(seed: int, row: int, v0: int, n: int) -> np.ndarray:
+    out = np.empty(n, dtype=np.uint32)
+    lib().fso_random_words(seed, row, v0, n, out)
+    return out
+
+
+def uniform_x(r: int) -> float:
+    return float(lib().fso_uniform_x(r))
+
+
+def gumbel_from_word(r: int) -> float:
+    return float(lib().fso_gumbel_from_word(r))
+
+
+def gumbel_from_words(r: np.ndarray):
+    r = np.ascontiguousarray(r, dtype=np.uint32)
+    g = np.empty(r.size, dtype=np.float64)
+    x = np.empty(r.size, dtype=np.float32)
+    lib().fso_gumbel_from_words(r, r.size, g, x.ctypes.data_as(C.c_void_p))
+    return g, x
+
+
+def gumbel(seed: int, row: int, vocab_id: int) -> float:
+    return float(lib().fso_gumbel(seed, row, vocab_id))
+
+
+def logit(H: np.ndarray, W: np.ndarray, b: int, i: int) -> float:
+    return float(lib().fso_logit(H, W, H.shape[1], b, i))
+
+
+def logits(H: np.ndarray, W: np.ndarray) -> np.ndarray:
+    B, D = H.shape
+    V = W.shape[0]
+    assert W.shape[1] == D
+    Y = np.empty((B, V), dtype=np.float64)
+    lib().fso_logits(H, W, B, D, V, Y)
+    return Y
+
+
+def gumbel_max_row(y: np.ndarray, tau: float, seed: int, row: int, vocab_offset: int = 0):
+    """Streaming Gumbel-max over one row of raw logits -> (idx, val, idx2, val2)."""
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    i1, i2 = C.c_int64(), C.c_int64()
+    m1, m2 = C.c_double(), C.c_double()
+    lib().fso_gumbel_max_row(y, y.size, float(tau), seed, row, vocab_offset,
+                             C.byref(i1), C.byref(m1), C.byref(i2), C.byref(m2))
+    return i1.value, m1.value, i2.value, m2.value
+
+
+def score_at(H, W, b_local: int, i_local: int, tau: float, seed: int, row: int, vocab_id: int) -> float:
+    return float(lib().fso_score_at(H, W, H.shape[1], b_local, i_local, float(tau), seed, row, vocab_id))
+
+
+def _opt_ptr(a: Optional[np.ndarray], dtype):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def sample(H, W, tau, seed: int = 0, row_seeds=None, row_offset: int = 0, row_ids=None,
+           vocab_offset: int = 0):
+    """Full path.  Returns dict(idx, val, top1, idx2, top2, threads)."""
+    B, D = H.shape
+    V = W.shape[0]
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    assert tau.shape == (B,)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    ri, ri_p = _opt_ptr(row_ids, np.int64)
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    top1 = np.empty(B, dtype=np.float64)
+    idx2 = np.empty(B, dtype=np.int64)
+    top2 = np.empty(B, dtype=np.float64)
+    nt = lib().fso_sample(H, W, B, D, V, tau, seed, rs_p, row_offset, ri_p, vocab_offset,
+                          out_idx, out_val, top1, idx2, top2)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, top1=top1, idx2=idx2, top2=top2, threads=nt)
+
+
+def sample_tiled(H, W, tau, tile: int, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                 vocab_offset: int = 0):
+    """Two-stage form with vocabulary tile size `tile`.  Returns dict(idx, val, cand_val, cand_idx)."""
+    B, D = H.shape
+    V = W.shape[0]
+    T = (V + tile - 1) // tile
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    cand_val = np.empty((B, T), dtype=np.float64)
+    cand_idx = np.empty((B, T), dtype=np.int64)
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    nt = lib().fso_sample_tiled(H, W, B, D, V, tau, seed, rs_p, row_offset, vocab_offset, tile,
+                                cand_val, cand_idx, out_idx, out_val)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, cand_val=cand_val, cand_idx=cand_idx)
+
+
+def draw_counts(y, tau: float, seed: int, ndraws: int, by_row: bool = True, row0: int = 0,
+                return_vals: bool = False):
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    counts = np.zeros(y.size, dtype=np.int64)
+    vals = np.empty(ndraws, dtype=np.float64) if return_vals else None
+    vp = vals.ctypes.data_as(C.c_void_p) if return_vals else None
+    lib().fso_draw_counts(y, y.size, float(tau), seed, row0, ndraws, 1 if by_row else 0, counts, vp)
+    return (counts, vals) if return_vals else counts
+
+
+def softmax(y, tau: float = 1.0):
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    p = np.empty_like(y)
+    lse = C.c_double()
+    lib().fso_softmax(y, y.size, float(tau), p, C.byref(lse))
+    return p, lse.value
+
+
+def num_threads() -> int:
+    return int(lib().fso_num_threads())

@@ -1,0 +1,310 @@
+/*
+ * CPU oracle for the fused LM-head + Gumbel-max sampling path.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, direct
+ * evaluation of what the method computes, used only by the tests, by the smoke
+ * check and by the CPU-baseline leg of the benchmark.  It shares no code,
+ * header, table or helper with the HIP library and neither includes the other.
+ *
+ * What it computes (one row b at a time, rows are independent):
+ *   1. logits            y_i = sum_d H[b,d] * W[i,d]            (Alg. 1, tiled matmul line;
+ *                        bf16 inputs widened exactly, accumulated in fp64, d ascending)
+ *   2. transform         z_i = y_i / tau_b                       (Alg. 1, "transform": temperature)
+ *   3. noise             r_i = word (i & 3) of Philox4x32-10(counter = (i >> 2, row, 0, 0),
+ *                        key = (lo32(seed_b), hi32(seed_b)))     (Section "RNG determinism":
+ *                        a counter-based generator indexed by the logical position (b, i))
+ *                        x_i = min(fma((float)r_i, 2^-32, 2^-33), 1 - 2^-24)   in fp32
+ *                        u_i = 1 - x_i  in the open interval (0,1)
+ *                        g_i = -log(-log u_i) = -log(-log1p(-x_i))             in fp64
+ *                        (Alg. 1 "Draw u in (0,1)"; appendix "Numerically Stable and Fast
+ *                        Gumbel Generation"; the paper's (r+1)/(2^32+1) is NOT used because in
+ *                        fp32 it rounds to 1.0 for the top 129 values of r)
+ *   4. perturbed score   s_i = z_i + g_i                          (Alg. 1)
+ *   5. streaming argmax  keep (m, i*) with a strict s_i > m update, i ascending, so the lowest
+ *                        index wins exact ties (appendix Alg. "Gumbel-Max sampling (standalone
+ *                        logits)"; Theorem "Gumbel-Max")
+ *   6. out_idx[b] = i* (0-based), out_val[b] = (float) m.
+ *
+ * A tiled variant (per-tile (m, idx) candidates, then an argmax over tiles) exists only to
+ * demonstrate the Lemma "Max over vocabulary tiles" on the oracle itself and to check the
+ * GPU's candidate buffer.
+ *
+ * NaN scores never win (the strict > comparison is false for NaN); a row with no
+ * score > -inf returns idx = -1, val = -inf.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ Philox4x32-10 */
+/* Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3" (SC'11). */
+
+void fso_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+        uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 32-bit random word for logical position (row, vocab_id) under a 64-bit seed. */
+uint32_t fso_random_word(uint64_t seed, int64_t row, int64_t vocab_id)
+{
+    uint32_t ctr[4] = { (uint32_t)((uint64_t)vocab_id >> 2), (uint32_t)(uint64_t)row, 0u, 0u };
+    uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    fso_philox4x32_10(ctr, key, out);
+    return out[(uint64_t)vocab_id & 3u];
+}
+
+/* ------------------------------------------------------------------ uniform -> Gumbel */
+
+/* x = 1 - u as an fp32 value in (0, 1): the shared starting point of both implementations. */
+float fso_uniform_x(uint32_t r)
+{
+    float x = fmaf((float)r, 0x1p-32f, 0x1p-33f);
+    float cap = 1.0f - 0x1p-24f;
+    return x < cap ? x : cap;
+}
+
+/* g = -log(-log u), u = 1 - x, evaluated in fp64. */
+double fso_gumbel_from_word(uint32_t r)
+{
+    double x = (double)fso_uniform_x(r);
+    return -log(-log1p(-x));
+}
+
+double fso_gumbel(uint64_t seed, int64_t row, int64_t vocab_id)
+{
+    return fso_gumbel_from_word(fso_random_word(seed, row, vocab_id));
+}
+
+/* ------------------------------------------------------------------ logits */
+
+static inline double bf16_to_double(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* One logit: y = sum_d H[b,d] * W[i,d], fp64, d ascending. */
+double fso_logit(const uint16_t* H, const uint16_t* W, int64_t D, int64_t b, int64_t i)
+{
+    const uint16_t* h = H + b * D;
+    const uint16_t* w = W + i * D;
+    double acc = 0.0;
+    for (int64_t d = 0; d < D; ++d)
+        acc += bf16_to_double(h[d]) * bf16_to_double(w[d]);
+    return acc;
+}
+
+/* All logits Y[B,V] (row-major, fp64).  Returns the number of threads used. */
+int fso_logits(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V, double* Y)
+{
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < V; ++i)
+        for (int64_t b = 0; b < B; ++b)
+            Y[b * V + i] = fso_logit(H, W, D, b, i);
+    return nthreads;
+}
+
+/* ------------------------------------------------------------------ streaming Gumbel-max */
+
+/*
+ * One row of raw logits y[0..V) -> sample.  vocab ids are vocab_offset + i (global ids, so a
+ * vocabulary shard reproduces the unsharded noise).  Also returns the runner-up
+ * (second-largest perturbed score and its index; -inf / -1 if V < 2) for the near-tie rule.
+ */
+void fso_gumbel_max_row(const double* y, int64_t V, double tau, uint64_t seed, int64_t row,
+                        int64_t vocab_offset, int64_t* best_idx, double* best_val,
+                        int64_t* second_idx, double* second_val)
+{
+    double m = -INFINITY, m2 = -INFINITY;
+    int64_t im = -1, im2 = -1;
+    for (int64_t i = 0; i < V; ++i) {
+        int64_t vid = vocab_offset + i;
+        double z = y[i] / tau;
+        double g = fso_gumbel(seed, row, vid);
+        double s = z + g;
+        if (s > m) {
+            m2 = m; im2 = im;
+            m = s; im = vid;
+        } else if (s > m2) {
+            m2 = s; im2 = vid;
+        }
+    }
+    *best_idx = im; *best_val = m;
+    if (second_idx) *second_idx = im2;
+    if (second_val) *second_val = m2;
+}
+
+/* Perturbed score of a single (row, vocab id): s = y/tau + g. */
+double fso_score_at(const uint16_t* H, const uint16_t* W, int64_t D, int64_t b_local,
+                    int64_t i_local, double tau, uint64_t seed, int64_t row, int64_t vocab_id)
+{
+    return fso_logit(H, W, D, b_local, i_local) / tau + fso_gumbel(seed, row, vocab_id);
+}
+
+static inline uint64_t row_seed(uint64_t seed, const uint64_t* row_seeds, int64_t b)
+{
+    return row_seeds ? row_seeds[b] : seed;
+}
+static inline int64_t row_id(const int64_t* row_ids, int64_t row_offset, int64_t b)
+{
+    return row_ids ? row_ids[b] : row_offset + b;
+}
+
+/*
+ * Full path: i*_b ~ Cat(softmax(H W^T / tau)) by Gumbel-max with the noise above.
+ *   H [B,D], W [V,D] bf16 bits; tau [B]; row_seeds [B] or NULL (then `seed` for all rows);
+ *   row_ids [B] or NULL (then row_offset + b) is the row word of the counter.
+ * Outputs (each may be NULL except out_idx): out_idx/out_val [B]; top1/top2 perturbed values in
+ * fp64 and the runner-up index, for the acceptance rule.  Returns threads used, or -1 on OOM.
+ */
+int fso_sample(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V,
+               const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+               const int64_t* row_ids, int64_t vocab_offset, int32_t* out_idx, float* out_val,
+               double* top1_val, int64_t* top2_idx, double* top2_val)
+{
+    if (B <= 0 || V <= 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits(H, W, B, D, V, Y);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t i1, i2;
+        double m1, m2;
+        fso_gumbel_max_row(Y + b * V, V, (double)tau[b], row_seed(seed, row_seeds, b),
+                           row_id(row_ids, row_offset, b), vocab_offset, &i1, &m1, &i2, &m2);
+        out_idx[b] = (int32_t)i1;
+        if (out_val) out_val[b] = (float)m1;
+        if (top1_val) top1_val[b] = m1;
+        if (top2_idx) top2_idx[b] = i2;
+        if (top2_val) top2_val[b] = m2;
+    }
+    free(Y);
+    return nthreads;
+}
+
+/*
+ * Two-stage form of Alg. 1 with an arbitrary vocabulary tile size: stage 1 keeps one
+ * (m, global idx) candidate per (row, tile); stage 2 takes the argmax over tiles, lowest tile
+ * first on exact ties.  cand_val/cand_idx are [B, T], T = ceil(V / tile).
+ */
+int fso_sample_tiled(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V,
+                     const float* tau, uint64_t seed, const uint64_t* row_seeds,
+                     int64_t row_offset, int64_t vocab_offset, int64_t tile, double* cand_val,
+                     int64_t* cand_idx, int32_t* out_idx, float* out_val)
+{
+    if (B <= 0 || V <= 0 || tile <= 0) return 0;
+    int64_t T = (V + tile - 1) / tile;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits(H, W, B, D, V, Y);
+    for (int64_t b = 0; b < B; ++b) {
+        /* Stage 1 */
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t lo = t * tile, hi = lo + tile < V ? lo + tile : V;
+            int64_t i1;
+            double m1;
+            fso_gumbel_max_row(Y + b * V + lo, hi - lo, (double)tau[b],
+                               row_seed(seed, row_seeds, b), row_offset + b, vocab_offset + lo,
+                               &i1, &m1, NULL, NULL);
+            cand_val[b * T + t] = m1;
+            cand_idx[b * T + t] = i1;
+        }
+        /* Stage 2 */
+        double m = -INFINITY;
+        int64_t im = -1;
+        for (int64_t t = 0; t < T; ++t)
+            if (cand_val[b * T + t] > m) { m = cand_val[b * T + t]; im = cand_idx[b * T + t]; }
+        out_idx[b] = (int32_t)im;
+        if (out_val) out_val[b] = (float)m;
+    }
+    free(Y);
+    return nthreads;
+}
+
+/* ------------------------------------------------------------------ helpers for the pins */
+
+/* counts[i] += number of draws that picked i, over draws k = 0..ndraws-1.
+ * by_row != 0: draw k uses (seed, row = row0 + k); else (seed + k, row = row0). */
+void fso_draw_counts(const double* y, int64_t V, double tau, uint64_t seed, int64_t row0,
+                     int64_t ndraws, int by_row, int64_t* counts, double* vals)
+{
+#pragma omp parallel
+    {
+        int64_t* local = (int64_t*)calloc((size_t)V, sizeof(int64_t));
+#pragma omp for schedule(static)
+        for (int64_t k = 0; k < ndraws; ++k) {
+            int64_t i1;
+            double m1;
+            uint64_t s = by_row ? seed : seed + (uint64_t)k;
+            int64_t row = by_row ? row0 + k : row0;
+            fso_gumbel_max_row(y, V, tau, s, row, 0, &i1, &m1, NULL, NULL);
+            if (i1 >= 0) local[i1] += 1;
+            if (vals) vals[k] = m1;
+        }
+#pragma omp critical
+        for (int64_t i = 0; i < V; ++i) counts[i] += local[i];
+        free(local);
+    }
+}
+
+/* Brute-force softmax probabilities of z = y / tau in fp64 (max-shifted). */
+void fso_softmax(const double* y, int64_t V, double tau, double* p, double* lse)
+{
+    double zmax = -INFINITY;
+    for (int64_t i = 0; i < V; ++i) { double z = y[i] / tau; if (z > zmax) zmax = z; }
+    double sum = 0.0;
+    for (int64_t i = 0; i < V; ++i) { p[i] = exp(y[i] / tau - zmax); sum += p[i]; }
+    for (int64_t i = 0; i < V; ++i) p[i] /= sum;
+    if (lse) *lse = zmax + log(sum);
+}
+
+/* Gumbel variates for words r[0..n): bulk form of fso_gumbel_from_word. */
+void fso_gumbel_from_words(const uint32_t* r, int64_t n, double* g, float* x)
+{
+    for (int64_t k = 0; k < n; ++k) {
+        g[k] = fso_gumbel_from_word(r[k]);
+        if (x) x[k] = fso_uniform_x(r[k]);
+    }
+}
+
+/* Random words for vocab ids [v0, v0+n) of one row: bulk form of fso_random_word. */
+void fso_random_words(uint64_t seed, int64_t row, int64_t v0, int64_t n, uint32_t* out)
+{
+    for (int64_t k = 0; k < n; ++k) out[k] = fso_random_word(seed, row, v0 + k);
+}
+
+int fso_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
