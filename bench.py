@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LM-head + Gumbel-max sampling call on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--no-sweep] [--no-cpu]
+
+One "step" is one whole call of the hot path (stage 1 + stage 2) on one batch of synthetic
+input of the Llama-3-8B-shaped LM head (D=4096, V=128256, bf16; workload C2).  The headline
+line is quoted at B=16, the largest batch of the bandwidth-bound decode regime; the same JSON
+line carries a sweep over B = 1..256 with the unfused comparison path beside it.
+
+Timing: W warm-up calls, then exactly K calls bracketed by events on the stream the kernels are
+launched on (torch's current stream, which is passed to the library), with a device
+synchronisation on both sides.  Inputs are resident in HBM before the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--batch", type=int, default=16, help="batch size of the headline line")
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the B = 1..256 sweep")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--variant", type=int, default=0, help="stage-1 kernel variant (0 = automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import fs_workloads as wl
+    import paper_2603_15854_amd as fs
+    from tests.parity import to_device_bf16
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    fs.lib()
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    D, V = w.D, w.V
+    T = fs.flash_sample_num_tiles(V)
+    flags = fs.FS_VARIANT(args.variant)
+
+    Wb = wl.make_weights(w)
+    Wd = to_device_bf16(Wb)
+    stream = torch.cuda.current_stream()
+
+    def setup(B):
+        H = wl.make_hidden(w, B)
+        s = dict(
+            B=B, H=H, Hd=to_device_bf16(H),
+            tau_h=wl.make_temperature(w, B),
+            seeds_h=wl.make_row_seeds(w, B),
+        )
+        s["tau"] = torch.from_numpy(s["tau_h"]).cuda()
+        s["seeds"] = None if s["seeds_h"] is None else torch.from_numpy(s["seeds_h"].view(np.int64)).cuda()
+        s["ws"] = torch.empty(max(256, fs.flash_sample_workspace_bytes(B, V)), dtype=torch.uint8, device="cuda")
+        s["oi"] = torch.empty(B, dtype=torch.int32, device="cuda")
+        s["ov"] = torch.empty(B, dtype=torch.float32, device="cuda")
+        s["cv"] = torch.empty((B, T), dtype=torch.float32, device="cuda")
+        s["ci"] = torch.empty((B, T), dtype=torch.int32, device="cuda")
+        return s
+
+    def fused(s):
+        fs.flash_sample_ex(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"], out_idx=s["oi"],
+                           out_val=s["ov"], workspace=s["ws"], stream=stream, flags=flags)
+
+    def stage1(s):
+        fs.flash_sample_stage1(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"],
+                               cand_val=s["cv"], cand_idx=s["ci"], stream=stream, flags=flags)
+
+    def unfused(s):
+        fs.flash_sample_unfused(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"], logits=s["lg"],
+                                out_idx=s["oi"], out_val=s["ov"], workspace=s["ws"], stream=stream)
+
+    def timed(fn, s, steps, warmup):
+        """Average milliseconds per call over exactly `steps` calls."""
+        for _ in range(warmup):
+            fn(s)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            fn(s)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    # ------------------------------------------------------------------ headline: whole call at B
+    B = args.batch
+    s = setup(B)
+    ms = timed(fused, s, args.steps, args.warmup)
+    bytes_fused = fs.io_model_bytes(B, D, V, fused=True)
+    gbs = bytes_fused / (ms * 1e-3) / 1e9
+
+    # dominant kernel (stage 1) alone, same stream, same launch configuration
+    ms1 = timed(stage1, s, args.steps, args.warmup)
+    bytes_stage1 = 2 * V * D + 2 * B * D + 8 * B * T      # W once + H once + candidates written
+    roofline = {
+        "kernel": "stage1 (fused matmul + Gumbel-max epilogue)",
+        "bound": "hbm",
+        "achieved": round(bytes_stage1 / (ms1 * 1e-3) / 1e9, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(bytes_stage1 / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "us_per_launch": round(ms1 * 1e3, 2),
+        "algorithmic_bytes_per_launch": bytes_stage1,
+        "traffic": None,
+    }
+
+    out = {
+        "metric": "fused LM-head+sample HBM GB/s (algorithmic bytes per call / time per call), "
+                  f"D={D} V={V}, B={B}",
+        "value": round(gbs, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms, 5),
+        "us_per_call": round(ms * 1e3, 2),
+        "tokens_per_s": round(B / (ms * 1e-3), 1),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: Llama-3-8B-shaped LM head, D={D}, V={V}, B={B}, bf16 W~N(0,1/D), "
+                               "hidden~N(0,1), tau=1, per-row seeds",
+                   "batch": B, "D": D, "V": V, "vocab_tile": fs.FS_VOCAB_TILE},
+        "roofline": roofline,
+    }
+
+    # ------------------------------------------------------------------ sweep B = 1..256
+    if not args.no_sweep:
+        sweep = []
+        steps = max(20, args.steps // 2)
+        for Bs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+            ss = setup(Bs)
+            ss["lg"] = torch.empty((Bs, V), dtype=torch.float32, device="cuda")
+            f_ms = timed(fused, ss, steps, 10)
+            u_ms = timed(unfused, ss, steps, 10)
+            bf = fs.io_model_bytes(Bs, D, V, fused=True)
+            sweep.append({
+                "B": Bs,
+                "fused_us": round(f_ms * 1e3, 2),
+                "unfused_us": round(u_ms * 1e3, 2),
+                "fused_over_unfused_speedup": round(u_ms / f_ms, 4),
+                "tokens_per_s": round(Bs / (f_ms * 1e-3), 1),
+                "hbm_gbs": round(bf / (f_ms * 1e-3) / 1e9, 1),
+                "pct_hbm_peak": round(100.0 * bf / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+                "tflops": round(2.0 * Bs * D * V / (f_ms * 1e-3) / 1e12, 1),
+                "pct_mfma_peak": round(100.0 * 2.0 * Bs * D * V / (f_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+            })
+            del ss
+        out["sweep"] = sweep
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    if not args.no_cpu:
+        import oracle
+        oracle.lib()
+        Bc = min(B, 16)
+        t0 = time.perf_counter()
+        ref = oracle.sample(np.ascontiguousarray(s["H"][:Bc]), Wb, np.ascontiguousarray(s["tau_h"][:Bc]),
+                            seed=w.seed,
+                            row_seeds=None if s["seeds_h"] is None else np.ascontiguousarray(s["seeds_h"][:Bc]))
+        dt = time.perf_counter() - t0
+        bytes_c = fs.io_model_bytes(Bc, D, V, fused=True)
+        out["cpu_baseline"] = {
+            "value": round(bytes_c / dt / 1e9, 4),
+            "unit": "GB/s",
+            "us_per_call": round(dt * 1e6, 1),
+            "tokens_per_s": round(Bc / dt, 2),
+            "cores": int(ref["threads"]),
+            "kind": "oracle",
+            "sample": f"one whole call of the workload (B={Bc} rows, all V={V} logits per row), fp64 oracle",
+        }
+        same = int((ref["idx"] == s["oi"][:Bc].cpu().numpy()).sum())
+        out["cpu_baseline"]["rows_equal_to_gpu"] = f"{same}/{Bc}"
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,180 @@
+/*
+ * flash_sample.h -- C ABI of the MI355X (gfx950) fused LM-head + exact Gumbel-max sampler.
+ *
+ * The library draws, for every row b of a batch,
+ *
+ *        i*_b  ~  Cat( softmax( H_b W^T / tau_b ) )                 (paper, Section
+ *                                                                    "FlashSampling Algorithm")
+ *
+ * by the Gumbel-max identity  i* = argmax_i ( y_i / tau + g_i ),  g_i iid Gumbel(0,1)
+ * (Theorem "Gumbel-Max"), evaluated in two stages (Alg. 1 "FlashSampling (two-stages)"):
+ *
+ *   stage 1  for every vocabulary tile of FS_VOCAB_TILE ids: logits by a tiled bf16 matmul with
+ *            fp32 accumulation kept on chip, scaled by 1/tau, perturbed with Gumbel noise, and
+ *            reduced to one (max value, global vocabulary id) candidate per (row, tile);
+ *   stage 2  argmax over the [B, T] candidate buffer, T = ceil(V / FS_VOCAB_TILE).
+ *
+ * The [B, V] logits never reach device memory on the fused path.
+ *
+ * Noise (Section "Further details of FlashSampling", "RNG determinism"; appendix "Numerically
+ * Stable and Fast Gumbel Generation"): the 32-bit word for logical position (row, vocab id) is
+ * word (id & 3) of Philox4x32-10 with counter (id >> 2, row, 0, 0) and key
+ * (lo32(seed), hi32(seed)); x = min(fma((float)r, 2^-32, 2^-33), 1 - 2^-24); u = 1 - x lies in
+ * the open interval (0,1); g = -log(-log u) in fp32.  `row` is row_offset + b and `id` is
+ * vocab_offset + i, so a batch shard or a vocabulary shard reproduces the unsharded sample.
+ * Exact ties go to the lowest vocabulary id (strict > in the appendix Alg. "Gumbel-Max sampling
+ * (standalone logits)").  NaN scores never win; a row without any score > -inf returns
+ * idx = -1, val = -inf.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library neither frees nor
+ *     retains them.  `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *   - Calls are asynchronous on `stream`; there is no host synchronisation inside.
+ *   - hidden is bf16 [B, D] row-major, W is bf16 [V, D] row-major (one row per vocabulary id),
+ *     temperature is fp32 [B] with every entry finite and > 0 (not checked: device memory).
+ *   - hidden, W and logits must be 16-byte aligned and D a multiple of 8 (128-bit bf16 loads);
+ *     other pointers must be aligned to their element type.
+ *   - Returns FS_OK or an error code; never throws, never aborts.  Outputs are written only
+ *     when FS_OK is returned.  B == 0 is a successful no-op.
+ *   - Results are deterministic: the same inputs give the same outputs on every call.
+ */
+#ifndef FLASH_SAMPLE_H
+#define FLASH_SAMPLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_VOCAB_TILE 128 /* vocabulary ids per stage-1 candidate */
+
+typedef enum {
+    FS_OK = 0,
+    FS_ERR_NULL = 1,        /* a required pointer is NULL */
+    FS_ERR_SHAPE = 2,       /* B < 0, D <= 0, V <= 0, D % 8 != 0, or an id/row range overflows */
+    FS_ERR_ALIGN = 3,       /* a pointer is not aligned as required */
+    FS_ERR_WORKSPACE = 4,   /* workspace missing or smaller than flash_sample_workspace_bytes */
+    FS_ERR_HIP = 5,         /* a HIP runtime call failed (launch, allocation) */
+    FS_ERR_UNSUPPORTED = 6  /* unknown flag or a kernel variant that cannot run this shape */
+} fs_status;
+
+/* flags for the *_ex entry points */
+#define FS_FLAG_NONE 0u
+/* bits 8..15: kernel variant for stage 1 (0 = automatic choice).  Every variant computes the
+ * same candidates up to fp32 summation order; the tests use them to show tiling invariance. */
+#define FS_VARIANT(v) (((uint32_t)(v) & 0xFFu) << 8)
+#define FS_VARIANT_AUTO 0
+/* Split-K family (B <= 16, D <= 8192): the contraction dimension is split over the waves of a
+ * workgroup and each wave keeps its slice of the hidden states in registers.  For D > 4096 all of
+ * them run the same 64-k-steps-per-wave kernel; for D <= 4096 they differ in staging: */
+#define FS_VARIANT_SPLITK_A 1 /* 32 k-steps per wave, 16-k-step LDS stages, 2 register sets */
+#define FS_VARIANT_SPLITK_B 2 /* 32 k-steps per wave, 8-k-step stages, 2 register sets */
+#define FS_VARIANT_TILED 3    /* any B, any D: LDS-tiled 128 x (16*NB) workgroup tiles */
+#define FS_VARIANT_SPLITK_C 4 /* 16 k-steps per wave (twice the waves), 8-k-step stages */
+#define FS_VARIANT_SPLITK_D 5 /* 32 k-steps per wave, 8-k-step stages, 4 register sets */
+#define FS_VARIANT_SPLITK_E 6 /* 32 k-steps per wave, 4-k-step stages, two workgroups per CU */
+/* bits 16..19: tuning aid for the split-K variants, workgroups per compute unit (0 = automatic) */
+#define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
+
+/* Number of stage-1 candidates per row, T = ceil(V / FS_VOCAB_TILE). */
+int flash_sample_num_tiles(int V);
+
+/* Bytes of device workspace the *_ex entry points need for (B, V): the candidate buffer of
+ * Alg. 1 (one fp32 value and one int32 id per row and vocabulary tile), 256-byte aligned parts. */
+size_t flash_sample_workspace_bytes(int B, int V);
+
+/*
+ * Draw one vocabulary id per row: i*_b ~ Cat(softmax(hidden_b W^T / temperature_b)).
+ *   out_idx [B] int32   0-based vocabulary id
+ *   out_val [B] fp32    the winning perturbed score y/tau + g
+ * One seed for all rows (rows are separated by the row word of the counter).  Runs on the null
+ * stream and uses a workspace cached inside the library (grown with hipMalloc when a call needs
+ * more than any earlier one on this device; never shrunk).
+ */
+fs_status flash_sample(const void* hidden, const void* W, int B, int D, int V,
+                       const float* temperature, uint64_t seed,
+                       int32_t* out_idx, float* out_val);
+
+/*
+ * Same operation with everything explicit.
+ *   row_seeds    NULL, or [B] uint64: row b draws with row_seeds[b] instead of `seed`
+ *   row_offset   added to b to form the row word of the noise counter (batch sharding)
+ *   vocab_offset added to i to form the vocabulary id used by the noise and returned in
+ *                out_idx (vocabulary sharding); vocab_offset >= 0, vocab_offset + V <= 2^31 - 1
+ *   workspace    device buffer of at least flash_sample_workspace_bytes(B, V) bytes, 256-byte
+ *                aligned; contents are overwritten; must not be shared by overlapping calls
+ *   flags        FS_FLAG_NONE or FS_VARIANT(...)
+ */
+fs_status flash_sample_ex(const void* hidden, const void* W, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
+ * Stage 1 of Alg. 1 alone: writes the candidate buffer
+ *   cand_val [B, T] fp32, cand_idx [B, T] int32 (global vocabulary ids), T = flash_sample_num_tiles(V).
+ * If `logits` is not NULL the kernel also stores the raw logits y = hidden W^T as fp32 [B, V]
+ * (the paper's logits-store flag, Section "IO Cost Model and Predicted Speedup" and appendix
+ * "Logits-Store Ablation"); nothing else in the kernel changes.
+ */
+fs_status flash_sample_stage1(const void* hidden, const void* W, int B, int D, int V,
+                              const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                              int64_t row_offset, int32_t vocab_offset,
+                              float* cand_val, int32_t* cand_idx, float* logits,
+                              void* stream, uint32_t flags);
+
+/* Stage 2 of Alg. 1 alone: out[b] = candidate with the largest value over t in [0, T), lowest
+ * id on exact ties.  cand_val / cand_idx are [B, T]. */
+fs_status flash_sample_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
+                              int32_t* out_idx, float* out_val, void* stream);
+
+/*
+ * Unfused comparison path (the materialised-logits pipeline the paper's IO model calls the
+ * baseline, Section "IO Cost Model and Predicted Speedup"): a GEMM kernel writes fp32 logits
+ * [B, V] to device memory, a separate kernel re-reads them and runs streaming Gumbel-max
+ * (appendix Alg. "Gumbel-Max sampling (standalone logits)"), and the tile argmax finishes.
+ * Same noise, same result as flash_sample_ex up to fp32 rounding of the score.
+ *   logits  [B, V] fp32 device buffer, 16-byte aligned, overwritten
+ */
+fs_status flash_sample_unfused(const void* hidden, const void* W, int B, int D, int V,
+                               const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                               int64_t row_offset, int32_t vocab_offset, float* logits,
+                               int32_t* out_idx, float* out_val,
+                               void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/* First half of the unfused path alone: logits[b, i] = sum_d hidden[b, d] * W[i, d] (fp32). */
+fs_status flash_lm_head_logits(const void* hidden, const void* W, int B, int D, int V,
+                               float* logits, void* stream, uint32_t flags);
+
+/* Second half of the unfused path alone: Gumbel-max over stored fp32 logits [B, V]. */
+fs_status flash_gumbel_argmax_logits(const float* logits, int B, int V, const float* temperature,
+                                     uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                                     int32_t vocab_offset, int32_t* out_idx, float* out_val,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Debug tap: g_out[k] = Gumbel noise the stage-1 epilogue uses for (seed, row, v0 + k), k < n
+ * (Alg. 1, "Draw u in (0,1) and set g = -log(-log u)").  g_out is an fp32 [n] device buffer. */
+fs_status flash_sample_noise(uint64_t seed, int64_t row, int32_t v0, int n, float* g_out,
+                             void* stream);
+
+/* Debug tap of the uniform -> Gumbel map alone: g_out[k] = g(words[k]) for 32-bit words given by
+ * the caller (device arrays of n elements), so a test can sweep every exponent and the edge words. */
+fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_out, void* stream);
+
+/* Measurement aid, not part of the method: a plain streaming kernel of known size.
+ * dst == NULL: read `bytes` bytes from src (the read-bandwidth ceiling of the device);
+ * dst != NULL: copy src to dst.  bytes must be a multiple of 16, pointers 16-byte aligned.
+ * `sink` is a 4-byte device location the read variant may write to. */
+fs_status flash_sample_stream_probe(void* dst, const void* src, size_t bytes, uint32_t* sink,
+                                    void* stream);
+
+/* Static description of an error code (never NULL). */
+const char* fs_status_string(fs_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASH_SAMPLE_H */

@@ -1,0 +1,295 @@
+"""Thin Python binding of the C ABI in ``include/flash_sample.h`` (ctypes; argument marshalling
+only -- every step of the method runs in the HIP kernels of ``libflashsample.so``).
+
+PyTorch is used for device memory and streams, nothing else.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+
+Functions mirror the C names: ``flash_sample``, ``flash_sample_ex``, ``flash_sample_stage1``,
+``flash_sample_stage2``, ``flash_sample_unfused``, ``flash_lm_head_logits``,
+``flash_gumbel_argmax_logits``, ``flash_sample_noise``, ``flash_sample_gumbel_transform``,
+``flash_sample_stream_probe``,
+``flash_sample_num_tiles``, ``flash_sample_workspace_bytes``, ``fs_status_string``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflashsample.so")
+
+FS_OK = 0
+FS_ERR_NULL, FS_ERR_SHAPE, FS_ERR_ALIGN, FS_ERR_WORKSPACE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = 1, 2, 3, 4, 5, 6
+FS_VOCAB_TILE = 128
+FS_VARIANT_AUTO, FS_VARIANT_SPLITK_A, FS_VARIANT_SPLITK_B, FS_VARIANT_TILED = 0, 1, 2, 3
+FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E = 4, 5, 6
+
+# every symbol include/flash_sample.h declares
+EXPORTS = (
+    "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
+    "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
+    "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
+    "flash_sample_stream_probe",
+    "fs_status_string",
+)
+
+
+def FS_VARIANT(v: int) -> int:
+    return (v & 0xFF) << 8
+
+
+def FS_TUNE_WGS_PER_CU(n: int) -> int:
+    return (n & 0xF) << 16
+
+
+class FlashSampleError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {fs_status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load libflashsample.so (built by ``python -m paper_2603_15854_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2603_15854_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u32, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_uint64, C.c_size_t
+    L.flash_sample_num_tiles.argtypes = [i32]
+    L.flash_sample_num_tiles.restype = i32
+    L.flash_sample_workspace_bytes.argtypes = [i32, i32]
+    L.flash_sample_workspace_bytes.restype = sz
+    L.flash_sample.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, vp]
+    L.flash_sample.restype = i32
+    L.flash_sample_ex.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_ex.restype = i32
+    L.flash_sample_stage1.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, u32]
+    L.flash_sample_stage1.restype = i32
+    L.flash_sample_stage2.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    L.flash_sample_stage2.restype = i32
+    L.flash_sample_unfused.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_unfused.restype = i32
+    L.flash_lm_head_logits.argtypes = [vp, vp, i32, i32, i32, vp, vp, u32]
+    L.flash_lm_head_logits.restype = i32
+    L.flash_gumbel_argmax_logits.argtypes = [vp, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, sz, vp]
+    L.flash_gumbel_argmax_logits.restype = i32
+    L.flash_sample_noise.argtypes = [u64, i64, C.c_int32, i32, vp, vp]
+    L.flash_sample_noise.restype = i32
+    L.flash_sample_gumbel_transform.argtypes = [vp, i32, vp, vp]
+    L.flash_sample_gumbel_transform.restype = i32
+    L.flash_sample_stream_probe.argtypes = [vp, vp, sz, vp, vp]
+    L.flash_sample_stream_probe.restype = i32
+    L.fs_status_string.argtypes = [i32]
+    L.fs_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def fs_status_string(status: int) -> str:
+    return lib().fs_status_string(int(status)).decode()
+
+
+def flash_sample_num_tiles(V: int) -> int:
+    return int(lib().flash_sample_num_tiles(int(V)))
+
+
+def flash_sample_workspace_bytes(B: int, V: int) -> int:
+    return int(lib().flash_sample_workspace_bytes(int(B), int(V)))
+
+
+# ----------------------------------------------------------------------------- marshalling
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str) -> None:
+    if status != FS_OK:
+        raise FlashSampleError(status, where)
+
+
+def _shapes(hidden, W):
+    import torch
+    if hidden.dtype != torch.bfloat16 or W.dtype != torch.bfloat16:
+        raise ValueError("hidden and W must be bfloat16")
+    if hidden.dim() != 2 or W.dim() != 2 or hidden.shape[1] != W.shape[1]:
+        raise ValueError("hidden must be [B, D] and W [V, D]")
+    return hidden.shape[0], hidden.shape[1], W.shape[0]
+
+
+def _outputs(B, device, out_idx, out_val):
+    import torch
+    if out_idx is None:
+        out_idx = torch.empty(B, dtype=torch.int32, device=device)
+    if out_val is None:
+        out_val = torch.empty(B, dtype=torch.float32, device=device)
+    return out_idx, out_val
+
+
+def _workspace(B, V, device, workspace):
+    import torch
+    need = flash_sample_workspace_bytes(B, V)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+# ----------------------------------------------------------------------------- entry points
+
+def flash_sample(hidden, W, temperature, seed: int = 0, out_idx=None, out_val=None):
+    """i*_b ~ Cat(softmax(hidden_b W^T / temperature_b)); returns (out_idx int32 [B], out_val fp32 [B]).
+    Runs on the null stream (the C entry point's contract)."""
+    B, D, V = _shapes(hidden, W)
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    st = lib().flash_sample(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                            _ptr(out_idx), _ptr(out_val))
+    _check(st, "flash_sample")
+    return out_idx, out_val
+
+
+def flash_sample_ex(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                    vocab_offset: int = 0, out_idx=None, out_val=None, workspace=None, stream=None,
+                    flags: int = 0):
+    B, D, V = _shapes(hidden, W)
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
+    st = lib().flash_sample_ex(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(out_idx),
+                               _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
+    _check(st, "flash_sample_ex")
+    return out_idx, out_val
+
+
+def flash_sample_stage1(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                        vocab_offset: int = 0, cand_val=None, cand_idx=None, logits=None,
+                        want_candidates: bool = True, stream=None, flags: int = 0):
+    """Stage 1 alone.  Returns (cand_val [B,T] fp32, cand_idx [B,T] int32) (None, None if not wanted)."""
+    import torch
+    B, D, V = _shapes(hidden, W)
+    T = flash_sample_num_tiles(V)
+    if want_candidates:
+        if cand_val is None:
+            cand_val = torch.empty((B, T), dtype=torch.float32, device=hidden.device)
+        if cand_idx is None:
+            cand_idx = torch.empty((B, T), dtype=torch.int32, device=hidden.device)
+    st = lib().flash_sample_stage1(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                                   _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(cand_val),
+                                   _ptr(cand_idx), _ptr(logits), _stream_ptr(stream), int(flags))
+    _check(st, "flash_sample_stage1")
+    return cand_val, cand_idx
+
+
+def flash_sample_stage2(cand_val, cand_idx, out_idx=None, out_val=None, stream=None):
+    B, T = cand_val.shape
+    out_idx, out_val = _outputs(B, cand_val.device, out_idx, out_val)
+    st = lib().flash_sample_stage2(_ptr(cand_val), _ptr(cand_idx), B, T, _ptr(out_idx), _ptr(out_val),
+                                   _stream_ptr(stream))
+    _check(st, "flash_sample_stage2")
+    return out_idx, out_val
+
+
+def flash_sample_unfused(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                         vocab_offset: int = 0, logits=None, out_idx=None, out_val=None,
+                         workspace=None, stream=None, flags: int = 0):
+    import torch
+    B, D, V = _shapes(hidden, W)
+    if logits is None:
+        logits = torch.empty((B, V), dtype=torch.float32, device=hidden.device)
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
+    st = lib().flash_sample_unfused(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                                    _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+                                    _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes,
+                                    _stream_ptr(stream), int(flags))
+    _check(st, "flash_sample_unfused")
+    return out_idx, out_val, logits
+
+
+def flash_lm_head_logits(hidden, W, logits=None, stream=None, flags: int = 0):
+    import torch
+    B, D, V = _shapes(hidden, W)
+    if logits is None:
+        logits = torch.empty((B, V), dtype=torch.float32, device=hidden.device)
+    st = lib().flash_lm_head_logits(_ptr(hidden), _ptr(W), B, D, V, _ptr(logits), _stream_ptr(stream),
+                                    int(flags))
+    _check(st, "flash_lm_head_logits")
+    return logits
+
+
+def flash_gumbel_argmax_logits(logits, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                               vocab_offset: int = 0, out_idx=None, out_val=None, workspace=None,
+                               stream=None):
+    B, V = logits.shape
+    out_idx, out_val = _outputs(B, logits.device, out_idx, out_val)
+    workspace, ws_bytes = _workspace(B, V, logits.device, workspace)
+    st = lib().flash_gumbel_argmax_logits(_ptr(logits), B, V, _ptr(temperature), int(seed),
+                                          _ptr(row_seeds), int(row_offset), int(vocab_offset),
+                                          _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes,
+                                          _stream_ptr(stream))
+    _check(st, "flash_gumbel_argmax_logits")
+    return out_idx, out_val
+
+
+def flash_sample_noise(seed: int, row: int, v0: int, n: int, device="cuda", stream=None):
+    import torch
+    g = torch.empty(n, dtype=torch.float32, device=device)
+    st = lib().flash_sample_noise(int(seed), int(row), int(v0), int(n), _ptr(g), _stream_ptr(stream))
+    _check(st, "flash_sample_noise")
+    return g
+
+
+def flash_sample_gumbel_transform(words, stream=None):
+    import torch
+    g = torch.empty(words.numel(), dtype=torch.float32, device=words.device)
+    st = lib().flash_sample_gumbel_transform(_ptr(words), words.numel(), _ptr(g), _stream_ptr(stream))
+    _check(st, "flash_sample_gumbel_transform")
+    return g
+
+
+def flash_sample_stream_probe(src, dst=None, sink=None, stream=None):
+    nbytes = src.numel() * src.element_size()
+    st = lib().flash_sample_stream_probe(_ptr(dst), _ptr(src), nbytes, _ptr(sink), _stream_ptr(stream))
+    _check(st, "flash_sample_stream_probe")
+
+
+# ----------------------------------------------------------------------------- byte model
+
+def io_model_bytes(B: int, D: int, V: int, fused: bool = True) -> int:
+    """Algorithmic HBM bytes of one call (the paper's IO cost model, Section "IO Cost Model and
+    Predicted Speedup", in bytes: bf16 W and H, fp32 logits, 8-byte candidates and outputs).
+    fused:    2 V D + 2 B D + 2 * 8 B T + 8 B
+    unfused:  2 V D + 2 B D + 2 * 4 B V + 2 * 8 B TC + 8 B      (TC = ceil(V / 1024))"""
+    T = (V + FS_VOCAB_TILE - 1) // FS_VOCAB_TILE
+    base = 2 * V * D + 2 * B * D + 8 * B
+    if fused:
+        return base + 2 * 8 * B * T
+    TC = (V + 1023) // 1024
+    return base + 2 * 4 * B * V + 2 * 8 * B * TC
+
+
+def io_model_speedup_elements(B: int, D: int, V: int) -> float:
+    """M_baseline / M_fused of the paper's IO cost model, in element counts as printed there:
+    (VD + DB + 2VB + B) / (VD + DB + B)."""
+    return (V * D + D * B + 2 * V * B + B) / (V * D + D * B + B)

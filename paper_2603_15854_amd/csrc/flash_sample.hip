@@ -1,0 +1,405 @@
+// Host side of the C ABI declared in include/flash_sample.h: argument checks, kernel choice,
+// launches.  Every step of the method runs in the kernels; nothing here touches the data.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "flash_sample.h"
+#include "fs_aux_kernels.hpp"
+#include "fs_common.hpp"
+#include "fs_stage1_splitk.hpp"
+#include "fs_stage1_tiled.hpp"
+
+namespace {
+
+using namespace fs;
+
+constexpr size_t kLdsPerCU = 160 * 1024;   // gfx950
+constexpr int kMaxDevices = 16;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+struct DeviceInfo {
+    bool known = false;
+    int cus = 256;
+    void* ws = nullptr;      // workspace cache of the plain entry point
+    size_t ws_bytes = 0;
+};
+DeviceInfo g_dev[kMaxDevices];
+std::mutex g_mu;
+
+// Compute units of the current device (cached).  Returns <= 0 on a HIP error.
+int current_device_cus(int* dev_out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_dev[dev].known) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            return -1;
+        g_dev[dev].cus = cus;
+        g_dev[dev].known = true;
+    }
+    if (dev_out) *dev_out = dev;
+    return g_dev[dev].cus;
+}
+
+// Kernels that use more than 64 KiB of dynamic LDS must say so once.
+template <class K>
+hipError_t allow_lds(K kernel, size_t bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+fs_status check_problem(const void* hidden, const void* W, int B, int D, int V,
+                        int64_t row_offset, int32_t vocab_offset)
+{
+    if (B < 0 || D <= 0 || V <= 0 || (D & 7) != 0) return FS_ERR_SHAPE;
+    if (vocab_offset < 0 || (int64_t)vocab_offset + (int64_t)V > (int64_t)INT32_MAX) return FS_ERR_SHAPE;
+    if (row_offset < 0) return FS_ERR_SHAPE;
+    if (B == 0) return FS_OK;
+    if (!hidden || !W) return FS_ERR_NULL;
+    if (!aligned(hidden, 16) || !aligned(W, 16)) return FS_ERR_ALIGN;
+    return FS_OK;
+}
+
+inline int num_tiles(int V) { return (V + kVocabTile - 1) / kVocabTile; }
+inline int num_chunks(int V) { return (V + kLogitsChunk - 1) / kLogitsChunk; }
+
+struct Workspace {
+    float* cand_val;
+    int32_t* cand_idx;
+};
+
+size_t workspace_bytes(int B, int V)
+{
+    if (B <= 0 || V <= 0) return 0;
+    const size_t per = align_up((size_t)B * (size_t)num_tiles(V) * 4, 256);
+    return 2 * per;
+}
+
+Workspace carve(void* ws, int B, int V)
+{
+    const size_t per = align_up((size_t)B * (size_t)num_tiles(V) * 4, 256);
+    Workspace w;
+    w.cand_val = reinterpret_cast<float*>(ws);
+    w.cand_idx = reinterpret_cast<int32_t*>(reinterpret_cast<unsigned char*>(ws) + per);
+    return w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// stage-1 launchers
+
+template <class Cfg>
+fs_status launch_splitk(const Stage1Params& p, int kpw, int nw, int wgs_per_cu_override, hipStream_t st)
+{
+    const size_t lds = Cfg::lds_bytes(nw);
+    if (nw > Cfg::kMaxWaves || lds > kLdsPerCU) return FS_ERR_UNSUPPORTED;
+    auto kernel = stage1_splitk_kernel<Cfg>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        attr_set = true;
+    }
+    const int cus = current_device_cus(nullptr);
+    if (cus <= 0) return FS_ERR_HIP;
+    // persistent grid: as many workgroups as are resident at once (registers and LDS decide)
+    static int resident[Cfg::kMaxWaves + 1] = {0};
+    if (resident[nw] == 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, nw * kWave, lds) != hipSuccess)
+            return FS_ERR_HIP;
+        resident[nw] = occ < 1 ? 1 : occ;
+    }
+    int per_cu = resident[nw];
+    if (wgs_per_cu_override > 0) per_cu = wgs_per_cu_override;
+    int grid = cus * per_cu;
+    if (grid > p.T) grid = p.T;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(nw * kWave), lds, st, p, nw, kpw);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+template <int NB>
+fs_status launch_tiled(const Stage1Params& p, hipStream_t st)
+{
+    using Cfg = TiledCfg<NB>;
+    auto kernel = stage1_tiled_kernel<NB>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        attr_set = true;
+    }
+    const int nbt = (p.B + Cfg::kBatchTile - 1) / Cfg::kBatchTile;
+    const long long grid = (long long)p.T * nbt;
+    if (grid > 0x7FFFFFFFll) return FS_ERR_SHAPE;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), Cfg::lds_bytes(), st, p);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
+{
+    if (p.B <= 16) return launch_tiled<1>(p, st);
+    if (p.B <= 32) return launch_tiled<2>(p, st);
+    if (p.B <= 64) return launch_tiled<4>(p, st);
+    if (p.B <= 128) return launch_tiled<8>(p, st);
+    return launch_tiled<16>(p, st);
+}
+
+fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
+{
+    if (flags & ~0x000FFF00u) return FS_ERR_UNSUPPORTED;
+    const int variant = (int)((flags >> 8) & 0xFFu);
+    const int wgs_override = (int)((flags >> 16) & 0xFu);
+    const int ksteps = (p.D + 31) / 32;
+    // split-K family: the hidden slice of a wave lives in registers, so the wave's k-range is
+    // bounded (32 k-steps = 128 VGPRs, or 64 k-steps = 256 VGPRs at one wave per SIMD)
+    auto splitk = [&](int which) -> fs_status {
+        if (p.B > 16 || ksteps > 64 * 4) return FS_ERR_UNSUPPORTED;
+        if (ksteps > 32 * 4) {
+            const int nw = (ksteps + 63) / 64;
+            const int kpw = (ksteps + nw - 1) / nw;
+            return launch_splitk<SplitKCfg<64, 16, 2, 4>>(p, kpw, nw, wgs_override, st);
+        }
+        if (which == FS_VARIANT_SPLITK_C) {
+            const int nw = (ksteps + 15) / 16;
+            const int kpw = (ksteps + nw - 1) / nw;
+            return launch_splitk<SplitKCfg<16, 8, 2, 8>>(p, kpw, nw, wgs_override, st);
+        }
+        const int nw = (ksteps + 31) / 32;
+        const int kpw = (ksteps + nw - 1) / nw;
+        switch (which) {
+        case FS_VARIANT_SPLITK_B: return launch_splitk<SplitKCfg<32, 8, 2, 4>>(p, kpw, nw, wgs_override, st);
+        case FS_VARIANT_SPLITK_D: return launch_splitk<SplitKCfg<32, 8, 4, 4>>(p, kpw, nw, wgs_override, st);
+        case FS_VARIANT_SPLITK_E: return launch_splitk<SplitKCfg<32, 4, 2, 8>>(p, kpw, nw, wgs_override, st);
+        default:                  return launch_splitk<SplitKCfg<32, 16, 2, 4>>(p, kpw, nw, wgs_override, st);
+        }
+    };
+    switch (variant) {
+    case FS_VARIANT_AUTO:
+        if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_A);
+        return launch_tiled_auto(p, st);
+    case FS_VARIANT_SPLITK_A:
+    case FS_VARIANT_SPLITK_B:
+    case FS_VARIANT_SPLITK_C:
+    case FS_VARIANT_SPLITK_D:
+    case FS_VARIANT_SPLITK_E:
+        return splitk(variant);
+    case FS_VARIANT_TILED:
+        return launch_tiled_auto(p, st);
+    default:
+        return FS_ERR_UNSUPPORTED;
+    }
+}
+
+fs_status launch_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
+                        int32_t* out_idx, float* out_val, hipStream_t st)
+{
+    hipLaunchKernelGGL(stage2_kernel, dim3(B), dim3(256), 0, st, cand_val, cand_idx, T, out_idx, out_val);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+int flash_sample_num_tiles(int V) { return V > 0 ? num_tiles(V) : 0; }
+
+size_t flash_sample_workspace_bytes(int B, int V) { return workspace_bytes(B, V); }
+
+const char* fs_status_string(fs_status s)
+{
+    switch (s) {
+    case FS_OK: return "ok";
+    case FS_ERR_NULL: return "a required pointer is NULL";
+    case FS_ERR_SHAPE: return "bad shape: need B >= 0, D > 0, V > 0, D % 8 == 0, offsets in range";
+    case FS_ERR_ALIGN: return "a pointer is not aligned as required";
+    case FS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FS_ERR_HIP: return "a HIP runtime call failed";
+    case FS_ERR_UNSUPPORTED: return "unknown flag, or the requested kernel variant cannot run this shape";
+    }
+    return "unknown status";
+}
+
+fs_status flash_sample_stage1(const void* hidden, const void* W, int B, int D, int V,
+                              const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                              int64_t row_offset, int32_t vocab_offset,
+                              float* cand_val, int32_t* cand_idx, float* logits,
+                              void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK || B == 0) return s;
+    if ((cand_val == nullptr) != (cand_idx == nullptr)) return FS_ERR_NULL;
+    if (!cand_val && !logits) return FS_ERR_NULL;
+    if (cand_val && !temperature) return FS_ERR_NULL;
+    if (logits && !aligned(logits, 16)) return FS_ERR_ALIGN;
+    if (!aligned(cand_val, 4) || !aligned(cand_idx, 4) || !aligned(temperature, 4) ||
+        !aligned(row_seeds, 8))
+        return FS_ERR_ALIGN;
+    Stage1Params p;
+    p.H = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W);
+    p.B = B; p.D = D; p.V = V; p.T = num_tiles(V);
+    p.tau = temperature;
+    p.seed = seed; p.row_seeds = row_seeds;
+    p.row_offset = row_offset; p.vocab_offset = vocab_offset;
+    p.cand_val = cand_val; p.cand_idx = cand_idx; p.logits = logits;
+    return launch_stage1(p, flags, static_cast<hipStream_t>(stream));
+}
+
+fs_status flash_sample_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
+                              int32_t* out_idx, float* out_val, void* stream)
+{
+    if (B < 0 || T <= 0) return FS_ERR_SHAPE;
+    if (B == 0) return FS_OK;
+    if (!cand_val || !cand_idx || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(cand_val, 4) || !aligned(cand_idx, 4) || !aligned(out_idx, 4) || !aligned(out_val, 4))
+        return FS_ERR_ALIGN;
+    return launch_stage2(cand_val, cand_idx, B, T, out_idx, out_val, static_cast<hipStream_t>(stream));
+}
+
+fs_status flash_sample_ex(const void* hidden, const void* W, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK || B == 0) return s;
+    if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(out_idx, 4) || !aligned(out_val, 4)) return FS_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < workspace_bytes(B, V))
+        return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);
+    s = flash_sample_stage1(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset,
+                            ws.cand_val, ws.cand_idx, nullptr, stream, flags);
+    if (s != FS_OK) return s;
+    return launch_stage2(ws.cand_val, ws.cand_idx, B, num_tiles(V), out_idx, out_val,
+                         static_cast<hipStream_t>(stream));
+}
+
+fs_status flash_sample(const void* hidden, const void* W, int B, int D, int V,
+                       const float* temperature, uint64_t seed, int32_t* out_idx, float* out_val)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, 0, 0);
+    if (s != FS_OK || B == 0) return s;
+    if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    int dev = 0;
+    if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
+    const size_t need = workspace_bytes(B, V);
+    void* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        DeviceInfo& d = g_dev[dev];
+        if (d.ws_bytes < need) {
+            // the old buffer may still be in use by an earlier call on the null stream
+            if (d.ws) {
+                if (hipStreamSynchronize(nullptr) != hipSuccess) return FS_ERR_HIP;
+                (void)hipFree(d.ws);
+                d.ws = nullptr;
+                d.ws_bytes = 0;
+            }
+            if (hipMalloc(&d.ws, need) != hipSuccess) { d.ws = nullptr; return FS_ERR_HIP; }
+            d.ws_bytes = need;
+        }
+        ws = d.ws;
+    }
+    return flash_sample_ex(hidden, W, B, D, V, temperature, seed, nullptr, 0, 0, out_idx, out_val,
+                           ws, need, nullptr, FS_FLAG_NONE);
+}
+
+fs_status flash_lm_head_logits(const void* hidden, const void* W, int B, int D, int V,
+                               float* logits, void* stream, uint32_t flags)
+{
+    if (B > 0 && !logits) return FS_ERR_NULL;
+    return flash_sample_stage1(hidden, W, B, D, V, nullptr, 0, nullptr, 0, 0, nullptr, nullptr, logits,
+                               stream, flags);
+}
+
+fs_status flash_gumbel_argmax_logits(const float* logits, int B, int V, const float* temperature,
+                                     uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                                     int32_t vocab_offset, int32_t* out_idx, float* out_val,
+                                     void* workspace, size_t workspace_bytes_given, void* stream)
+{
+    if (B < 0 || V <= 0 || row_offset < 0 || vocab_offset < 0 ||
+        (int64_t)vocab_offset + (int64_t)V > (int64_t)INT32_MAX || B > 65535)
+        return FS_ERR_SHAPE;
+    if (B == 0) return FS_OK;
+    if (!logits || !temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(logits, 16) || !aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(row_seeds, 8))
+        return FS_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < workspace_bytes(B, V))
+        return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);   // [B, TC] fits inside [B, T]: TC <= T
+    const int TC = num_chunks(V);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(gumbel_argmax_logits_kernel, dim3(TC, B), dim3(256), 0, st, logits, V, TC,
+                       temperature, seed, row_seeds, row_offset, vocab_offset, ws.cand_val, ws.cand_idx);
+    if (hipGetLastError() != hipSuccess) return FS_ERR_HIP;
+    return launch_stage2(ws.cand_val, ws.cand_idx, B, TC, out_idx, out_val, st);
+}
+
+fs_status flash_sample_unfused(const void* hidden, const void* W, int B, int D, int V,
+                               const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                               int64_t row_offset, int32_t vocab_offset, float* logits,
+                               int32_t* out_idx, float* out_val,
+                               void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK || B == 0) return s;
+    if (!logits || !temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (B > 65535) return FS_ERR_SHAPE;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < workspace_bytes(B, V))
+        return FS_ERR_WORKSPACE;
+    s = flash_lm_head_logits(hidden, W, B, D, V, logits, stream, flags);
+    if (s != FS_OK) return s;
+    return flash_gumbel_argmax_logits(logits, B, V, temperature, seed, row_seeds, row_offset, vocab_offset,
+                                      out_idx, out_val, workspace, workspace_bytes_given, stream);
+}
+
+fs_status flash_sample_noise(uint64_t seed, int64_t row, int32_t v0, int n, float* g_out, void* stream)
+{
+    if (n < 0 || v0 < 0 || row < 0 || (int64_t)v0 + n > (int64_t)INT32_MAX) return FS_ERR_SHAPE;
+    if (n == 0) return FS_OK;
+    if (!g_out) return FS_ERR_NULL;
+    if (!aligned(g_out, 4)) return FS_ERR_ALIGN;
+    hipLaunchKernelGGL(noise_kernel, dim3((n + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       seed, (uint32_t)(uint64_t)row, v0, n, g_out);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_out, void* stream)
+{
+    if (n < 0) return FS_ERR_SHAPE;
+    if (n == 0) return FS_OK;
+    if (!words || !g_out) return FS_ERR_NULL;
+    if (!aligned(words, 4) || !aligned(g_out, 4)) return FS_ERR_ALIGN;
+    hipLaunchKernelGGL(gumbel_transform_kernel, dim3((n + 255) / 256), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), words, n, g_out);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+fs_status flash_sample_stream_probe(void* dst, const void* src, size_t bytes, uint32_t* sink, void* stream)
+{
+    if ((bytes & 15) != 0) return FS_ERR_SHAPE;
+    if (bytes == 0) return FS_OK;
+    if (!src) return FS_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(dst, 16) || !aligned(sink, 4)) return FS_ERR_ALIGN;
+    const int cus = current_device_cus(nullptr);
+    if (cus <= 0) return FS_ERR_HIP;
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    const size_t cap = (size_t)cus * 8;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(stream_probe_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src), n16, sink);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+}  // extern "C"

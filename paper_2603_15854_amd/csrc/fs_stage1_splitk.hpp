@@ -1,0 +1,221 @@
+// Stage 1 of Alg. 1 for the bandwidth-bound decode regime (B <= 16): the whole batch is one
+// 16-wide MFMA operand, so the kernel is a stream over W and nothing else matters.
+//
+// Work split.  A workgroup owns vocabulary tiles t = blockIdx.x, blockIdx.x + gridDim.x, ...
+// (128 ids each = 8 row-tiles of 16 ids).  Its NW waves split the contraction dimension:
+// wave w owns k-steps [w*kpw, (w+1)*kpw) (one k-step = 32 elements).  The wave's slice of the
+// hidden states, in MFMA operand layout, is loaded ONCE into registers (<= KPW*4 VGPRs) and
+// reused for every vocabulary row the workgroup ever touches, so the steady-state global traffic
+// is W alone, read exactly once, in runs of up to KPW*64 contiguous bytes per row.
+//
+// Data path of W:  global --128-bit coalesced loads--> registers (the in-flight window, PF
+// stages deep) --ds_write_b128--> wave-private LDS stage (XOR-swizzled) --ds_read_b128 in MFMA
+// operand layout--> v_mfma_f32_16x16x32_bf16 with A = W rows (M = vocabulary), B = hidden
+// (N = batch, zero-padded to 16).  The LDS hop only transposes lanes: a coalesced load gives
+// a lane 16 consecutive bytes of ONE row per 64-lane instruction, the MFMA wants lane l to hold
+// row l%16.  Stages are wave-private, so the main loop has no barrier.
+//
+// After the 8 row-tiles of a vocabulary tile each wave parks its fp32 partial tiles in LDS;
+// one barrier; then wave w reduces the partials of row-tiles w, w+NW, ... in fixed wave order
+// (deterministic), scales by 1/tau, adds Gumbel noise (one Philox block per lane per row-tile:
+// a lane holds 4 consecutive vocabulary ids of one batch row), and keeps a running
+// (max, id).  A second barrier, a 16-lane merge over waves, and the candidate is written.
+#pragma once
+
+#include "fs_common.hpp"
+
+namespace fs {
+
+// KPW: k-steps per wave (register-resident hidden slice); SK: k-steps per LDS stage;
+// PF: stage register sets in flight; MAXW: upper bound on waves per workgroup (launch bounds).
+template <int KPW, int SK, int PF, int MAXW>
+struct SplitKCfg {
+    static constexpr int kKPW = KPW;
+    static constexpr int kSK = SK;
+    static constexpr int kPF = PF;
+    static constexpr int kMaxWaves = MAXW;
+    static constexpr int kStagesPerRowTile = KPW / SK;
+    static constexpr int kRowBytes = SK * 64;                 // bytes of one row inside a stage
+    static constexpr int kStageBytes = 16 * kRowBytes;        // 16 rows
+    static constexpr int kLanesPerRow = kRowBytes / 16;       // lanes that cover one row
+    static constexpr int kRowsPerInstr = kWave / kLanesPerRow;
+    static constexpr int kInstrPerStage = 16 / kRowsPerInstr;
+    static_assert(KPW % SK == 0, "stage must divide the wave's k-range");
+    static_assert(kStagesPerRowTile % PF == 0 && PF <= kStagesPerRowTile, "static register sets");
+    static_assert(kLanesPerRow >= 16 && kLanesPerRow <= 64, "swizzle needs >= 16 chunks per row");
+
+    // LDS bytes for nw waves: stages + partial tiles [8][nw][64] float4 + wave candidates.
+    static constexpr size_t lds_bytes(int nw)
+    {
+        return (size_t)nw * kStageBytes + (size_t)8 * nw * 1024 + (size_t)nw * 16 * 8;
+    }
+};
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::kMaxWaves * kWave)
+stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
+{
+    constexpr int KPW = Cfg::kKPW, SK = Cfg::kSK, PF = Cfg::kPF;
+    constexpr int NSTG = Cfg::kStagesPerRowTile;
+    constexpr int NI = Cfg::kInstrPerStage;
+    constexpr int LPR = Cfg::kLanesPerRow;
+    constexpr int RPI = Cfg::kRowsPerInstr;
+    constexpr int ROWB = Cfg::kRowBytes;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15;   // batch column of the MFMA B operand / of the output tile
+    const int g = lane >> 4;   // k-group of the operands, row-group of the output tile
+    const int B = p.B, D = p.D, V = p.V;
+
+    // this wave's slice of the contraction dimension
+    const int ksteps_total = (D + 31) >> 5;
+    const int ks0 = wave * kpw;
+    int nks = ksteps_total - ks0;
+    nks = nks < 0 ? 0 : (nks > kpw ? kpw : nks);
+    const int kbeg = ks0 * 32;
+    int kend = kbeg + nks * 32;
+    kend = kend > D ? D : kend;
+
+    unsigned char* stage = smem + (size_t)wave * Cfg::kStageBytes;
+    f32x4* partial = reinterpret_cast<f32x4*>(smem + (size_t)nw * Cfg::kStageBytes);
+    float2* wave_cand = reinterpret_cast<float2*>(smem + (size_t)nw * Cfg::kStageBytes +
+                                                  (size_t)8 * nw * 1024);
+
+    // hidden slice in B-operand layout: lane (n, g) holds H[n, k .. k+8), k = kbeg + 32 s + 8 g
+    bf16x8 hreg[KPW];
+#pragma unroll
+    for (int s = 0; s < KPW; ++s) {
+        const int k = kbeg + s * 32 + g * 8;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n < B && s < nks && k < D) v = ld_global_16B(p.H + (size_t)n * D + k);
+        hreg[s] = __builtin_bit_cast(bf16x8, v);
+    }
+
+    // per-row epilogue constants
+    float inv_tau = 1.0f;
+    uint64_t seed_n = p.seed;
+    if (n < B && p.cand_val) {   // logits-only launches pass no temperatures
+        inv_tau = 1.0f / p.tau[n];
+        if (p.row_seeds) seed_n = p.row_seeds[n];
+    }
+    const uint32_t row_word = (uint32_t)(uint64_t)(p.row_offset + n);
+
+    // row-tiles of this workgroup, in processing order
+    const int T = p.T;
+    const int ntiles = ((int)blockIdx.x < T) ? (T - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+    const int nrt = ntiles * 8;
+
+    // stage load geometry of this lane
+    const int ld_row = lane / LPR;           // row within one load instruction
+    const int ld_chunk = lane % LPR;         // 16-byte chunk within the row
+    const int ld_k = kbeg + ld_chunk * 8;    // + h * SK * 32
+
+    uint4 wreg[PF][NI];
+
+    auto row_base = [&](int rtl) -> int {
+        if (rtl >= nrt) return V;            // nothing there: every load predicated off
+        return ((int)blockIdx.x + (rtl >> 3) * (int)gridDim.x) * kVocabTile + (rtl & 7) * 16;
+    };
+    auto issue_loads = [&](uint4 (&dst)[NI], int rtl, int h) {
+        const int rb = row_base(rtl);
+        const int k = ld_k + h * (SK * 32);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int row = rb + j * RPI + ld_row;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (row < V && k < kend) v = ld_global_16B_stream(p.W + (size_t)row * D + k);
+            dst[j] = v;
+        }
+    };
+
+    // LDS addresses: a stage is [16 rows][ROWB bytes]; 16-byte chunk c of row r sits in slot
+    // c ^ (r & 15), which makes both the row-contiguous writes and the 16-rows-per-pass MFMA
+    // operand reads bank-conflict free.  Row r = j*RPI + ld_row of load j; the two terms occupy
+    // disjoint bits, so the offset is (st_base ^ const_j) + const_j'.
+    const int st_base = ld_row * ROWB + ((ld_chunk ^ ld_row) << 4);
+    auto st_off = [&](int j) -> int { return (st_base ^ (((j * RPI) & 15) << 4)) + j * RPI * ROWB; };
+    const int rd_row_off = n * ROWB;   // A-operand row of this lane is lane & 15
+
+#pragma unroll
+    for (int h = 0; h < PF; ++h) issue_loads(wreg[h], 0, h);
+
+    for (int rtl = 0; rtl < nrt; ++rtl) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int h = 0; h < NSTG; ++h) {
+            const int set = h % PF;
+            const bool active = h * SK < nks;   // wave-uniform
+            if (active) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    *reinterpret_cast<uint4*>(stage + st_off(j)) = wreg[set][j];
+            }
+            // refill the register set with the stage PF ahead in the stream
+            if (h + PF < NSTG) issue_loads(wreg[set], rtl, h + PF);
+            else               issue_loads(wreg[set], rtl + 1, h + PF - NSTG);
+            if (active) {
+#pragma unroll
+                for (int s = 0; s < SK; ++s) {
+                    const int c = 4 * s + g;
+                    const uint4 a = *reinterpret_cast<const uint4*>(stage + rd_row_off + ((c ^ n) << 4));
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                                  hreg[h * SK + s], acc, 0, 0, 0);
+                }
+            }
+        }
+        const int rt = rtl & 7;
+        partial[(rt * nw + wave) * 64 + lane] = acc;
+
+        if (rt == 7) {
+            const int tile = (int)blockIdx.x + (rtl >> 3) * (int)gridDim.x;
+            const int tile_row0 = tile * kVocabTile;
+            __syncthreads();   // all partial tiles of this vocabulary tile are in LDS
+            float best = -__builtin_inff();
+            int best_id = -1;
+            for (int r8 = wave; r8 < 8; r8 += nw) {
+                f32x4 y = partial[(r8 * nw) * 64 + lane];
+                for (int w = 1; w < nw; ++w) y += partial[(r8 * nw + w) * 64 + lane];
+                const int v0 = tile_row0 + r8 * 16 + 4 * g;   // local vocabulary row of y[0]
+                if (v0 < V && n < B) {
+                    if (p.logits) {
+                        float* dst = p.logits + (size_t)n * V + v0;
+                        if (v0 + 3 < V && (V & 3) == 0) {
+                            *reinterpret_cast<f32x4*>(dst) = y;
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (v0 + j < V) dst[j] = y[j];
+                        }
+                    }
+                    if (p.cand_val) {
+                        float gn[4];
+                        gumbel4(seed_n, row_word, (uint32_t)(p.vocab_offset + v0), gn);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float s = fmaf(y[j], inv_tau, gn[j]);
+                            if (v0 + j < V && s > best) { best = s; best_id = p.vocab_offset + v0 + j; }
+                        }
+                    }
+                }
+            }
+            cand_reduce_lane_groups(best, best_id);
+            if (g == 0) wave_cand[wave * 16 + n] = make_float2(best, __int_as_float(best_id));
+            __syncthreads();   // wave candidates visible; partial buffer free again
+            if (wave == 0 && lane < 16 && n < B && p.cand_val) {
+                float bv = -__builtin_inff();
+                int bi = -1;
+                for (int w = 0; w < nw; ++w) {
+                    const float2 c = wave_cand[w * 16 + n];
+                    cand_merge(bv, bi, c.x, __float_as_int(c.y));
+                }
+                p.cand_val[(size_t)n * T + tile] = bv;
+                p.cand_idx[(size_t)n * T + tile] = bi;
+            }
+        }
+    }
+}
+
+}  // namespace fs

@@ -1,0 +1,129 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and its byte model matches
+the paper's IO cost model."""
+import os
+import re
+
+import pytest
+
+import paper_2603_15854_amd as fs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "flash_sample.h")
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+FAKE = 0x7F0000001000  # an aligned, never dereferenced address: the checks under test return first
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flash_[a-z0-9_]+|fs_status_string)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = fs.lib()
+    declared = _declared_symbols()
+    assert declared, "no declarations found in the header"
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sorted(fs.EXPORTS) == declared        # the binding covers the same set
+
+
+def test_tile_and_workspace_arithmetic():
+    assert fs.FS_VOCAB_TILE == 128
+    assert fs.flash_sample_num_tiles(4096) == 32          # config 1: T = 32
+    assert fs.flash_sample_num_tiles(128256) == 1002
+    assert fs.flash_sample_num_tiles(152064) == 1188
+    assert fs.flash_sample_num_tiles(129280) == 1010
+    assert fs.flash_sample_num_tiles(129) == 2 and fs.flash_sample_num_tiles(1) == 1
+    assert fs.flash_sample_num_tiles(0) == 0
+    # candidates: one fp32 + one int32 per (row, tile), two 256-byte aligned parts
+    assert fs.flash_sample_workspace_bytes(16, 128256) == 2 * 64256          # 16*1002*4 = 64128 -> 64256
+    assert fs.flash_sample_workspace_bytes(1, 4096) == 2 * 256
+    assert fs.flash_sample_workspace_bytes(0, 4096) == 0
+
+
+def test_status_strings():
+    seen = set()
+    for code in range(0, 7):
+        s = fs.fs_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert fs.fs_status_string(99) == "unknown status"
+
+
+def test_bad_arguments_are_rejected_before_any_device_work():
+    L = fs.lib()
+
+    def ex(hidden=FAKE, W=FAKE, B=4, D=256, V=4096, tau=FAKE, row_offset=0, vocab_offset=0,
+           out_idx=FAKE, out_val=FAKE, ws=FAKE + 0x100000, ws_bytes=1 << 20, flags=0):
+        return L.flash_sample_ex(hidden, W, B, D, V, tau, 0, None, row_offset, vocab_offset, out_idx,
+                                 out_val, ws, ws_bytes, None, flags)
+
+    assert ex(B=0) == fs.FS_OK                                  # empty batch: successful no-op
+    assert ex(B=0, hidden=None, W=None, tau=None, out_idx=None, out_val=None, ws=None, ws_bytes=0) == fs.FS_OK
+    assert ex(B=-1) == fs.FS_ERR_SHAPE
+    assert ex(D=0) == fs.FS_ERR_SHAPE and ex(V=0) == fs.FS_ERR_SHAPE
+    assert ex(D=250) == fs.FS_ERR_SHAPE                         # D % 8 != 0
+    assert ex(vocab_offset=-1) == fs.FS_ERR_SHAPE
+    assert ex(vocab_offset=2**31 - 1 - 4095) == fs.FS_ERR_SHAPE  # vocab_offset + V overflows int32
+    assert ex(row_offset=-5) == fs.FS_ERR_SHAPE
+    assert ex(hidden=None) == fs.FS_ERR_NULL and ex(W=None) == fs.FS_ERR_NULL
+    assert ex(tau=None) == fs.FS_ERR_NULL and ex(out_idx=None) == fs.FS_ERR_NULL
+    assert ex(out_val=None) == fs.FS_ERR_NULL
+    assert ex(hidden=FAKE + 8) == fs.FS_ERR_ALIGN and ex(W=FAKE + 2) == fs.FS_ERR_ALIGN
+    assert ex(out_idx=FAKE + 2) == fs.FS_ERR_ALIGN
+    assert ex(ws=None) == fs.FS_ERR_WORKSPACE
+    assert ex(ws=FAKE + 0x100010) == fs.FS_ERR_WORKSPACE        # not 256-byte aligned
+    assert ex(ws_bytes=fs.flash_sample_workspace_bytes(4, 4096) - 1) == fs.FS_ERR_WORKSPACE
+
+    # the plain entry point, the stages and the unfused path share the checks
+    assert L.flash_sample(None, FAKE, 1, 256, 4096, FAKE, 0, FAKE, FAKE) == fs.FS_ERR_NULL
+    assert L.flash_sample(FAKE, FAKE, 1, 252, 4096, FAKE, 0, FAKE, FAKE) == fs.FS_ERR_SHAPE
+    assert L.flash_sample(FAKE, FAKE, 0, 256, 4096, FAKE, 0, FAKE, FAKE) == fs.FS_OK
+    assert L.flash_sample_stage1(FAKE, FAKE, 1, 256, 4096, FAKE, 0, None, 0, 0, None, None, None, None, 0) == fs.FS_ERR_NULL
+    assert L.flash_sample_stage1(FAKE, FAKE, 1, 256, 4096, FAKE, 0, None, 0, 0, FAKE, None, None, None, 0) == fs.FS_ERR_NULL
+    assert L.flash_sample_stage2(None, FAKE, 1, 32, FAKE, FAKE, None) == fs.FS_ERR_NULL
+    assert L.flash_sample_stage2(FAKE, FAKE, 1, 0, FAKE, FAKE, None) == fs.FS_ERR_SHAPE
+    assert L.flash_sample_stage2(FAKE, FAKE, 0, 32, FAKE, FAKE, None) == fs.FS_OK
+    assert L.flash_sample_unfused(FAKE, FAKE, 1, 256, 4096, FAKE, 0, None, 0, 0, None, FAKE, FAKE,
+                                  FAKE, 1 << 20, None, 0) == fs.FS_ERR_NULL
+    assert L.flash_lm_head_logits(FAKE, FAKE, 1, 256, 4096, None, None, 0) == fs.FS_ERR_NULL
+    assert L.flash_gumbel_argmax_logits(FAKE, 1, 0, FAKE, 0, None, 0, 0, FAKE, FAKE, FAKE, 1 << 20, None) == fs.FS_ERR_SHAPE
+    assert L.flash_sample_noise(0, 0, 0, -1, FAKE, None) == fs.FS_ERR_SHAPE
+    assert L.flash_sample_noise(0, 0, 0, 0, None, None) == fs.FS_OK
+    assert L.flash_sample_gumbel_transform(None, 4, FAKE, None) == fs.FS_ERR_NULL
+    assert L.flash_sample_stream_probe(None, FAKE, 24, None, None) == fs.FS_ERR_SHAPE
+    assert L.flash_sample_stream_probe(None, None, 32, None, None) == fs.FS_ERR_NULL
+
+
+def test_io_model_matches_the_papers_predicted_overheads():
+    # appendix table "Predicted vs. measured overhead of storing logits to HBM": 2B/D in percent
+    rows = []
+    with open(os.path.join(GOLDEN, "io_model.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                D, V, B, pct = line.split()
+                rows.append((int(D), int(V), int(B), float(pct)))
+    assert len(rows) == 12
+    for D, V, B, pct in rows:
+        model = (fs.io_model_speedup_elements(B, D, V) - 1.0) * 100.0
+        approx = 200.0 * B / D                                   # the printed column is 2B/D
+        assert abs(approx - pct) <= 0.0051, (D, V, B, approx, pct)
+        # the exact ratio 1 + 2/(D/B + D/V + 1/V) differs from it only by the D/V and 1/V terms
+        exact = 200.0 / (D / B + D / V + 1.0 / V)
+        assert abs(model - exact) < 1e-9
+        assert 0 < approx - model < approx * 1.01 * B / V
+    # byte form used by the benchmark: fp32 logits double the element-count overhead (4B/D)
+    B, D, V = 16, 4096, 128256
+    fused, unfused = fs.io_model_bytes(B, D, V, True), fs.io_model_bytes(B, D, V, False)
+    assert fused == 2 * V * D + 2 * B * D + 16 * B * 1002 + 8 * B
+    assert abs((unfused - fused) / fused - 4 * B / D) < 2e-3
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(fs, "_lib", None)
+    monkeypatch.setattr(fs, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        fs.lib()

@@ -1,0 +1,356 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer outputs (indices) must match exactly outside near-ties; floating-point outputs
+within the stated tolerances (see tests/parity.py for the acceptance rule)."""
+import numpy as np
+import pytest
+
+import fs_workloads as wl
+from tests.parity import judge, to_device_bf16, to_device_seeds
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fs():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2603_15854_amd as fs
+    fs.lib()          # fails loudly if the HIP library is missing
+    return fs
+
+
+_W_CACHE = {}
+
+
+def weights(name):
+    """(host bits, device tensor) of a workload's W, generated once per session."""
+    if name not in _W_CACHE:
+        _W_CACHE.clear()                     # keep one big W at a time on host and device
+        torch.cuda.empty_cache()
+        Wb = wl.make_weights(wl.WORKLOADS[name])
+        _W_CACHE[name] = (Wb, to_device_bf16(Wb))
+    return _W_CACHE[name]
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def run_fused(fs, Hd, Wd, tau, seed=0, row_seeds=None, flags=0, **kw):
+    idx, val = fs.flash_sample_ex(Hd, Wd, dev_f32(tau), seed=seed, row_seeds=to_device_seeds(row_seeds),
+                                  flags=flags, **kw)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), val.cpu().numpy()
+
+
+SMALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6]      # auto, split-K A/B, tiled, split-K C/D/E
+
+
+# ----------------------------------------------------------------------------- noise
+
+def test_gumbel_transform_matches_oracle_over_all_exponents(fs, orc):
+    # every power of two, its neighbours, the edge words, and a random sweep
+    words = [0, 1, 2, 3, 2**32 - 1, 2**32 - 2, 2**32 - 128, 2**32 - 129, 2**32 - 257]
+    for e in range(1, 32):
+        words += [2**e - 1, 2**e, 2**e + 1]
+    rng = np.random.default_rng(3)
+    words = np.array(words + list(rng.integers(0, 2**32, size=200_000)), dtype=np.uint32)
+    # dense coverage of the series/log switch at x = 2^-5 and of small x
+    words = np.concatenate([words, (2**27 + rng.integers(-2**20, 2**20, size=50_000)).astype(np.uint32),
+                            rng.integers(0, 2**20, size=50_000).astype(np.uint32)])
+    wd = torch.from_numpy(words.view(np.int32)).cuda()
+    g_gpu = fs.flash_sample_gumbel_transform(wd).cpu().numpy().astype(np.float64)
+    g_ref, _ = orc.gumbel_from_words(words)
+    assert np.all(np.isfinite(g_gpu))
+    assert np.max(np.abs(g_gpu - g_ref)) <= 1e-4
+    # relative to the size of g the error stays at fp32 rounding level
+    assert np.max(np.abs(g_gpu - g_ref) / (1.0 + np.abs(g_ref))) <= 5e-6
+
+
+def test_noise_tap_matches_oracle_counter_layout(fs, orc):
+    for seed, row, v0, n in [(0, 0, 0, 4096), ((7 << 32) | 9, 513, 128000, 5000), (3, 2**31 + 5, 1001, 777)]:
+        g_gpu = fs.flash_sample_noise(seed, row, v0, n).cpu().numpy().astype(np.float64)
+        g_ref, _ = orc.gumbel_from_words(orc.random_words(seed, row, v0, n))
+        assert np.max(np.abs(g_gpu - g_ref)) <= 1e-4, (seed, row, v0)
+
+
+# ----------------------------------------------------------------------------- small shapes
+
+def _small_case(fs, orc, B, D, V, variant, data_seed, tau=None, seed=5, row_seeds=None,
+                row_offset=0, vocab_offset=0, scale=1.0):
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=data_seed, w_row_scale=scale)
+    tau = np.linspace(0.6, 1.6, B).astype(np.float32) if tau is None else np.asarray(tau, np.float32)
+    ref = orc.sample(H, W, tau, seed=seed, row_seeds=row_seeds, row_offset=row_offset,
+                     vocab_offset=vocab_offset)
+    gi, gv = run_fused(fs, to_device_bf16(H), to_device_bf16(W), tau, seed=seed, row_seeds=row_seeds,
+                       row_offset=row_offset, vocab_offset=vocab_offset, flags=fs.FS_VARIANT(variant))
+    v = judge(orc, H, W, tau, gi, gv, ref, seed=seed, row_seeds=row_seeds, row_offset=row_offset,
+              vocab_offset=vocab_offset)
+    assert v.ok, (B, D, V, variant, str(v), v.failures[:3])
+    return v
+
+
+@pytest.mark.parametrize("variant", SMALL_VARIANTS)
+def test_config_c1_tiny(fs, orc, variant):
+    c1 = wl.WORKLOADS["C1"]
+    H, W = wl.make_hidden(c1, 1), wl.make_weights(c1)
+    tau = wl.make_temperature(c1, 1)
+    ref = orc.sample(H, W, tau, seed=c1.seed)
+    gi, gv = run_fused(fs, to_device_bf16(H), to_device_bf16(W), tau, seed=c1.seed,
+                       flags=fs.FS_VARIANT(variant))
+    v = judge(orc, H, W, tau, gi, gv, ref, seed=c1.seed)
+    assert v.ok and v.exact == 1, (str(v), v.failures)
+
+
+@pytest.mark.parametrize("variant", SMALL_VARIANTS)
+def test_candidate_buffer_matches_oracle_tiles(fs, orc, variant):
+    # stage 1 alone: every (row, 128-id tile) candidate against the oracle's two-stage form
+    B, D, V = (5, 512, 128 * 9 + 37)
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=41)
+    tau = np.array([1.0, 0.5, 1.5, 0.8, 1.2], dtype=np.float32)
+    ref = orc.sample_tiled(H, W, tau, 128, seed=17)
+    cv, ci = fs.flash_sample_stage1(to_device_bf16(H), to_device_bf16(W), dev_f32(tau), seed=17,
+                                    flags=fs.FS_VARIANT(variant))
+    oi, ov = fs.flash_sample_stage2(cv, ci)
+    torch.cuda.synchronize()
+    cv, ci = cv.cpu().numpy(), ci.cpu().numpy()
+    T = fs.flash_sample_num_tiles(V)
+    assert cv.shape == (B, T) == ref["cand_val"].shape
+    assert np.max(np.abs(cv - ref["cand_val"])) <= 2e-3 / 0.5 + 1e-3 * (1 + np.abs(ref["cand_val"]).max())
+    mism = np.argwhere(ci != ref["cand_idx"])
+    for b, t in mism:    # only near-ties inside the tile may differ
+        s = orc.score_at(H, W, int(b), int(ci[b, t]), float(tau[b]), 17, int(b), int(ci[b, t]))
+        assert ref["cand_val"][b, t] - s < 1e-3 * (1 + abs(ref["cand_val"][b, t]))
+    assert len(mism) <= 2
+    # stage 2 alone equals numpy argmax over the GPU's own candidates (bit exact, lowest id on ties)
+    t_star = np.argmax(cv, axis=1)
+    assert np.array_equal(oi.cpu().numpy(), ci[np.arange(B), t_star])
+    assert np.array_equal(ov.cpu().numpy(), cv[np.arange(B), t_star])
+
+
+SHAPES = [
+    # (B, D, V): ragged vocabulary tiles, ragged k-steps, one-element edges, several batch tiles
+    (1, 8, 1), (1, 8, 5), (3, 24, 127), (2, 264, 129), (16, 1000, 1000), (7, 4104, 300),
+    (4, 4096, 2048 + 64), (9, 7168, 520), (16, 8192, 260), (13, 2048, 128 * 20 + 1),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("variant", SMALL_VARIANTS)
+def test_small_batch_shapes_all_variants(fs, orc, shape, variant):
+    B, D, V = shape
+    if variant in (1, 2, 4, 5, 6) and D > 8192:
+        pytest.skip("split-K variants cover D <= 8192")
+    _small_case(fs, orc, B, D, V, variant, data_seed=50 + B + V)
+
+
+@pytest.mark.parametrize("shape", [(17, 512, 700), (33, 1032, 1300), (100, 264, 640), (130, 2048, 515),
+                                   (256, 512, 384), (300, 256, 1000), (5, 8200, 300), (2, 16384, 257)])
+def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
+    B, D, V = shape
+    _small_case(fs, orc, B, D, V, 0, data_seed=70 + B)
+    _small_case(fs, orc, B, D, V, 3, data_seed=70 + B)
+
+
+def test_split_k_variants_refuse_what_they_cannot_run(fs):
+    H = torch.zeros((17, 256), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((256, 256), dtype=torch.bfloat16, device="cuda")
+    tau = torch.ones(17, device="cuda")
+    with pytest.raises(fs.FlashSampleError) as e:
+        fs.flash_sample_ex(H, W, tau, flags=fs.FS_VARIANT(1))
+    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+    with pytest.raises(fs.FlashSampleError) as e:
+        fs.flash_sample_ex(H, W, tau, flags=fs.FS_VARIANT(99))
+    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+    with pytest.raises(fs.FlashSampleError) as e:
+        fs.flash_sample_ex(H, W, tau, flags=1)
+    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+
+
+def test_row_seeds_offsets_and_shards(fs, orc):
+    B, D, V = 6, 1024, 3000
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=90)
+    Hd, Wd = to_device_bf16(H), to_device_bf16(W)
+    tau = np.full(B, 0.9, dtype=np.float32)
+    seeds = np.array([0, 1, 2, (9 << 32) + 1, 2**63 + 5, 77], dtype=np.uint64)
+    for variant in (0, 3):
+        flags = fs.FS_VARIANT(variant)
+        # per-row seeds and a row offset
+        _small_case(fs, orc, B, D, V, variant, data_seed=90, tau=tau, row_seeds=seeds, row_offset=1000)
+        full_i, full_v = run_fused(fs, Hd, Wd, tau, seed=8, flags=flags)
+        # vocabulary shards with global ids (aligned and misaligned offsets) merge to the full result
+        for cuts in ([0, 1024, 2048, 3000], [0, 1001, 2003, 3000]):
+            best_v = np.full(B, -np.inf, dtype=np.float32)
+            best_i = np.full(B, -1, dtype=np.int32)
+            for lo, hi in zip(cuts[:-1], cuts[1:]):
+                gi, gv = run_fused(fs, Hd, Wd[lo:hi].contiguous(), tau, seed=8, vocab_offset=lo, flags=flags)
+                assert np.all((gi >= lo) & (gi < hi))
+                upd = gv > best_v
+                best_v, best_i = np.where(upd, gv, best_v), np.where(upd, gi, best_i)
+            assert np.array_equal(best_i, full_i), (variant, cuts)
+            assert np.allclose(best_v, full_v, rtol=0, atol=2e-5)
+        # batch shards with row offsets
+        gi, gv = run_fused(fs, Hd[2:5].contiguous(), Wd, tau[2:5], seed=8, row_offset=2, flags=flags)
+        assert np.array_equal(gi, full_i[2:5])
+
+
+def test_determinism_and_plain_entry_point(fs, orc):
+    c1 = wl.WORKLOADS["C1"]
+    H, W = wl.make_hidden(c1, 1), wl.make_weights(c1)
+    Hd, Wd = to_device_bf16(H), to_device_bf16(W)
+    tau = dev_f32(wl.make_temperature(c1, 1))
+    a = fs.flash_sample_ex(Hd, Wd, tau, seed=0)
+    b = fs.flash_sample_ex(Hd, Wd, tau, seed=0)
+    c = fs.flash_sample(Hd, Wd, tau, seed=0)          # null stream, cached workspace
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert torch.equal(a[0], c[0]) and torch.equal(a[1], c[1])
+    # the cached workspace grows when a later call needs more
+    H2, W2 = wl.make_small(D=256, V=20000, B=16, data_seed=91)
+    tau2 = np.ones(16, dtype=np.float32)
+    i2, v2 = fs.flash_sample(to_device_bf16(H2), to_device_bf16(W2), dev_f32(tau2), seed=4)
+    torch.cuda.synchronize()
+    ref = orc.sample(H2, W2, tau2, seed=4)
+    assert judge(orc, H2, W2, tau2, i2.cpu().numpy(), v2.cpu().numpy(), ref, seed=4).ok
+    # different seeds give different draws somewhere
+    i3, _ = fs.flash_sample(to_device_bf16(H2), to_device_bf16(W2), dev_f32(tau2), seed=5)
+    assert not torch.equal(i2, i3)
+    # empty batch is a no-op
+    e = fs.flash_sample_ex(Hd[:0], Wd, tau[:0])
+    assert e[0].numel() == 0
+
+
+def test_rows_without_a_finite_score(fs, orc):
+    B, D, V = 4, 256, 640
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=92)
+    H = H.copy()
+    H[1, :] = 0x7FC0            # bf16 NaN: every logit of row 1 is NaN
+    W = W.copy()
+    W[77, 0] = 0x7F80           # +inf weight: logits of id 77 are +-inf or NaN
+    tau = np.ones(B, dtype=np.float32)
+    ref = orc.sample(H, W, tau, seed=3)
+    assert ref["idx"][1] == -1
+    for variant in (0, 3):
+        gi, gv = run_fused(fs, to_device_bf16(H), to_device_bf16(W), tau, seed=3, flags=fs.FS_VARIANT(variant))
+        assert gi[1] == -1 and gv[1] == -np.inf
+        for b in (0, 2, 3):
+            assert gi[b] == ref["idx"][b]
+
+
+def test_logits_tap_and_unfused_path_small(fs, orc):
+    for (B, D, V) in [(3, 512, 1000), (16, 4096, 1300), (40, 1024, 2050), (130, 256, 1027)]:
+        H, W = wl.make_small(D=D, V=V, B=B, data_seed=93 + B)
+        Hd, Wd = to_device_bf16(H), to_device_bf16(W)
+        tau = np.linspace(0.5, 1.5, B).astype(np.float32)
+        Y = orc.logits(H, W)
+        for variant in (0, 3):
+            lg = fs.flash_lm_head_logits(Hd, Wd, flags=fs.FS_VARIANT(variant))
+            torch.cuda.synchronize()
+            assert np.max(np.abs(lg.cpu().numpy().astype(np.float64) - Y)) <= 2e-3   # per-logit budget
+        ref = orc.sample(H, W, tau, seed=6)
+        ui, uv, lg = fs.flash_sample_unfused(Hd, Wd, dev_f32(tau), seed=6)
+        fi, fv = fs.flash_sample_ex(Hd, Wd, dev_f32(tau), seed=6)
+        torch.cuda.synchronize()
+        v = judge(orc, H, W, tau, ui.cpu().numpy(), uv.cpu().numpy(), ref, seed=6)
+        assert v.ok, (B, D, V, str(v), v.failures[:3])
+        assert np.max(np.abs(lg.cpu().numpy().astype(np.float64) - Y)) <= 2e-3
+        same = (ui == fi).cpu().numpy()
+        assert same.sum() >= B - v.near_ties - 1
+        # the stored-logits sampler alone, fed the oracle's logits rounded to fp32
+        gi, gv = fs.flash_gumbel_argmax_logits(torch.from_numpy(Y.astype(np.float32)).cuda(), dev_f32(tau), seed=6)
+        torch.cuda.synchronize()
+        assert judge(orc, H, W, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, seed=6).ok
+
+
+# ----------------------------------------------------------------------------- full-size configs
+
+def _subset_rows(B, k=12):
+    """Rows spread over the batch, including both ends and 16-row block edges."""
+    if B <= k:
+        return list(range(B))
+    picks = {0, 1, 15, 16, 17, B - 1, B - 2, B // 2, B // 2 + 1}
+    rng = np.random.default_rng(B)
+    while len(picks) < k:
+        picks.add(int(rng.integers(0, B)))
+    return sorted(p for p in picks if p < B)
+
+
+def _full_config(fs, orc, name, B, flags=0, use_row_seeds=None, tau=None, subset=12):
+    w = wl.WORKLOADS[name]
+    Wb, Wd = weights(name)
+    H = wl.make_hidden(w, B)
+    tau = wl.make_temperature(w, B) if tau is None else tau
+    row_seeds = wl.make_row_seeds(w, B) if (use_row_seeds is None or use_row_seeds) else None
+    if use_row_seeds is False:
+        row_seeds = None
+    gi, gv = run_fused(fs, to_device_bf16(H), Wd, tau, seed=w.seed, row_seeds=row_seeds, flags=flags)
+    # (1) every row: the reported value is the oracle's score of the reported index
+    for b in range(B):
+        seed_b = int(row_seeds[b]) if row_seeds is not None else w.seed
+        assert 0 <= gi[b] < w.V
+        s = orc.score_at(H, Wb, b, int(gi[b]), float(tau[b]), seed_b, b, int(gi[b]))
+        assert abs(gv[b] - s) <= 2e-3 / min(float(tau[b]), 1.0) + 1e-3 * (1 + abs(s)), (name, B, b)
+    # (2) a spread of rows (all of them for small B): full argmax equality under the acceptance rule
+    rows = _subset_rows(B, subset)
+    ref = orc.sample(np.ascontiguousarray(H[rows]), Wb, np.ascontiguousarray(tau[rows]), seed=w.seed,
+                     row_seeds=None if row_seeds is None else np.ascontiguousarray(row_seeds[rows]),
+                     row_ids=np.array(rows, dtype=np.int64))
+    # judge() indexes H/gpu arrays by global row b and ref by position
+    v = judge(orc, H, Wb, tau, gi, gv, ref, seed=w.seed, row_seeds=row_seeds,
+              row_ids=np.array(rows, dtype=np.int64), rows=rows)
+    print(f"[parity] {name} B={B} flags={flags:#x}: {v}", flush=True)
+    assert v.ok, (name, B, str(v), v.failures[:3])
+    return gi, gv, v
+
+
+@pytest.mark.parametrize("B", [1, 2, 4, 8, 16])
+def test_config_c2_llama_shape(fs, orc, B):
+    gi, gv, _ = _full_config(fs, orc, "C2", B)                       # per-row seeds, all rows
+    _full_config(fs, orc, "C2", B, use_row_seeds=False)             # single seed entry
+    ti, tv, _ = _full_config(fs, orc, "C2", B, flags=fs.FS_VARIANT(3))   # tiled kernel, same draws
+    assert np.array_equal(gi, ti)
+    assert np.allclose(gv, tv, rtol=0, atol=1e-4)
+
+
+@pytest.mark.parametrize("B", [32, 64, 128])
+def test_config_c3_qwen_shape(fs, orc, B):
+    _full_config(fs, orc, "C3", B)
+
+
+def test_config_c4_compute_leaning_peaky(fs, orc):
+    _, _, v = _full_config(fs, orc, "C4", 256, subset=16)
+    # the unfused path draws the same tokens on this near-tie-heavy config
+    w = wl.WORKLOADS["C4"]
+    Wb, Wd = weights("C4")
+    H = wl.make_hidden(w, 256)
+    tau = wl.make_temperature(w, 256)
+    fi, fv = run_fused(fs, to_device_bf16(H), Wd, tau, seed=w.seed)
+    ui, uv, _ = fs.flash_sample_unfused(to_device_bf16(H), Wd, dev_f32(tau), seed=w.seed)
+    torch.cuda.synchronize()
+    assert (ui.cpu().numpy() != fi).sum() <= 2
+
+
+@pytest.mark.parametrize("B", [1, 8, 64, 256, 512])
+def test_config_c5_wide_hidden(fs, orc, B):
+    _full_config(fs, orc, "C5", B)
+
+
+def test_config_c5_temperature_to_zero_is_argmax(fs, orc):
+    w = wl.WORKLOADS["C5"]
+    Wb, Wd = weights("C5")
+    B = 8
+    H = wl.make_hidden(w, B)
+    tau = np.full(B, 1e-4, dtype=np.float32)
+    gi, gv = run_fused(fs, to_device_bf16(H), Wd, tau, seed=w.seed)
+    Y = orc.logits(H, Wb)
+    checked = 0
+    for b in range(B):
+        order = np.argsort(Y[b])
+        gap = Y[b, order[-1]] - Y[b, order[-2]]
+        if gap > 26 * 1e-4 + 4e-3:      # noise range (26 tau) plus the fp32 logit budget, both ways
+            assert gi[b] == order[-1], (b, gap)
+            checked += 1
+    assert checked >= B // 2
+    _full_config(fs, orc, "C5", B, tau=tau)     # and the general acceptance rule still holds
