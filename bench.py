@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the B = 1..256 sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--variant", type=int, default=0, help="stage-1 kernel variant (0 = automatic)")
+    ap.add_argument("--calibrate", type=int, default=0,
+                    help="also launch N plain read and N plain copy kernels over a W-sized buffer "
+                         "(known traffic, to scale the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -151,6 +154,17 @@ def main() -> int:
                    "batch": B, "D": D, "V": V, "vocab_tile": fs.FS_VOCAB_TILE},
         "roofline": roofline,
     }
+
+    if args.calibrate > 0:
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(Wd)
+        for _ in range(args.calibrate):
+            fs.flash_sample_stream_probe(Wd, sink=sink, stream=stream)            # reads 2*V*D bytes
+        for _ in range(args.calibrate):
+            fs.flash_sample_stream_probe(Wd, dst=dst, sink=sink, stream=stream)   # reads and writes 2*V*D
+        torch.cuda.synchronize()
+        out["calibration"] = {"probe_bytes": int(Wd.numel() * 2), "launches_each": args.calibrate}
+        del dst
 
     # ------------------------------------------------------------------ sweep B = 1..256
     if not args.no_sweep:
