@@ -75,6 +75,8 @@ typedef enum {
 #define FS_VARIANT_SPLITK_C 4 /* 16 k-steps per wave (twice the waves), 8-k-step stages */
 #define FS_VARIANT_SPLITK_D 5 /* 32 k-steps per wave, 8-k-step stages, 4 register sets */
 #define FS_VARIANT_SPLITK_E 6 /* 32 k-steps per wave, 4-k-step stages, two workgroups per CU */
+#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled 128 x {32,64,128} tiles, two register sets in
+                                 flight, two workgroups per CU, XCD-paired batch tiles (default for B > 16) */
 /* bits 16..19: tuning aid for the split-K variants, workgroups per compute unit (0 = automatic) */
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 

@@ -23,7 +23,7 @@ FS_OK = 0
 FS_ERR_NULL, FS_ERR_SHAPE, FS_ERR_ALIGN, FS_ERR_WORKSPACE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = 1, 2, 3, 4, 5, 6
 FS_VOCAB_TILE = 128
 FS_VARIANT_AUTO, FS_VARIANT_SPLITK_A, FS_VARIANT_SPLITK_B, FS_VARIANT_TILED = 0, 1, 2, 3
-FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E = 4, 5, 6
+FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E, FS_VARIANT_TILED2 = 4, 5, 6, 7
 
 # every symbol include/flash_sample.h declares
 EXPORTS = (

@@ -11,6 +11,7 @@
 #include "fs_common.hpp"
 #include "fs_stage1_splitk.hpp"
 #include "fs_stage1_tiled.hpp"
+#include "fs_stage1_tiled2.hpp"
 
 namespace {
 
@@ -150,6 +151,34 @@ fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
     return launch_tiled<16>(p, st);
 }
 
+template <class Cfg>
+fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
+{
+    const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
+    const long long grid = (long long)((p.T + 7) / 8) * 8 * nbt;
+    if (grid > 0x7FFFFFFFll) return FS_ERR_SHAPE;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (allow_lds(stage1_tiled2_kernel<Cfg, true>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, false>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        attr_set = true;
+    }
+    if (nbt == 1)
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true>), dim3((unsigned)grid), dim3(256),
+                           Cfg::lds_bytes(), st, p, nbt);
+    else
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false>), dim3((unsigned)grid), dim3(256),
+                           Cfg::lds_bytes(), st, p, nbt);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+fs_status launch_tiled2_auto(const Stage1Params& p, hipStream_t st)
+{
+    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>>(p, st);
+    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>>(p, st);
+    return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>>(p, st);
+}
+
 fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
 {
     if (flags & ~0x000FFF00u) return FS_ERR_UNSUPPORTED;
@@ -181,8 +210,9 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     };
     switch (variant) {
     case FS_VARIANT_AUTO:
-        if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_A);
-        return launch_tiled_auto(p, st);
+        if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_B);
+        if (p.B <= 16) return launch_tiled_auto(p, st);
+        return launch_tiled2_auto(p, st);
     case FS_VARIANT_SPLITK_A:
     case FS_VARIANT_SPLITK_B:
     case FS_VARIANT_SPLITK_C:
@@ -191,6 +221,8 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
         return splitk(variant);
     case FS_VARIANT_TILED:
         return launch_tiled_auto(p, st);
+    case FS_VARIANT_TILED2:
+        return launch_tiled2_auto(p, st);
     default:
         return FS_ERR_UNSUPPORTED;
     }

@@ -20,7 +20,18 @@ stage2_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ ca
     const int32_t* ci = cand_idx + (size_t)b * T;
     float best = -__builtin_inff();
     int best_id = -1;
-    for (int t = threadIdx.x; t < T; t += 256) cand_merge(best, best_id, cv[t], ci[t]);
+    for (int t0 = 0; t0 < T; t0 += 4 * 256) {   // four independent loads per thread in flight
+        float v[4];
+        int id[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = t0 + u * 256 + (int)threadIdx.x;
+            v[u] = t < T ? cv[t] : -__builtin_inff();
+            id[u] = t < T ? ci[t] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cand_merge(best, best_id, v[u], id[u]);
+    }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         const float ov = __shfl_xor(best, off, kWave);

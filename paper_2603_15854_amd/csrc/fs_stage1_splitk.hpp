@@ -84,16 +84,6 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     float2* wave_cand = reinterpret_cast<float2*>(smem + (size_t)nw * Cfg::kStageBytes +
                                                   (size_t)8 * nw * 1024);
 
-    // hidden slice in B-operand layout: lane (n, g) holds H[n, k .. k+8), k = kbeg + 32 s + 8 g
-    bf16x8 hreg[KPW];
-#pragma unroll
-    for (int s = 0; s < KPW; ++s) {
-        const int k = kbeg + s * 32 + g * 8;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (n < B && s < nks && k < D) v = ld_global_16B(p.H + (size_t)n * D + k);
-        hreg[s] = __builtin_bit_cast(bf16x8, v);
-    }
-
     // per-row epilogue constants
     float inv_tau = 1.0f;
     uint64_t seed_n = p.seed;
@@ -115,19 +105,26 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
 
     uint4 wreg[PF][NI];
 
+    // The loads of the main loop are unconditional (addresses clamped into the matrix) so that
+    // the compiler can count them and wait for exactly the stage it needs (s_waitcnt vmcnt(N))
+    // instead of draining everything in flight.  Rows past V re-read row V-1 and only feed
+    // logits the epilogue masks; the prefetch that runs past the workgroup's last row-tile
+    // re-reads rows 0..15 (cache hits); chunks past the wave's k-range are zeroed when the
+    // stage is written to LDS.
     auto row_base = [&](int rtl) -> int {
-        if (rtl >= nrt) return V;            // nothing there: every load predicated off
+        if (rtl >= nrt) return 0;
         return ((int)blockIdx.x + (rtl >> 3) * (int)gridDim.x) * kVocabTile + (rtl & 7) * 16;
     };
     auto issue_loads = [&](uint4 (&dst)[NI], int rtl, int h) {
         const int rb = row_base(rtl);
-        const int k = ld_k + h * (SK * 32);
+        int k = ld_k + h * (SK * 32);
+        k = k < kend - 8 ? k : kend - 8;
+        const uint16_t* src = p.W + k;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-            const int row = rb + j * RPI + ld_row;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (row < V && k < kend) v = ld_global_16B_stream(p.W + (size_t)row * D + k);
-            dst[j] = v;
+            int row = rb + j * RPI + ld_row;
+            row = row < V - 1 ? row : V - 1;
+            dst[j] = ld_global_16B_stream(src + (size_t)row * D);
         }
     };
 
@@ -139,8 +136,20 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     auto st_off = [&](int j) -> int { return (st_base ^ (((j * RPI) & 15) << 4)) + j * RPI * ROWB; };
     const int rd_row_off = n * ROWB;   // A-operand row of this lane is lane & 15
 
+    // start the W stream first: it does not depend on the hidden states
 #pragma unroll
     for (int h = 0; h < PF; ++h) issue_loads(wreg[h], 0, h);
+
+    // hidden slice in B-operand layout: lane (n, g) holds H[n, k .. k+8), k = kbeg + 32 s + 8 g
+    bf16x8 hreg[KPW];
+#pragma unroll
+    for (int s = 0; s < KPW; ++s) {
+        const int k = kbeg + s * 32 + g * 8;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (n < B && s < nks && k < D) v = ld_global_16B(p.H + (size_t)n * D + k);
+        hreg[s] = __builtin_bit_cast(bf16x8, v);
+    }
+
 
     for (int rtl = 0; rtl < nrt; ++rtl) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -149,9 +158,13 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
             const int set = h % PF;
             const bool active = h * SK < nks;   // wave-uniform
             if (active) {
+                const bool in_range = ld_k + h * (SK * 32) < kend;   // false only in a ragged K tail
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    *reinterpret_cast<uint4*>(stage + st_off(j)) = wreg[set][j];
+                for (int j = 0; j < NI; ++j) {
+                    uint4 v = wreg[set][j];
+                    if (!in_range) v = make_uint4(0u, 0u, 0u, 0u);
+                    *reinterpret_cast<uint4*>(stage + st_off(j)) = v;
+                }
             }
             // refill the register set with the stage PF ahead in the stream
             if (h + PF < NSTG) issue_loads(wreg[set], rtl, h + PF);

@@ -1,0 +1,233 @@
+// Stage 1 of Alg. 1 for B > 16: LDS-tiled matmul with the sampling epilogue, built so that two
+// (or more) workgroups are resident per compute unit.  While one workgroup runs its VALU-heavy
+// epilogue (Philox, logs, argmax) the other keeps the MFMA pipe and the HBM stream busy.
+//
+// Workgroup: 4 waves as WM x WN; tile = 128 vocabulary ids x BT batch rows; wave tile =
+// (128/WM) x (BT/WN).  MFMA A operand = W rows (M = vocabulary), B operand = hidden rows
+// (N = batch), v_mfma_f32_16x16x32_bf16, fp32 accumulators.
+//
+// K loop, 64 elements per step, two LDS buffers (steps k and k+1), one barrier per step.
+// Global loads run ahead of use in registers: the hidden tile two steps ahead, the W tile in
+// groups of GS steps (GS*128 contiguous bytes of every row are requested back to back, which
+// HBM serves better than isolated 128-byte pieces), two groups in flight.
+// LDS rows are 128 bytes, chunk c of row r in slot c ^ ((r & 7) ^ ((r >> 3) & 1)).
+//
+// When the batch needs several tiles (B > BT), the workgroups that share a W tile get dispatch
+// ids 8 apart: workgroups are dealt round-robin to the 8 XCDs, so they land on the same XCD at
+// the same time and the second read of the W tile is served by that XCD's L2.  W is then loaded
+// with plain loads; with a single batch tile it is streamed with non-temporal loads.
+#pragma once
+
+#include "fs_common.hpp"
+#include "fs_stage1_tiled.hpp"   // tiled_slot
+
+namespace fs {
+
+template <int BT_, int WM_, int WN_, int GS_>
+struct Tiled2Cfg {
+    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_;
+    static_assert(WM * WN == 4, "four waves per workgroup");
+    static constexpr int RB = kVocabTile / (16 * WM);   // 16-row blocks per wave
+    static constexpr int CB = BT / (16 * WN);           // 16-column blocks per wave
+    static_assert(RB >= 1 && CB >= 1, "wave tile");
+    static constexpr int kKS = 64;
+    static constexpr int kWBytes = kVocabTile * 128;
+    static constexpr int kHBytes = BT * 128;
+    static constexpr int kBufBytes = kWBytes + kHBytes;
+    static constexpr int kWLoads = kVocabTile * 8 / 256;       // 4
+    static constexpr int kHLoads = (BT * 8 + 255) / 256;       // 1..4
+    static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8; }
+};
+
+template <class Cfg, bool STREAM_W>
+__global__ void __launch_bounds__(256, 2)
+stage1_tiled2_kernel(const Stage1Params p, const int nbt)
+{
+    constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
+    constexpr int KS = Cfg::kKS;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
+    auto h_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes + Cfg::kWBytes; };
+    float2* wave_cand = reinterpret_cast<float2*>(smem + 2 * Cfg::kBufBytes);   // [WM][BT]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int n = lane & 15, g = lane >> 4;
+    const int B = p.B, D = p.D, V = p.V, T = p.T;
+
+    // dispatch id -> (vocabulary tile, batch tile): ids of one W tile are 8 apart (same XCD)
+    const int id = (int)blockIdx.x;
+    const int group = id / (8 * nbt);
+    const int rem = id - group * (8 * nbt);
+    const int tile = group * 8 + (rem & 7);
+    const int bt = rem >> 3;
+    if (tile >= T) return;                       // whole workgroup leaves: no barrier is skipped
+    const int b0 = bt * BT;
+    const int tile_row0 = tile * kVocabTile;
+
+    const int ld_chunk = tid & 7;
+    const int ld_row = tid >> 3;   // 0..31
+    uint4 wst[2][GS][Cfg::kWLoads];   // two groups of GS steps
+    uint4 hst[2][Cfg::kHLoads];       // two steps
+
+    auto fetch_w = [&](uint4 (&wr)[Cfg::kWLoads], int k0) {
+        const int k = k0 + ld_chunk * 8;
+#pragma unroll
+        for (int i = 0; i < Cfg::kWLoads; ++i) {
+            const int row = tile_row0 + ld_row + 32 * i;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (row < V && k < D) {
+                const uint16_t* src = p.W + (size_t)row * D + k;
+                v = STREAM_W ? ld_global_16B_stream(src) : ld_global_16B(src);
+            }
+            wr[i] = v;
+        }
+    };
+    auto fetch_w_group = [&](uint4 (&grp)[GS][Cfg::kWLoads], int group) {
+#pragma unroll
+        for (int s = 0; s < GS; ++s) fetch_w(grp[s], (group * GS + s) * KS);
+    };
+    auto fetch_h = [&](uint4 (&hr)[Cfg::kHLoads], int k0) {
+        const int k = k0 + ld_chunk * 8;
+#pragma unroll
+        for (int i = 0; i < Cfg::kHLoads; ++i) {
+            const int r = ld_row + 32 * i;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (r < BT && b0 + r < B && k < D) v = ld_global_16B(p.H + (size_t)(b0 + r) * D + k);
+            hr[i] = v;
+        }
+    };
+    auto park = [&](const uint4 (&wr)[Cfg::kWLoads], const uint4 (&hr)[Cfg::kHLoads], int buf) {
+#pragma unroll
+        for (int i = 0; i < Cfg::kWLoads; ++i) {
+            const int r = ld_row + 32 * i;
+            *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = wr[i];
+        }
+#pragma unroll
+        for (int i = 0; i < Cfg::kHLoads; ++i) {
+            const int r = ld_row + 32 * i;
+            if (r < BT)
+                *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = hr[i];
+        }
+    };
+
+    f32x4 acc[RB][CB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i)
+#pragma unroll
+        for (int j = 0; j < CB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int c = 4 * s + g;
+            bf16x8 a[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int r = wm * (16 * RB) + i * 16 + n;
+                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                                                      w_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+            }
+#pragma unroll
+            for (int j = 0; j < CB; ++j) {
+                const int r = wn * (16 * CB) + j * 16 + n;
+                const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                                                                h_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b, acc[i][j], 0, 0, 0);
+            }
+        }
+    };
+
+    const int nk = (D + KS - 1) / KS;
+    // prologue: W groups 0 and 1 and hidden steps 0 and 1 in flight; step 0 parked
+    // (loads past the end of K are predicated off inside the fetches)
+    fetch_w_group(wst[0], 0);
+    fetch_w_group(wst[1], 1);
+    fetch_h(hst[0], 0);
+    fetch_h(hst[1], KS);
+    park(wst[0][0], hst[0], 0);
+    fetch_h(hst[0], 2 * KS);
+    if (GS == 1) fetch_w_group(wst[0], 2);
+    __syncthreads();
+    for (int base = 0; base < nk; base += 2 * GS) {
+#pragma unroll
+        for (int u = 0; u < 2 * GS; ++u) {
+            const int t = base + u;                 // step computed now, from LDS buffer u & 1
+            if (t < nk) {
+                const int nset = ((u + 1) / GS) & 1;   // register set and slot of step t + 1
+                const int nslot = (u + 1) % GS;
+                if (t + 1 < nk) park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1);
+                fetch_h(hst[(u + 1) & 1], (t + 3) * KS);
+                if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + 2);   // set is free again
+                compute(u & 1);
+                __syncthreads();
+            }
+        }
+    }
+
+    // epilogue: acc[i][j][q] = logit of vocabulary row tile_row0 + wm*16*RB + 16 i + 4 g + q,
+    // batch row b0 + wn*16*CB + 16 j + n
+#pragma unroll
+    for (int j = 0; j < CB; ++j) {
+        const int bl = wn * (16 * CB) + j * 16 + n;   // row inside the batch tile
+        const int b = b0 + bl;
+        float best = -__builtin_inff();
+        int best_id = -1;
+        if (b < B) {
+            float inv_tau = 1.0f;
+            uint64_t seed_b = p.seed;
+            if (p.cand_val) {
+                inv_tau = 1.0f / p.tau[b];
+                if (p.row_seeds) seed_b = p.row_seeds[b];
+            }
+            const uint32_t row_word = (uint32_t)(uint64_t)(p.row_offset + b);
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const f32x4 y = acc[i][j];
+                const int v0 = tile_row0 + wm * (16 * RB) + i * 16 + 4 * g;
+                if (v0 < V) {
+                    if (p.logits) {
+                        float* dst = p.logits + (size_t)b * V + v0;
+                        if (v0 + 3 < V && (V & 3) == 0) {
+                            *reinterpret_cast<f32x4*>(dst) = y;
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                if (v0 + q < V) dst[q] = y[q];
+                        }
+                    }
+                    if (p.cand_val) {
+                        float gn[4];
+                        gumbel4(seed_b, row_word, (uint32_t)(p.vocab_offset + v0), gn);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float s = fmaf(y[q], inv_tau, gn[q]);
+                            if (v0 + q < V && s > best) { best = s; best_id = p.vocab_offset + v0 + q; }
+                        }
+                    }
+                }
+            }
+        }
+        cand_reduce_lane_groups(best, best_id);
+        if (g == 0) wave_cand[wm * BT + bl] = make_float2(best, __int_as_float(best_id));
+    }
+    __syncthreads();
+    if (p.cand_val && tid < BT && b0 + tid < B) {
+        float bv = -__builtin_inff();
+        int bi = -1;
+#pragma unroll
+        for (int w = 0; w < WM; ++w) {
+            const float2 c = wave_cand[w * BT + tid];
+            cand_merge(bv, bi, c.x, __float_as_int(c.y));
+        }
+        p.cand_val[(size_t)(b0 + tid) * T + tile] = bv;
+        p.cand_idx[(size_t)(b0 + tid) * T + tile] = bi;
+    }
+}
+
+}  // namespace fs

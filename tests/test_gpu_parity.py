@@ -45,7 +45,7 @@ def run_fused(fs, Hd, Wd, tau, seed=0, row_seeds=None, flags=0, **kw):
     return idx.cpu().numpy(), val.cpu().numpy()
 
 
-SMALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6]      # auto, split-K A/B, tiled, split-K C/D/E
+SMALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7]   # auto, split-K A/B, tiled, split-K C/D/E, tiled2
 
 
 # ----------------------------------------------------------------------------- noise
@@ -150,8 +150,8 @@ def test_small_batch_shapes_all_variants(fs, orc, shape, variant):
                                    (256, 512, 384), (300, 256, 1000), (5, 8200, 300), (2, 16384, 257)])
 def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
     B, D, V = shape
-    _small_case(fs, orc, B, D, V, 0, data_seed=70 + B)
-    _small_case(fs, orc, B, D, V, 3, data_seed=70 + B)
+    for variant in (0, 3, 7):
+        _small_case(fs, orc, B, D, V, variant, data_seed=70 + B)
 
 
 def test_split_k_variants_refuse_what_they_cannot_run(fs):
