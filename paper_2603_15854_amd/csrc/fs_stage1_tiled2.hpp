@@ -18,6 +18,8 @@
 // with plain loads; with a single batch tile it is streamed with non-temporal loads.
 #pragma once
 
+#include <type_traits>
+
 #include "fs_common.hpp"
 #include "fs_stage1_tiled.hpp"   // tiled_slot
 
@@ -35,7 +37,8 @@ struct Tiled2Cfg {
     static constexpr int kHBytes = BT * 128;
     static constexpr int kBufBytes = kWBytes + kHBytes;
     static constexpr int kWLoads = kVocabTile * 8 / 256;       // 4
-    static constexpr int kHLoads = (BT * 8 + 255) / 256;       // 1..4
+    static constexpr int kHLoads = BT * 8 / 256;               // 1..4
+    static_assert(BT % 32 == 0, "hidden tile rows are loaded 32 at a time");
     static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8; }
 };
 
@@ -73,17 +76,24 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     uint4 wst[2][GS][Cfg::kWLoads];   // two groups of GS steps
     uint4 hst[2][Cfg::kHLoads];       // two steps
 
+    // Every load of the K loop is unconditional, so the compiler can count the loads in flight and
+    // wait for exactly the step it parks (s_waitcnt vmcnt(N)) instead of draining the prefetch:
+    // rows past V (or B) re-read the last valid row and only feed outputs nobody reads (each
+    // output row/column depends on its own operand row only); a prefetch that runs past the end
+    // of K reads one fixed cache line; a chunk past D inside the last step is zeroed when parked.
+    const bool k_ragged = (D & (KS - 1)) != 0;
     auto fetch_w = [&](uint4 (&wr)[Cfg::kWLoads], int k0) {
-        const int k = k0 + ld_chunk * 8;
+        const bool over = k0 >= D;                          // uniform
+        int k = k0 + ld_chunk * 8;
+        k = k < D - 8 ? k : D - 8;
+        k = over ? ld_chunk * 8 : k;
 #pragma unroll
         for (int i = 0; i < Cfg::kWLoads; ++i) {
-            const int row = tile_row0 + ld_row + 32 * i;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (row < V && k < D) {
-                const uint16_t* src = p.W + (size_t)row * D + k;
-                v = STREAM_W ? ld_global_16B_stream(src) : ld_global_16B(src);
-            }
-            wr[i] = v;
+            int row = tile_row0 + ld_row + 32 * i;
+            row = row < V - 1 ? row : V - 1;
+            row = over ? tile_row0 : row;
+            const uint16_t* src = p.W + (size_t)row * D + k;
+            wr[i] = STREAM_W ? ld_global_16B_stream(src) : ld_global_16B(src);
         }
     };
     auto fetch_w_group = [&](uint4 (&grp)[GS][Cfg::kWLoads], int group) {
@@ -91,26 +101,33 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         for (int s = 0; s < GS; ++s) fetch_w(grp[s], (group * GS + s) * KS);
     };
     auto fetch_h = [&](uint4 (&hr)[Cfg::kHLoads], int k0) {
-        const int k = k0 + ld_chunk * 8;
+        const bool over = k0 >= D;
+        int k = k0 + ld_chunk * 8;
+        k = k < D - 8 ? k : D - 8;
+        k = over ? ld_chunk * 8 : k;
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
-            const int r = ld_row + 32 * i;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (r < BT && b0 + r < B && k < D) v = ld_global_16B(p.H + (size_t)(b0 + r) * D + k);
-            hr[i] = v;
+            int r = b0 + ld_row + 32 * i;
+            r = r < B - 1 ? r : B - 1;
+            hr[i] = ld_global_16B(p.H + (size_t)r * D + k);
         }
     };
-    auto park = [&](const uint4 (&wr)[Cfg::kWLoads], const uint4 (&hr)[Cfg::kHLoads], int buf) {
+    // park step `step` (registers -> LDS buffer buf)
+    auto park = [&](const uint4 (&wr)[Cfg::kWLoads], const uint4 (&hr)[Cfg::kHLoads], int buf, int step) {
+        const bool zero = k_ragged && (step * KS + ld_chunk * 8 >= D);   // only in the last step
 #pragma unroll
         for (int i = 0; i < Cfg::kWLoads; ++i) {
             const int r = ld_row + 32 * i;
-            *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = wr[i];
+            uint4 v = wr[i];
+            if (zero) v = make_uint4(0u, 0u, 0u, 0u);
+            *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
             const int r = ld_row + 32 * i;
-            if (r < BT)
-                *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = hr[i];
+            uint4 v = hr[i];
+            if (zero) v = make_uint4(0u, 0u, 0u, 0u);
+            *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
         }
     };
 
@@ -145,30 +162,36 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 
     const int nk = (D + KS - 1) / KS;
     // prologue: W groups 0 and 1 and hidden steps 0 and 1 in flight; step 0 parked
-    // (loads past the end of K are predicated off inside the fetches)
+    // (fetches past the end of K read one fixed cache line)
     fetch_w_group(wst[0], 0);
     fetch_w_group(wst[1], 1);
     fetch_h(hst[0], 0);
     fetch_h(hst[1], KS);
-    park(wst[0][0], hst[0], 0);
+    park(wst[0][0], hst[0], 0, 0);
     fetch_h(hst[0], 2 * KS);
     if (GS == 1) fetch_w_group(wst[0], 2);
     __syncthreads();
-    for (int base = 0; base < nk; base += 2 * GS) {
+    // One body = 2*GS steps, after which the register sets are back in their starting roles.
+    // Full bodies run without any condition (parking a step past the end only fills the LDS
+    // buffer nobody reads next); the ragged remainder uses the guarded form.
+    auto body = [&](int base, auto guarded) {
 #pragma unroll
         for (int u = 0; u < 2 * GS; ++u) {
             const int t = base + u;                 // step computed now, from LDS buffer u & 1
-            if (t < nk) {
+            if (!decltype(guarded)::value || t < nk) {
                 const int nset = ((u + 1) / GS) & 1;   // register set and slot of step t + 1
                 const int nslot = (u + 1) % GS;
-                if (t + 1 < nk) park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1);
+                park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1, t + 1);
                 fetch_h(hst[(u + 1) & 1], (t + 3) * KS);
                 if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + 2);   // set is free again
                 compute(u & 1);
                 __syncthreads();
             }
         }
-    }
+    };
+    int base = 0;
+    for (; base + 2 * GS <= nk; base += 2 * GS) body(base, std::false_type{});
+    if (base < nk) body(base, std::true_type{});
 
     // epilogue: acc[i][j][q] = logit of vocabulary row tile_row0 + wm*16*RB + 16 i + 4 g + q,
     // batch row b0 + wn*16*CB + 16 j + n
