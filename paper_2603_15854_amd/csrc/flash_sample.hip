@@ -174,6 +174,8 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 
 fs_status launch_tiled2_auto(const Stage1Params& p, hipStream_t st)
 {
+    // batch tile 32 / 64 / 128; W prefetched in groups of 4 (2 at the widest tile) K steps.
+    // Other wave arrangements and group sizes measured within 3 % of these on MI355X.
     if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>>(p, st);
     if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>>(p, st);
     return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>>(p, st);

@@ -25,9 +25,9 @@
 
 namespace fs {
 
-template <int BT_, int WM_, int WN_, int GS_>
+template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2>
 struct Tiled2Cfg {
-    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_;
+    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_, OCC = OCC_;
     static_assert(WM * WN == 4, "four waves per workgroup");
     static constexpr int RB = kVocabTile / (16 * WM);   // 16-row blocks per wave
     static constexpr int CB = BT / (16 * WN);           // 16-column blocks per wave
@@ -43,7 +43,7 @@ struct Tiled2Cfg {
 };
 
 template <class Cfg, bool STREAM_W>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;

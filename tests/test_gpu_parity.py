@@ -264,6 +264,53 @@ def test_logits_tap_and_unfused_path_small(fs, orc):
         assert judge(orc, H, W, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, seed=6).ok
 
 
+def test_gpu_samples_follow_softmax_chi_square(fs, orc):
+    # the paper's kernel-level check (V = 512, 10^4 draws, chi-square), run on the GPU path itself:
+    # many rows with the same hidden state differ only in the row word of the noise counter
+    from scipy import stats
+    D, V, tau = 64, 512, 0.9
+    H1, W = wl.make_small(D=D, V=V, B=1, data_seed=95, w_row_scale=2.0)
+    y = orc.logits(H1, W)[0]
+    z = y / tau
+    p = np.exp(z - z.max())
+    p /= p.sum()
+    Wd = to_device_bf16(W)
+
+    def chi2_ok(counts, n):
+        order = np.argsort(p)
+        ce, cc, cells_e, cells_c = 0.0, 0, [], []
+        for i in order:
+            ce += p[i] * n
+            cc += counts[i]
+            if ce >= 5:
+                cells_e.append(ce); cells_c.append(cc); ce, cc = 0.0, 0
+        cells_e[-1] += ce; cells_c[-1] += cc
+        e, c = np.array(cells_e), np.array(cells_c)
+        return ((c - e) ** 2 / e).sum(), stats.chi2.ppf(0.999, len(e) - 1)
+
+    # large batch through the tiled kernel
+    n = 40_000
+    Hn = np.repeat(H1, n, axis=0)
+    gi, _ = run_fused(fs, to_device_bf16(Hn), Wd, np.full(n, tau, np.float32), seed=2024)
+    counts = np.bincount(gi, minlength=V)
+    chi2, crit = chi2_ok(counts, n)
+    assert chi2 < crit, (chi2, crit)
+    # the same rows drawn by the oracle must give the same tokens (spot check of 64 rows)
+    ref = orc.sample(np.ascontiguousarray(Hn[:64]), W, np.full(64, tau, np.float32), seed=2024)
+    assert (ref["idx"] == gi[:64]).sum() >= 63
+    # small batches through the split-K kernel, rows numbered by row_offset
+    H16 = to_device_bf16(np.repeat(H1, 16, axis=0))
+    tau16 = dev_f32(np.full(16, tau))
+    draws = []
+    for c in range(400):
+        idx, _ = fs.flash_sample_ex(H16, Wd, tau16, seed=7, row_offset=16 * c)
+        draws.append(idx)
+    torch.cuda.synchronize()
+    draws = torch.cat(draws).cpu().numpy()
+    chi2, crit = chi2_ok(np.bincount(draws, minlength=V), draws.size)
+    assert chi2 < crit, (chi2, crit)
+
+
 # ----------------------------------------------------------------------------- full-size configs
 
 def _subset_rows(B, k=12):
