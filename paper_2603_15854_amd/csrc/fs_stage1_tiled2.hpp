@@ -71,6 +71,17 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int b0 = bt * BT;
     const int tile_row0 = tile * kVocabTile;
 
+    // K steps of this tile, visited in rotated order: workgroups that run at the same time start
+    // at different offsets along K (eight phases), so that at any instant the rows being read are
+    // spread over column ranges, hence over HBM channels, instead of all sitting at the same
+    // offset of 8 KB-strided rows.  Logical step t is K step kmap(t); t >= nk stays out of range.
+    const int nk = (D + KS - 1) / KS;
+    const int kstart = (int)(((unsigned)tile + ((unsigned)tile >> 3)) & 7u) * (nk >> 3);
+    auto kmap = [&](int t) -> int {
+        const int a = t + kstart;
+        return t >= nk ? t : (a >= nk ? a - nk : a);
+    };
+
     const int ld_chunk = tid & 7;
     const int ld_row = tid >> 3;   // 0..31
     uint4 wst[2][GS][Cfg::kWLoads];   // two groups of GS steps
@@ -98,7 +109,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     };
     auto fetch_w_group = [&](uint4 (&grp)[GS][Cfg::kWLoads], int group) {
 #pragma unroll
-        for (int s = 0; s < GS; ++s) fetch_w(grp[s], (group * GS + s) * KS);
+        for (int s = 0; s < GS; ++s) fetch_w(grp[s], kmap(group * GS + s) * KS);
     };
     auto fetch_h = [&](uint4 (&hr)[Cfg::kHLoads], int k0) {
         const bool over = k0 >= D;
@@ -112,7 +123,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             hr[i] = ld_global_16B(p.H + (size_t)r * D + k);
         }
     };
-    // park step `step` (registers -> LDS buffer buf)
+    // park K step `step` (registers -> LDS buffer buf)
     auto park = [&](const uint4 (&wr)[Cfg::kWLoads], const uint4 (&hr)[Cfg::kHLoads], int buf, int step) {
         const bool zero = k_ragged && (step * KS + ld_chunk * 8 >= D);   // only in the last step
 #pragma unroll
@@ -160,15 +171,14 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
     };
 
-    const int nk = (D + KS - 1) / KS;
     // prologue: W groups 0 and 1 and hidden steps 0 and 1 in flight; step 0 parked
     // (fetches past the end of K read one fixed cache line)
     fetch_w_group(wst[0], 0);
     fetch_w_group(wst[1], 1);
-    fetch_h(hst[0], 0);
-    fetch_h(hst[1], KS);
-    park(wst[0][0], hst[0], 0, 0);
-    fetch_h(hst[0], 2 * KS);
+    fetch_h(hst[0], kmap(0) * KS);
+    fetch_h(hst[1], kmap(1) * KS);
+    park(wst[0][0], hst[0], 0, kmap(0));
+    fetch_h(hst[0], kmap(2) * KS);
     if (GS == 1) fetch_w_group(wst[0], 2);
     __syncthreads();
     // One body = 2*GS steps, after which the register sets are back in their starting roles.
@@ -181,8 +191,8 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             if (!decltype(guarded)::value || t < nk) {
                 const int nset = ((u + 1) / GS) & 1;   // register set and slot of step t + 1
                 const int nslot = (u + 1) % GS;
-                park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1, t + 1);
-                fetch_h(hst[(u + 1) & 1], (t + 3) * KS);
+                park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1, kmap(t + 1));
+                fetch_h(hst[(u + 1) & 1], kmap(t + 3) * KS);
                 if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + 2);   // set is free again
                 compute(u & 1);
                 __syncthreads();
