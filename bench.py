@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
+MEASURED_TRAFFIC_C2_B16 = int((514402.0 * 2.0 + 1011.7) * 1024)   # bytes per stage-1 launch (rocprofv3)
 
 
 def main() -> int:
@@ -129,7 +130,10 @@ def main() -> int:
         "frac": round(bytes_stage1 / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "us_per_launch": round(ms1 * 1e3, 2),
         "algorithmic_bytes_per_launch": bytes_stage1,
-        "traffic": None,
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.0 KiB per count) + WRITE_SIZE
+        # (x 1.0 KiB per count), both scaled by a plain copy kernel of known size; measured for
+        # this launch configuration only (profiles/stage1_splitk_C2_B16_hbm_traffic_pmc.txt)
+        "traffic": MEASURED_TRAFFIC_C2_B16 if (w.name == "C2" and B == 16 and args.variant == 0) else None,
     }
 
     out = {
