@@ -40,11 +40,12 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     constexpr uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
-        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
-        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
-        const uint32_t t0 = hi1 ^ c1 ^ k0;
-        const uint32_t t2 = hi0 ^ c3 ^ k1;
-        c0 = t0; c1 = lo1; c2 = t2; c3 = lo0;
+        // one 32x32->64 multiply per product (v_mad_u64_u32) instead of separate high and low halves
+        const uint64_t p0 = (uint64_t)M0 * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)M1 * (uint64_t)c2;
+        const uint32_t t0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t t2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c0 = t0; c1 = (uint32_t)p1; c2 = t2; c3 = (uint32_t)p0;
         k0 += W0; k1 += W1;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
