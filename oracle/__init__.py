@@ -83,6 +83,21 @@ def lib():
     L.fso_gumbel_from_words.restype = None
     L.fso_random_words.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, _u32p]
     L.fso_random_words.restype = None
+    L.fso_transform_row.argtypes = [_f64p, C.c_int64, C.c_double, C.c_void_p, C.c_void_p, _f64p]
+    L.fso_transform_row.restype = None
+    L.fso_gumbel_max_transformed.argtypes = [_f64p, C.c_int64, C.c_uint64, C.c_int64, C.c_int64,
+                                             C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                             C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    L.fso_gumbel_max_transformed.restype = None
+    L.fso_log_sum_exp.argtypes = [_f64p, C.c_int64]
+    L.fso_log_sum_exp.restype = C.c_double
+    L.fso_sample_full.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                                  C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                  C.c_int64, _i32p, _f32p, _f64p, _f64p, _i64p, _f64p]
+    L.fso_sample_full.restype = C.c_int
+    L.fso_score_at_full.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                    C.c_uint64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]
+    L.fso_score_at_full.restype = C.c_double
     L.fso_num_threads.argtypes = []
     L.fso_num_threads.restype = C.c_int
     _lib = L
@@ -219,6 +234,76 @@ def softmax(y, tau: float = 1.0):
     lse = C.c_double()
     lib().fso_softmax(y, y.size, float(tau), p, C.byref(lse))
     return p, lse.value
+
+
+def pack_allowed(allowed_bool: np.ndarray) -> np.ndarray:
+    """Pack a boolean array [..., V] (True = allowed) into 32-bit words [..., ceil(V/32)],
+    bit i%32 of word i/32.  Pure data layout, no method arithmetic."""
+    a = np.asarray(allowed_bool, dtype=bool)
+    V = a.shape[-1]
+    nw = (V + 31) // 32
+    pad = np.zeros(a.shape[:-1] + (nw * 32,), dtype=bool)
+    pad[..., :V] = a
+    bits = pad.reshape(a.shape[:-1] + (nw, 32)).astype(np.uint64)
+    words = (bits << np.arange(32, dtype=np.uint64)).sum(axis=-1)
+    return np.ascontiguousarray(words.astype(np.uint32))
+
+
+def transform_row(y, tau: float, bias=None, allowed_words=None) -> np.ndarray:
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    z = np.empty_like(y)
+    b, bp = _opt_ptr(bias, np.float32)
+    a, ap = _opt_ptr(allowed_words, np.uint32)
+    lib().fso_transform_row(y, y.size, float(tau), bp, ap, z)
+    return z
+
+
+def gumbel_max_transformed(z, seed: int, row: int, vocab_offset: int = 0):
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    i1, i2 = C.c_int64(), C.c_int64()
+    m1, m2 = C.c_double(), C.c_double()
+    lib().fso_gumbel_max_transformed(z, z.size, seed, row, vocab_offset, C.byref(i1), C.byref(m1),
+                                     C.byref(i2), C.byref(m2))
+    return i1.value, m1.value, i2.value, m2.value
+
+
+def log_sum_exp(z) -> float:
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    return float(lib().fso_log_sum_exp(z, z.size))
+
+
+def sample_full(H, W, tau, seed: int = 0, row_seeds=None, row_offset: int = 0, row_ids=None,
+                vocab_offset: int = 0, bias=None, allowed_words=None):
+    """Full transform + log-normaliser.  allowed_words: None, [nw] (shared) or [B, nw] uint32."""
+    B, D = H.shape
+    V = W.shape[0]
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    ri, ri_p = _opt_ptr(row_ids, np.int64)
+    bb, bb_p = _opt_ptr(bias, np.float32)
+    aw, aw_p = _opt_ptr(allowed_words, np.uint32)
+    stride = 0
+    if aw is not None and aw.ndim == 2:
+        assert aw.shape[0] == B
+        stride = aw.shape[1]
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    lse = np.empty(B, dtype=np.float64)
+    top1 = np.empty(B, dtype=np.float64)
+    idx2 = np.empty(B, dtype=np.int64)
+    top2 = np.empty(B, dtype=np.float64)
+    nt = lib().fso_sample_full(H, W, B, D, V, tau, seed, rs_p, row_offset, ri_p, vocab_offset, bb_p, aw_p,
+                               stride, out_idx, out_val, lse, top1, idx2, top2)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, lse=lse, top1=top1, idx2=idx2, top2=top2, threads=nt)
+
+
+def score_at_full(H, W, b_local, i_local, tau, seed, row, vocab_id, bias=None, allowed_row=None) -> float:
+    bb, bb_p = _opt_ptr(bias, np.float32)
+    ar, ar_p = _opt_ptr(allowed_row, np.uint32)
+    return float(lib().fso_score_at_full(H, W, H.shape[1], b_local, i_local, float(tau), seed, row,
+                                         vocab_id, bb_p, ar_p))
 
 
 def num_threads() -> int:

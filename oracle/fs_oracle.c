@@ -29,6 +29,9 @@
  * demonstrate the Lemma "Max over vocabulary tiles" on the oracle itself and to check the
  * GPU's candidate buffer.
  *
+ * The full transform (additive bias, temperature, -inf mask) and the log-normaliser
+ * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below).
+ *
  * NaN scores never win (the strict > comparison is false for NaN); a row with no
  * score > -inf returns idx = -1, val = -inf.
  */
@@ -246,6 +249,109 @@ int fso_sample_tiled(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D,
     }
     free(Y);
     return nthreads;
+}
+
+/* ------------------------------------------------------------------ full transform + log-normaliser */
+/*
+ * Transformed logits of one row (Section "Background", Notation: "deterministic operations such as
+ * additive bias, temperature scaling, or masking"; Alg. 1, "transform"; Section "Top-k, Nucleus
+ * Sampling, and Masking": forbidden ids are set to -inf before perturbation):
+ *      z_i = (y_i + bias_i) / tau            if id i is allowed
+ *      z_i = -inf                             if id i is masked out
+ * bias is fp32 [V] or NULL (indexed by the local id i); allowed is a bit array of V bits packed in
+ * 32-bit words (bit i%32 of word i/32 set = allowed) or NULL (everything allowed).
+ * The order bias -> temperature -> mask is this build's reading; the paper does not fix it.
+ */
+void fso_transform_row(const double* y, int64_t V, double tau, const float* bias,
+                       const uint32_t* allowed, double* z)
+{
+    for (int64_t i = 0; i < V; ++i) {
+        double v = y[i];
+        if (bias) v += (double)bias[i];
+        v /= tau;
+        if (allowed && !((allowed[i >> 5] >> (i & 31)) & 1u)) v = -INFINITY;
+        z[i] = v;
+    }
+}
+
+/* Streaming Gumbel-max over already transformed logits z (same noise, same tie rule as
+ * fso_gumbel_max_row; -inf entries can never win because the update is a strict >). */
+void fso_gumbel_max_transformed(const double* z, int64_t V, uint64_t seed, int64_t row,
+                                int64_t vocab_offset, int64_t* best_idx, double* best_val,
+                                int64_t* second_idx, double* second_val)
+{
+    double m = -INFINITY, m2 = -INFINITY;
+    int64_t im = -1, im2 = -1;
+    for (int64_t i = 0; i < V; ++i) {
+        int64_t vid = vocab_offset + i;
+        double s = z[i] + fso_gumbel(seed, row, vid);
+        if (s > m) { m2 = m; im2 = im; m = s; im = vid; }
+        else if (s > m2) { m2 = s; im2 = vid; }
+    }
+    *best_idx = im; *best_val = m;
+    if (second_idx) *second_idx = im2;
+    if (second_val) *second_val = m2;
+}
+
+/* log Z = log sum_i exp(z_i) (appendix "Returning Log-Normalizers or Max Values"), max-shifted,
+ * fp64; -inf when no entry is finite. */
+double fso_log_sum_exp(const double* z, int64_t V)
+{
+    double zmax = -INFINITY;
+    for (int64_t i = 0; i < V; ++i) if (z[i] > zmax) zmax = z[i];
+    if (!(zmax > -INFINITY)) return -INFINITY;
+    if (zmax == INFINITY) return INFINITY;
+    double sum = 0.0;
+    for (int64_t i = 0; i < V; ++i) sum += exp(z[i] - zmax);
+    return zmax + log(sum);
+}
+
+/*
+ * Full path with the whole transform and the log-normaliser:
+ *   i*_b ~ Cat(softmax(z_b)), z_b = transform(H_b W^T), out_lse[b] = log sum_i exp(z_{b,i}).
+ * allowed: NULL, or bit rows of `mask_stride_words` 32-bit words per batch row
+ * (mask_stride_words == 0: one row of bits shared by every batch row).
+ */
+int fso_sample_full(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V,
+                    const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                    const int64_t* row_ids, int64_t vocab_offset, const float* bias,
+                    const uint32_t* allowed, int64_t mask_stride_words, int32_t* out_idx,
+                    float* out_val, double* out_lse, double* top1_val, int64_t* top2_idx,
+                    double* top2_val)
+{
+    if (B <= 0 || V <= 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits(H, W, B, D, V, Y);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        double* z = Y + b * V;   /* transformed in place */
+        const uint32_t* arow = allowed ? allowed + (size_t)b * (size_t)mask_stride_words : NULL;
+        fso_transform_row(z, V, (double)tau[b], bias, arow, z);
+        int64_t i1, i2;
+        double m1, m2;
+        fso_gumbel_max_transformed(z, V, row_seed(seed, row_seeds, b), row_id(row_ids, row_offset, b),
+                                   vocab_offset, &i1, &m1, &i2, &m2);
+        out_idx[b] = (int32_t)i1;
+        if (out_val) out_val[b] = (float)m1;
+        if (out_lse) out_lse[b] = fso_log_sum_exp(z, V);
+        if (top1_val) top1_val[b] = m1;
+        if (top2_idx) top2_idx[b] = i2;
+        if (top2_val) top2_val[b] = m2;
+    }
+    free(Y);
+    return nthreads;
+}
+
+/* Transformed score of a single (row, id): z + g, or -inf if the id is masked. */
+double fso_score_at_full(const uint16_t* H, const uint16_t* W, int64_t D, int64_t b_local,
+                         int64_t i_local, double tau, uint64_t seed, int64_t row, int64_t vocab_id,
+                         const float* bias, const uint32_t* allowed_row)
+{
+    double y = fso_logit(H, W, D, b_local, i_local), z;
+    fso_transform_row(&y, 1, tau, bias ? bias + i_local : NULL, NULL, &z);
+    if (allowed_row && !((allowed_row[i_local >> 5] >> (i_local & 31)) & 1u)) return -INFINITY;
+    return z + fso_gumbel(seed, row, vocab_id);
 }
 
 /* ------------------------------------------------------------------ helpers for the pins */
