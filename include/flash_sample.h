@@ -116,6 +116,33 @@ fs_status flash_sample_ex(const void* hidden, const void* W, int B, int D, int V
                           void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
 /*
+ * The same draw with the whole deterministic transform of the paper's notation ("additive bias,
+ * temperature scaling, or masking", Section "Background"; Alg. 1, "transform"; Section "Top-k,
+ * Nucleus Sampling, and Masking": forbidden ids are set to -inf before perturbation) and,
+ * optionally, the log-normaliser (appendix "Returning Log-Normalizers or Max Values"):
+ *      z_{b,i} = (y_{b,i} + bias_i) / temperature_b     if id i is allowed for row b, else -inf
+ *      i*_b ~ Cat(softmax(z_b)),   out_val[b] = max_i (z_{b,i} + g_{b,i}),
+ *      out_lse[b] = log sum_i exp(z_{b,i})
+ *   bias               NULL, or fp32 [V] (indexed by the local id i), 16-byte aligned
+ *   allowed            NULL (all allowed), or bit rows: bit (i % 32) of 32-bit word (i / 32) set
+ *                      means local id i may be sampled; padding bits past V are ignored
+ *   mask_stride_words  32-bit words between the bit rows of consecutive batch rows
+ *                      (>= ceil(V/32)), or 0: one bit row shared by every batch row
+ *   out_lse            NULL, or fp32 [B]
+ *   workspace          at least flash_sample_full_workspace_bytes(B, V) bytes, 256-byte aligned
+ *   flags              FS_FLAG_NONE (the automatic kernel choice only)
+ * A row whose ids are all masked returns idx = -1, val = -inf, lse = -inf.  The order
+ * bias -> temperature -> mask is this library's reading; the paper does not fix it.
+ */
+size_t flash_sample_full_workspace_bytes(int B, int V);
+fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int V,
+                            const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                            int64_t row_offset, int32_t vocab_offset,
+                            const float* bias, const uint32_t* allowed, int64_t mask_stride_words,
+                            int32_t* out_idx, float* out_val, float* out_lse,
+                            void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
  * Stage 1 of Alg. 1 alone: writes the candidate buffer
  *   cand_val [B, T] fp32, cand_idx [B, T] int32 (global vocabulary ids), T = flash_sample_num_tiles(V).
  * If `logits` is not NULL the kernel also stores the raw logits y = hidden W^T as fp32 [B, V]

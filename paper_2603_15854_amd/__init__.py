@@ -28,6 +28,7 @@ FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E, FS_VARIANT_TILED2
 # every symbol include/flash_sample.h declares
 EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
+    "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
     "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
     "flash_sample_stream_probe",
@@ -71,6 +72,11 @@ def lib():
     L.flash_sample.restype = i32
     L.flash_sample_ex.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, sz, vp, u32]
     L.flash_sample_ex.restype = i32
+    L.flash_sample_full_workspace_bytes.argtypes = [i32, i32]
+    L.flash_sample_full_workspace_bytes.restype = sz
+    L.flash_sample_full.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
+                                    vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_full.restype = i32
     L.flash_sample_stage1.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, u32]
     L.flash_sample_stage1.restype = i32
     L.flash_sample_stage2.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -180,6 +186,35 @@ def flash_sample_ex(hidden, W, temperature, seed: int = 0, row_seeds=None, row_o
                                _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_ex")
     return out_idx, out_val
+
+
+def flash_sample_full_workspace_bytes(B: int, V: int) -> int:
+    return int(lib().flash_sample_full_workspace_bytes(int(B), int(V)))
+
+
+def flash_sample_full(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                      vocab_offset: int = 0, bias=None, allowed=None, want_lse: bool = True,
+                      out_idx=None, out_val=None, out_lse=None, workspace=None, stream=None, flags: int = 0):
+    """Draw with bias / allowed-id mask / log-normaliser.  `allowed` is an int32 tensor of bit words,
+    [ceil(V/32)] (shared by all rows) or [B, >= ceil(V/32)].  Returns (out_idx, out_val, out_lse)."""
+    import torch
+    B, D, V = _shapes(hidden, W)
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    if want_lse and out_lse is None:
+        out_lse = torch.empty(B, dtype=torch.float32, device=hidden.device)
+    stride = 0
+    if allowed is not None and allowed.dim() == 2:
+        stride = allowed.shape[1]
+    need = flash_sample_full_workspace_bytes(B, V)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    st = lib().flash_sample_full(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                                 _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(bias),
+                                 _ptr(allowed), int(stride), _ptr(out_idx), _ptr(out_val), _ptr(out_lse),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream_ptr(stream), int(flags))
+    _check(st, "flash_sample_full")
+    return out_idx, out_val, out_lse
 
 
 def flash_sample_stage1(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,

@@ -96,12 +96,12 @@ Workspace carve(void* ws, int B, int V)
 // ---------------------------------------------------------------------------------------------
 // stage-1 launchers
 
-template <class Cfg>
+template <class Cfg, bool FULL = false>
 fs_status launch_splitk(const Stage1Params& p, int kpw, int nw, int wgs_per_cu_override, hipStream_t st)
 {
     const size_t lds = Cfg::lds_bytes(nw);
     if (nw > Cfg::kMaxWaves || lds > kLdsPerCU) return FS_ERR_UNSUPPORTED;
-    auto kernel = stage1_splitk_kernel<Cfg>;
+    auto kernel = stage1_splitk_kernel<Cfg, FULL>;
     static bool attr_set = false;
     if (!attr_set) {
         if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
@@ -151,7 +151,7 @@ fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
     return launch_tiled<16>(p, st);
 }
 
-template <class Cfg>
+template <class Cfg, bool FULL = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
@@ -159,15 +159,15 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     if (grid > 0x7FFFFFFFll) return FS_ERR_SHAPE;
     static bool attr_set = false;
     if (!attr_set) {
-        if (allow_lds(stage1_tiled2_kernel<Cfg, true>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        if (allow_lds(stage1_tiled2_kernel<Cfg, false>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
         attr_set = true;
     }
     if (nbt == 1)
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true>), dim3((unsigned)grid), dim3(256),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL>), dim3((unsigned)grid), dim3(256),
                            Cfg::lds_bytes(), st, p, nbt);
     else
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false>), dim3((unsigned)grid), dim3(256),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL>), dim3((unsigned)grid), dim3(256),
                            Cfg::lds_bytes(), st, p, nbt);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
@@ -179,6 +179,24 @@ fs_status launch_tiled2_auto(const Stage1Params& p, hipStream_t st)
     if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>>(p, st);
     if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>>(p, st);
     return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>>(p, st);
+}
+
+// stage 1 with the full transform / log-normaliser epilogue: the default kernels only
+fs_status launch_stage1_full(const Stage1Params& p, uint32_t flags, hipStream_t st)
+{
+    if (flags != FS_FLAG_NONE) return FS_ERR_UNSUPPORTED;
+    const int ksteps = (p.D + 31) / 32;
+    if (p.B <= 16 && ksteps <= 64 * 4) {
+        if (ksteps > 32 * 4) {
+            const int nw = (ksteps + 63) / 64;
+            return launch_splitk<SplitKCfg<64, 16, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
+        }
+        const int nw = (ksteps + 31) / 32;
+        return launch_splitk<SplitKCfg<32, 8, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
+    }
+    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, true>(p, st);
+    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>, true>(p, st);
+    return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>, true>(p, st);
 }
 
 fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
@@ -283,6 +301,7 @@ fs_status flash_sample_stage1(const void* hidden, const void* W, int B, int D, i
     p.seed = seed; p.row_seeds = row_seeds;
     p.row_offset = row_offset; p.vocab_offset = vocab_offset;
     p.cand_val = cand_val; p.cand_idx = cand_idx; p.logits = logits;
+    p.bias = nullptr; p.allowed = nullptr; p.mask_stride = 0; p.lse_max = nullptr; p.lse_sum = nullptr;
     return launch_stage1(p, flags, static_cast<hipStream_t>(stream));
 }
 
@@ -345,6 +364,47 @@ fs_status flash_sample(const void* hidden, const void* W, int B, int D, int V,
     }
     return flash_sample_ex(hidden, W, B, D, V, temperature, seed, nullptr, 0, 0, out_idx, out_val,
                            ws, need, nullptr, FS_FLAG_NONE);
+}
+
+size_t flash_sample_full_workspace_bytes(int B, int V) { return 2 * workspace_bytes(B, V); }
+
+fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int V,
+                            const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                            int64_t row_offset, int32_t vocab_offset,
+                            const float* bias, const uint32_t* allowed, int64_t mask_stride_words,
+                            int32_t* out_idx, float* out_val, float* out_lse,
+                            void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK || B == 0) return s;
+    if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (allowed && mask_stride_words != 0 && mask_stride_words < (int64_t)((V + 31) / 32)) return FS_ERR_SHAPE;
+    if (mask_stride_words < 0) return FS_ERR_SHAPE;
+    if (!aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(out_lse, 4) || !aligned(temperature, 4) ||
+        !aligned(row_seeds, 8) || !aligned(bias, 16) || !aligned(allowed, 4))
+        return FS_ERR_ALIGN;
+    const size_t half = workspace_bytes(B, V);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < 2 * half) return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);
+    const Workspace ws2 = carve(static_cast<unsigned char*>(workspace) + half, B, V);
+    Stage1Params p;
+    p.H = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W);
+    p.B = B; p.D = D; p.V = V; p.T = num_tiles(V);
+    p.tau = temperature;
+    p.seed = seed; p.row_seeds = row_seeds;
+    p.row_offset = row_offset; p.vocab_offset = vocab_offset;
+    p.cand_val = ws.cand_val; p.cand_idx = ws.cand_idx; p.logits = nullptr;
+    p.bias = bias; p.allowed = allowed; p.mask_stride = mask_stride_words;
+    p.lse_max = out_lse ? ws2.cand_val : nullptr;
+    p.lse_sum = out_lse ? reinterpret_cast<float*>(ws2.cand_idx) : nullptr;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = launch_stage1_full(p, flags, st);
+    if (s != FS_OK) return s;
+    s = launch_stage2(ws.cand_val, ws.cand_idx, B, p.T, out_idx, out_val, st);
+    if (s != FS_OK || !out_lse) return s;
+    hipLaunchKernelGGL(lse_reduce_kernel, dim3(B), dim3(256), 0, st, p.lse_max, p.lse_sum, p.T, out_lse);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
 fs_status flash_lm_head_logits(const void* hidden, const void* W, int B, int D, int V,

@@ -48,6 +48,35 @@ stage2_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ ca
     }
 }
 
+// Log-normaliser finish: merges the per-tile online log-sum-exp states (max, sum) of a row into
+// out_lse[b] = log sum_i exp(z_i) (appendix "Returning Log-Normalizers or Max Values").
+__global__ void __launch_bounds__(256)
+lse_reduce_kernel(const float* __restrict__ lse_max, const float* __restrict__ lse_sum, int T,
+                  float* __restrict__ out_lse)
+{
+    __shared__ float sm[4];
+    __shared__ float ss[4];
+    const int b = blockIdx.x;
+    const float* pm = lse_max + (size_t)b * T;
+    const float* ps = lse_sum + (size_t)b * T;
+    float m = -__builtin_inff(), s = 0.0f;
+    for (int t = threadIdx.x; t < T; t += 256) lse_merge(m, s, pm[t], ps[t]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float om = __shfl_xor(m, off, kWave);
+        const float os = __shfl_xor(s, off, kWave);
+        lse_merge(m, s, om, os);
+    }
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; ss[threadIdx.x >> 6] = s; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) lse_merge(m, s, sm[w], ss[w]);
+        constexpr float kLn2 = 0.6931471805599453f;
+        out_lse[b] = s > 0.0f ? m + kLn2 * __builtin_amdgcn_logf(s) : -__builtin_inff();
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Streaming Gumbel-max over materialised fp32 logits (appendix Alg. "Gumbel-Max sampling
 // (standalone logits)").  Workgroup (t, b) scans vocabulary ids [1024 t, 1024 t + 1024) of row b,

@@ -27,6 +27,12 @@ struct Stage1Params {
     float* cand_val;          // [B, T]  (nullptr: no sampling epilogue)
     int32_t* cand_idx;        // [B, T]
     float* logits;            // [B, V] fp32 or nullptr (logits-store flag)
+    // full transform and log-normaliser (kernels instantiated with FULL = true only)
+    const float* bias;        // [V] fp32 or nullptr: z = (y + bias) / tau
+    const uint32_t* allowed;  // bit rows (bit i%32 of word i/32 set = id i allowed) or nullptr
+    int64_t mask_stride;      // 32-bit words per batch row of `allowed`; 0 = one row for all
+    float* lse_max;           // [B, T] running maximum of z per (row, tile), or nullptr
+    float* lse_sum;           // [B, T] sum of exp(z - max) per (row, tile)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -121,6 +127,101 @@ __device__ __forceinline__ void cand_reduce_lane_groups(float& v, int& i)
         const float ov = __shfl_xor(v, off, kWave);
         const int oi = __shfl_xor(i, off, kWave);
         cand_merge(v, i, ov, oi);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Online log-sum-exp state (m, s): log sum exp = m + log s.  Empty state is (-inf, 0).
+__device__ __forceinline__ float exp_diff(float a, float m)   // exp(a - m), 0 when a = -inf
+{
+    constexpr float kLog2e = 1.4426950408889634f;
+    return a == -__builtin_inff() ? 0.0f : __builtin_amdgcn_exp2f((a - m) * kLog2e);
+}
+__device__ __forceinline__ void lse_merge(float& m, float& s, float om, float os)
+{
+    const float nm = fmaxf(m, om);
+    s = s * exp_diff(m, nm) + os * exp_diff(om, nm);
+    m = nm;
+}
+__device__ __forceinline__ void lse_reduce_lane_groups(float& m, float& s)
+{
+#pragma unroll
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float om = __shfl_xor(m, off, kWave);
+        const float os = __shfl_xor(s, off, kWave);
+        lse_merge(m, s, om, os);
+    }
+}
+
+// Per-row constants of the sampling epilogue.
+struct RowEpi {
+    float inv_tau;
+    uint64_t seed;
+    uint32_t row_word;
+    const uint32_t* allowed_row;   // FULL only
+};
+
+template <bool FULL>
+__device__ __forceinline__ RowEpi make_row_epi(const Stage1Params& p, int b)
+{
+    RowEpi r;
+    r.inv_tau = 1.0f / p.tau[b];
+    r.seed = p.row_seeds ? p.row_seeds[b] : p.seed;
+    r.row_word = (uint32_t)(uint64_t)(p.row_offset + b);
+    r.allowed_row = nullptr;
+    if constexpr (FULL) {
+        if (p.allowed) r.allowed_row = p.allowed + (size_t)b * (size_t)p.mask_stride;
+    }
+    return r;
+}
+
+// Epilogue of Alg. 1 for the four consecutive vocabulary rows v0 .. v0+3 (local ids, v0 % 4 == 0)
+// a lane holds for one batch row: transform, noise, perturbed score, running argmax; with FULL
+// also additive bias, the allowed-id mask (-inf before perturbation) and the online
+// log-sum-exp of the transformed logits.
+template <bool FULL>
+__device__ __forceinline__ void epilogue_quad(const Stage1Params& p, const RowEpi& r, const f32x4 y,
+                                              int v0, int V, float& best, int& best_id,
+                                              float& lmax, float& lsum)
+{
+    float gn[4];
+    gumbel4(r.seed, r.row_word, (uint32_t)(p.vocab_offset + v0), gn);
+    if constexpr (!FULL) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float s = fmaf(y[j], r.inv_tau, gn[j]);
+            if (v0 + j < V && s > best) { best = s; best_id = p.vocab_offset + v0 + j; }
+        }
+    } else {
+        float bq[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.bias) {
+            if (v0 + 3 < V) {
+                const f32x4 q = *reinterpret_cast<const f32x4*>(p.bias + v0);
+                bq[0] = q[0]; bq[1] = q[1]; bq[2] = q[2]; bq[3] = q[3];
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (v0 + j < V) bq[j] = p.bias[v0 + j];
+            }
+        }
+        uint32_t bits = 0xFu;
+        if (r.allowed_row) bits = r.allowed_row[v0 >> 5] >> (v0 & 31);
+        float z[4];
+        float zmax = -__builtin_inff();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            z[j] = (y[j] + bq[j]) * r.inv_tau;
+            if (!((bits >> j) & 1u) || v0 + j >= V) z[j] = -__builtin_inff();
+            zmax = fmaxf(zmax, z[j]);          // fmaxf ignores NaN
+            const float s = z[j] + gn[j];
+            if (s > best) { best = s; best_id = p.vocab_offset + v0 + j; }
+        }
+        if (p.lse_max && zmax > -__builtin_inff()) {
+            float m4 = zmax, s4 = 0.0f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s4 += exp_diff(z[j], m4);
+            lse_merge(lmax, lsum, m4, s4);
+        }
     }
 }
 

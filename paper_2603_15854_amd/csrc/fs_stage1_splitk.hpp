@@ -47,11 +47,11 @@ struct SplitKCfg {
     // LDS bytes for nw waves: stages + partial tiles [8][nw][64] float4 + wave candidates.
     static constexpr size_t lds_bytes(int nw)
     {
-        return (size_t)nw * kStageBytes + (size_t)8 * nw * 1024 + (size_t)nw * 16 * 8;
+        return (size_t)nw * kStageBytes + (size_t)8 * nw * 1024 + (size_t)nw * 16 * 8 * 2;
     }
 };
 
-template <class Cfg>
+template <class Cfg, bool FULL = false>
 __global__ void __launch_bounds__(Cfg::kMaxWaves * kWave)
 stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
 {
@@ -83,15 +83,11 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     f32x4* partial = reinterpret_cast<f32x4*>(smem + (size_t)nw * Cfg::kStageBytes);
     float2* wave_cand = reinterpret_cast<float2*>(smem + (size_t)nw * Cfg::kStageBytes +
                                                   (size_t)8 * nw * 1024);
+    float2* wave_lse = wave_cand + nw * 16;
 
-    // per-row epilogue constants
-    float inv_tau = 1.0f;
-    uint64_t seed_n = p.seed;
-    if (n < B && p.cand_val) {   // logits-only launches pass no temperatures
-        inv_tau = 1.0f / p.tau[n];
-        if (p.row_seeds) seed_n = p.row_seeds[n];
-    }
-    const uint32_t row_word = (uint32_t)(uint64_t)(p.row_offset + n);
+    // per-row epilogue constants (logits-only launches pass no temperatures)
+    RowEpi repi = {1.0f, p.seed, (uint32_t)(uint64_t)(p.row_offset + n), nullptr};
+    if (n < B && p.cand_val) repi = make_row_epi<FULL>(p, n);
 
     // row-tiles of this workgroup, in processing order
     const int T = p.T;
@@ -188,6 +184,7 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
             __syncthreads();   // all partial tiles of this vocabulary tile are in LDS
             float best = -__builtin_inff();
             int best_id = -1;
+            float lmax = -__builtin_inff(), lsum = 0.0f;
             for (int r8 = wave; r8 < 8; r8 += nw) {
                 f32x4 y = partial[(r8 * nw) * 64 + lane];
                 for (int w = 1; w < nw; ++w) y += partial[(r8 * nw + w) * 64 + lane];
@@ -203,19 +200,15 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
                                 if (v0 + j < V) dst[j] = y[j];
                         }
                     }
-                    if (p.cand_val) {
-                        float gn[4];
-                        gumbel4(seed_n, row_word, (uint32_t)(p.vocab_offset + v0), gn);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float s = fmaf(y[j], inv_tau, gn[j]);
-                            if (v0 + j < V && s > best) { best = s; best_id = p.vocab_offset + v0 + j; }
-                        }
-                    }
+                    if (p.cand_val) epilogue_quad<FULL>(p, repi, y, v0, V, best, best_id, lmax, lsum);
                 }
             }
             cand_reduce_lane_groups(best, best_id);
             if (g == 0) wave_cand[wave * 16 + n] = make_float2(best, __int_as_float(best_id));
+            if constexpr (FULL) {
+                lse_reduce_lane_groups(lmax, lsum);
+                if (g == 0) wave_lse[wave * 16 + n] = make_float2(lmax, lsum);
+            }
             __syncthreads();   // wave candidates visible; partial buffer free again
             if (wave == 0 && lane < 16 && n < B && p.cand_val) {
                 float bv = -__builtin_inff();
@@ -226,6 +219,17 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
                 }
                 p.cand_val[(size_t)n * T + tile] = bv;
                 p.cand_idx[(size_t)n * T + tile] = bi;
+                if constexpr (FULL) {
+                    if (p.lse_max) {
+                        float m = -__builtin_inff(), sacc = 0.0f;
+                        for (int w = 0; w < nw; ++w) {
+                            const float2 c = wave_lse[w * 16 + n];
+                            lse_merge(m, sacc, c.x, c.y);
+                        }
+                        p.lse_max[(size_t)n * T + tile] = m;
+                        p.lse_sum[(size_t)n * T + tile] = sacc;
+                    }
+                }
             }
         }
     }

@@ -148,13 +148,9 @@ stage1_tiled_kernel(const Stage1Params p)
         float best = -__builtin_inff();
         int best_id = -1;
         if (b < B) {
-            float inv_tau = 1.0f;
-            uint64_t seed_b = p.seed;
-            if (p.cand_val) {
-                inv_tau = 1.0f / p.tau[b];
-                if (p.row_seeds) seed_b = p.row_seeds[b];
-            }
-            const uint32_t row_word = (uint32_t)(uint64_t)(p.row_offset + b);
+            RowEpi repi = {1.0f, p.seed, (uint32_t)(uint64_t)(p.row_offset + b), nullptr};
+            if (p.cand_val) repi = make_row_epi<false>(p, b);
+            float unused_m = 0.0f, unused_s = 0.0f;
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const f32x4 y = acc[i][nb];
@@ -170,15 +166,7 @@ stage1_tiled_kernel(const Stage1Params p)
                                 if (v0 + j < V) dst[j] = y[j];
                         }
                     }
-                    if (p.cand_val) {
-                        float gn[4];
-                        gumbel4(seed_b, row_word, (uint32_t)(p.vocab_offset + v0), gn);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float s = fmaf(y[j], inv_tau, gn[j]);
-                            if (v0 + j < V && s > best) { best = s; best_id = p.vocab_offset + v0 + j; }
-                        }
-                    }
+                    if (p.cand_val) epilogue_quad<false>(p, repi, y, v0, V, best, best_id, unused_m, unused_s);
                 }
             }
         }

@@ -39,10 +39,10 @@ struct Tiled2Cfg {
     static constexpr int kWLoads = kVocabTile * 8 / 256;       // 4
     static constexpr int kHLoads = BT * 8 / 256;               // 1..4
     static_assert(BT % 32 == 0, "hidden tile rows are loaded 32 at a time");
-    static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8; }
+    static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8 * 2; }
 };
 
-template <class Cfg, bool STREAM_W>
+template <class Cfg, bool STREAM_W, bool FULL = false>
 __global__ void __launch_bounds__(256, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
@@ -53,6 +53,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
     auto h_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes + Cfg::kWBytes; };
     float2* wave_cand = reinterpret_cast<float2*>(smem + 2 * Cfg::kBufBytes);   // [WM][BT]
+    float2* wave_lse = wave_cand + WM * BT;                                    // [WM][BT]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -211,14 +212,10 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         const int b = b0 + bl;
         float best = -__builtin_inff();
         int best_id = -1;
+        float lmax = -__builtin_inff(), lsum = 0.0f;
         if (b < B) {
-            float inv_tau = 1.0f;
-            uint64_t seed_b = p.seed;
-            if (p.cand_val) {
-                inv_tau = 1.0f / p.tau[b];
-                if (p.row_seeds) seed_b = p.row_seeds[b];
-            }
-            const uint32_t row_word = (uint32_t)(uint64_t)(p.row_offset + b);
+            RowEpi repi = {1.0f, p.seed, (uint32_t)(uint64_t)(p.row_offset + b), nullptr};
+            if (p.cand_val) repi = make_row_epi<FULL>(p, b);
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
                 const f32x4 y = acc[i][j];
@@ -234,20 +231,16 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
                                 if (v0 + q < V) dst[q] = y[q];
                         }
                     }
-                    if (p.cand_val) {
-                        float gn[4];
-                        gumbel4(seed_b, row_word, (uint32_t)(p.vocab_offset + v0), gn);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float s = fmaf(y[q], inv_tau, gn[q]);
-                            if (v0 + q < V && s > best) { best = s; best_id = p.vocab_offset + v0 + q; }
-                        }
-                    }
+                    if (p.cand_val) epilogue_quad<FULL>(p, repi, y, v0, V, best, best_id, lmax, lsum);
                 }
             }
         }
         cand_reduce_lane_groups(best, best_id);
         if (g == 0) wave_cand[wm * BT + bl] = make_float2(best, __int_as_float(best_id));
+        if constexpr (FULL) {
+            lse_reduce_lane_groups(lmax, lsum);
+            if (g == 0) wave_lse[wm * BT + bl] = make_float2(lmax, lsum);
+        }
     }
     __syncthreads();
     if (p.cand_val && tid < BT && b0 + tid < B) {
@@ -260,6 +253,18 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
         p.cand_val[(size_t)(b0 + tid) * T + tile] = bv;
         p.cand_idx[(size_t)(b0 + tid) * T + tile] = bi;
+        if constexpr (FULL) {
+            if (p.lse_max) {
+                float m = -__builtin_inff(), sacc = 0.0f;
+#pragma unroll
+                for (int w = 0; w < WM; ++w) {
+                    const float2 c = wave_lse[w * BT + tid];
+                    lse_merge(m, sacc, c.x, c.y);
+                }
+                p.lse_max[(size_t)(b0 + tid) * T + tile] = m;
+                p.lse_sum[(size_t)(b0 + tid) * T + tile] = sacc;
+            }
+        }
     }
 }
 

@@ -44,7 +44,8 @@ class Verdict:
 
 
 def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_ids=None,
-          row_offset=0, vocab_offset=0, rows: Optional[Sequence[int]] = None) -> Verdict:
+          row_offset=0, vocab_offset=0, rows: Optional[Sequence[int]] = None,
+          bias=None, allowed_words=None) -> Verdict:
     """ref = oracle.sample(...) over the rows being judged (same order as `rows`, which index
     into H / gpu_idx; default all rows).  row_ids gives the global row word per judged row."""
     B = H.shape[0]
@@ -68,7 +69,12 @@ def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_
         if gi < vocab_offset or gi >= vocab_offset + W.shape[0]:
             v.failures.append((b, "index out of range", gi, gv))
             continue
-        s_pick = orc.score_at(H, W, b, gi - vocab_offset, t, seed_b, row_word, gi)
+        if bias is None and allowed_words is None:
+            s_pick = orc.score_at(H, W, b, gi - vocab_offset, t, seed_b, row_word, gi)
+        else:   # full transform: (y + bias) / tau, -inf when the id is masked for this row
+            arow = None if allowed_words is None else (allowed_words if allowed_words.ndim == 1 else allowed_words[b])
+            s_pick = orc.score_at_full(H, W, b, gi - vocab_offset, t, seed_b, row_word, gi, bias=bias,
+                                       allowed_row=arow)
         val_tol = 2e-3 / min(t, 1.0) + tol
         err = abs(gv - s_pick)
         v.max_val_err = max(v.max_val_err, err)
