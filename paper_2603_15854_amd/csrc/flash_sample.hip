@@ -155,7 +155,8 @@ template <class Cfg, bool FULL = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
-    const long long grid = (long long)((p.T + 7) / 8) * 8 * nbt;
+    const int macro_tiles = (p.V + Cfg::VT - 1) / Cfg::VT;
+    const long long grid = (long long)((macro_tiles + 7) / 8) * 8 * nbt;
     if (grid > 0x7FFFFFFFll) return FS_ERR_SHAPE;
     static bool attr_set = false;
     if (!attr_set) {
@@ -164,21 +165,24 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
         attr_set = true;
     }
     if (nbt == 1)
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL>), dim3((unsigned)grid), dim3(256),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            Cfg::lds_bytes(), st, p, nbt);
     else
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL>), dim3((unsigned)grid), dim3(256),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            Cfg::lds_bytes(), st, p, nbt);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
+// B > 16: batch tile 32 (4 waves, 128 vocabulary rows per workgroup) up to B = 32; above that
+// 8 waves on 256 vocabulary rows with a 64- or 128-row batch tile, which halves the hidden-tile
+// re-reads per W byte (measured -10 % time at B = 64, -7 % at B = 128, -3 % at B = 256 against
+// the 128-row workgroups).  A 256 x 256 tile does not fit the register file at 2 waves per SIMD.
+template <bool FULL>
 fs_status launch_tiled2_auto(const Stage1Params& p, hipStream_t st)
 {
-    // batch tile 32 / 64 / 128; W prefetched in groups of 4 (2 at the widest tile) K steps.
-    // Other wave arrangements and group sizes measured within 3 % of these on MI355X.
-    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>>(p, st);
-    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>>(p, st);
-    return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>>(p, st);
+    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
+    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
+    return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
 }
 
 // stage 1 with the full transform / log-normaliser epilogue: the default kernels only
@@ -194,9 +198,7 @@ fs_status launch_stage1_full(const Stage1Params& p, uint32_t flags, hipStream_t 
         const int nw = (ksteps + 31) / 32;
         return launch_splitk<SplitKCfg<32, 8, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
     }
-    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, true>(p, st);
-    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 4>, true>(p, st);
-    return launch_tiled2<Tiled2Cfg<128, 2, 2, 2>, true>(p, st);
+    return launch_tiled2_auto<true>(p, st);
 }
 
 fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
@@ -232,7 +234,7 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     case FS_VARIANT_AUTO:
         if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_B);
         if (p.B <= 16) return launch_tiled_auto(p, st);
-        return launch_tiled2_auto(p, st);
+        return launch_tiled2_auto<false>(p, st);
     case FS_VARIANT_SPLITK_A:
     case FS_VARIANT_SPLITK_B:
     case FS_VARIANT_SPLITK_C:
@@ -242,7 +244,7 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     case FS_VARIANT_TILED:
         return launch_tiled_auto(p, st);
     case FS_VARIANT_TILED2:
-        return launch_tiled2_auto(p, st);
+        return launch_tiled2_auto<false>(p, st);
     default:
         return FS_ERR_UNSUPPORTED;
     }

@@ -25,29 +25,37 @@
 
 namespace fs {
 
-template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2>
+// VT: vocabulary rows per workgroup (128 or 256 = one or two candidate tiles); BT: batch rows;
+// WM x WN waves (4 or 8); GS: K steps per W prefetch group; OCC: waves per SIMD asked for.
+template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2, int VT_ = kVocabTile>
 struct Tiled2Cfg {
-    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_, OCC = OCC_;
-    static_assert(WM * WN == 4, "four waves per workgroup");
-    static constexpr int RB = kVocabTile / (16 * WM);   // 16-row blocks per wave
-    static constexpr int CB = BT / (16 * WN);           // 16-column blocks per wave
-    static_assert(RB >= 1 && CB >= 1, "wave tile");
+    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_, OCC = OCC_, VT = VT_;
+    static constexpr int kWaves = WM * WN;
+    static constexpr int kThreads = kWaves * kWave;
+    static_assert(kWaves == 4 || kWaves == 8, "four or eight waves per workgroup");
+    static_assert(VT % kVocabTile == 0, "whole candidate tiles");
+    static constexpr int RB = VT / (16 * WM);            // 16-row blocks per wave
+    static constexpr int CB = BT / (16 * WN);            // 16-column blocks per wave
+    static_assert(RB >= 1 && CB >= 1 && kVocabTile % (16 * RB) == 0, "wave tile inside one candidate tile");
+    static constexpr int kWavesPerCandTile = kVocabTile / (16 * RB);
+    static constexpr int kCandTiles = VT / kVocabTile;
     static constexpr int kKS = 64;
-    static constexpr int kWBytes = kVocabTile * 128;
+    static constexpr int kWBytes = VT * 128;
     static constexpr int kHBytes = BT * 128;
     static constexpr int kBufBytes = kWBytes + kHBytes;
-    static constexpr int kWLoads = kVocabTile * 8 / 256;       // 4
-    static constexpr int kHLoads = BT * 8 / 256;               // 1..4
-    static_assert(BT % 32 == 0, "hidden tile rows are loaded 32 at a time");
+    static constexpr int kRowsPerPass = kThreads / 8;    // rows one workgroup-wide load covers
+    static constexpr int kWLoads = VT / kRowsPerPass;
+    static constexpr int kHLoads = BT / kRowsPerPass;
+    static_assert(kWLoads >= 1 && kHLoads >= 1 && BT % kRowsPerPass == 0, "tile rows per load pass");
     static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8 * 2; }
 };
 
 template <class Cfg, bool STREAM_W, bool FULL = false>
-__global__ void __launch_bounds__(256, Cfg::OCC)
+__global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
-    constexpr int KS = Cfg::kKS;
+    constexpr int KS = Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
@@ -62,15 +70,15 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int n = lane & 15, g = lane >> 4;
     const int B = p.B, D = p.D, V = p.V, T = p.T;
 
-    // dispatch id -> (vocabulary tile, batch tile): ids of one W tile are 8 apart (same XCD)
+    // dispatch id -> (vocabulary macro tile, batch tile): ids of one W tile are 8 apart (same XCD)
     const int id = (int)blockIdx.x;
     const int group = id / (8 * nbt);
     const int rem = id - group * (8 * nbt);
-    const int tile = group * 8 + (rem & 7);
+    const int tile = group * 8 + (rem & 7);      // macro tile of VT vocabulary rows
     const int bt = rem >> 3;
-    if (tile >= T) return;                       // whole workgroup leaves: no barrier is skipped
+    if (tile * VT >= V) return;                  // whole workgroup leaves: no barrier is skipped
     const int b0 = bt * BT;
-    const int tile_row0 = tile * kVocabTile;
+    const int tile_row0 = tile * VT;
 
     // K steps of this tile, visited in rotated order: workgroups that run at the same time start
     // at different offsets along K (eight phases), so that at any instant the rows being read are
@@ -84,7 +92,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     };
 
     const int ld_chunk = tid & 7;
-    const int ld_row = tid >> 3;   // 0..31
+    const int ld_row = tid >> 3;   // 0..RPP-1
     uint4 wst[2][GS][Cfg::kWLoads];   // two groups of GS steps
     uint4 hst[2][Cfg::kHLoads];       // two steps
 
@@ -101,7 +109,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         k = over ? ld_chunk * 8 : k;
 #pragma unroll
         for (int i = 0; i < Cfg::kWLoads; ++i) {
-            int row = tile_row0 + ld_row + 32 * i;
+            int row = tile_row0 + ld_row + RPP * i;
             row = row < V - 1 ? row : V - 1;
             row = over ? tile_row0 : row;
             const uint16_t* src = p.W + (size_t)row * D + k;
@@ -119,7 +127,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         k = over ? ld_chunk * 8 : k;
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
-            int r = b0 + ld_row + 32 * i;
+            int r = b0 + ld_row + RPP * i;
             r = r < B - 1 ? r : B - 1;
             hr[i] = ld_global_16B(p.H + (size_t)r * D + k);
         }
@@ -129,14 +137,14 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         const bool zero = k_ragged && (step * KS + ld_chunk * 8 >= D);   // only in the last step
 #pragma unroll
         for (int i = 0; i < Cfg::kWLoads; ++i) {
-            const int r = ld_row + 32 * i;
+            const int r = ld_row + RPP * i;
             uint4 v = wr[i];
             if (zero) v = make_uint4(0u, 0u, 0u, 0u);
             *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
-            const int r = ld_row + 32 * i;
+            const int r = ld_row + RPP * i;
             uint4 v = hr[i];
             if (zero) v = make_uint4(0u, 0u, 0u, 0u);
             *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
@@ -243,26 +251,31 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
     }
     __syncthreads();
-    if (p.cand_val && tid < BT && b0 + tid < B) {
+    // one candidate per (batch row, candidate tile of 128 ids): merge the waves that share the tile
+    constexpr int WPT = Cfg::kWavesPerCandTile;
+    const int cq = tid / BT;                      // candidate tile inside the macro tile
+    const int bcol = tid - cq * BT;
+    const int ctile = tile * Cfg::kCandTiles + cq;
+    if (p.cand_val && tid < BT * Cfg::kCandTiles && b0 + bcol < B && ctile < T) {
         float bv = -__builtin_inff();
         int bi = -1;
 #pragma unroll
-        for (int w = 0; w < WM; ++w) {
-            const float2 c = wave_cand[w * BT + tid];
+        for (int w = 0; w < WPT; ++w) {
+            const float2 c = wave_cand[(cq * WPT + w) * BT + bcol];
             cand_merge(bv, bi, c.x, __float_as_int(c.y));
         }
-        p.cand_val[(size_t)(b0 + tid) * T + tile] = bv;
-        p.cand_idx[(size_t)(b0 + tid) * T + tile] = bi;
+        p.cand_val[(size_t)(b0 + bcol) * T + ctile] = bv;
+        p.cand_idx[(size_t)(b0 + bcol) * T + ctile] = bi;
         if constexpr (FULL) {
             if (p.lse_max) {
                 float m = -__builtin_inff(), sacc = 0.0f;
 #pragma unroll
-                for (int w = 0; w < WM; ++w) {
-                    const float2 c = wave_lse[w * BT + tid];
+                for (int w = 0; w < WPT; ++w) {
+                    const float2 c = wave_lse[(cq * WPT + w) * BT + bcol];
                     lse_merge(m, sacc, c.x, c.y);
                 }
-                p.lse_max[(size_t)(b0 + tid) * T + tile] = m;
-                p.lse_sum[(size_t)(b0 + tid) * T + tile] = sacc;
+                p.lse_max[(size_t)(b0 + bcol) * T + ctile] = m;
+                p.lse_sum[(size_t)(b0 + bcol) * T + ctile] = sacc;
             }
         }
     }
