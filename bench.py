@@ -53,7 +53,7 @@ def main() -> int:
 
     import fs_workloads as wl
     import paper_2603_15854_amd as fs
-    from tests.parity import to_device_bf16
+    from fs_workloads import to_device_bf16
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

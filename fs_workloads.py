@@ -142,3 +142,17 @@ def make_small(D: int, V: int, B: int, data_seed: int, w_row_scale: float = 1.0)
     H = _normal_bf16(B, D, 1.0, (data_seed, _TAG_H), threads=1)
     W = _normal_bf16(V, D, w_row_scale / float(np.sqrt(D)), (data_seed, _TAG_W), threads=1)
     return H, W
+
+
+def to_device_bf16(bits: np.ndarray):
+    """bf16 bit patterns (uint16) -> torch.bfloat16 tensor on the current GPU (a plain upload)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def to_device_seeds(seeds: Optional[np.ndarray]):
+    """uint64 seeds -> device tensor carrying the same 64-bit patterns (torch has no uint64 math)."""
+    import torch
+    if seeds is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64)).cuda()

@@ -14,16 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 
-def to_device_bf16(bits: np.ndarray):
-    import torch
-    return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
-
-
-def to_device_seeds(seeds: Optional[np.ndarray]):
-    import torch
-    if seeds is None:
-        return None
-    return torch.from_numpy(np.ascontiguousarray(seeds, dtype=np.uint64).view(np.int64)).cuda()
+from fs_workloads import to_device_bf16, to_device_seeds  # noqa: F401  (re-exported for the tests)
 
 
 @dataclass
