@@ -100,6 +100,24 @@ def lib():
     L.fso_score_at_full.restype = C.c_double
     L.fso_num_threads.argtypes = []
     L.fso_num_threads.restype = C.c_int
+    L.fso_group_word.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_uint32]
+    L.fso_group_word.restype = C.c_uint32
+    L.fso_group_stats.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_uint64, C.c_int64, C.c_int64,
+                                  _i64p, _f64p, _f64p, _f64p]
+    L.fso_group_stats.restype = None
+    L.fso_group_choose_parallel.argtypes = [_f64p, C.c_int64, C.c_uint64, C.c_int64, C.c_int64, _f64p]
+    L.fso_group_choose_parallel.restype = C.c_int64
+    L.fso_group_choose_online.argtypes = [_f64p, C.c_int64, C.c_uint64, C.c_int64, C.c_int64, _f64p,
+                                          _f64p, C.POINTER(C.c_double)]
+    L.fso_group_choose_online.restype = C.c_int64
+    L.fso_sample_grouped.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                                     C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                     C.c_void_p, C.c_int64, C.c_int64, C.c_int, _i32p, _f64p, _i64p,
+                                     _f64p, _f64p, _f64p, _f64p, _f64p]
+    L.fso_sample_grouped.restype = C.c_int
+    L.fso_grouped_draw_counts.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int64,
+                                          C.c_int64, _i64p]
+    L.fso_grouped_draw_counts.restype = None
     _lib = L
     return L
 
@@ -304,6 +322,73 @@ def score_at_full(H, W, b_local, i_local, tau, seed, row, vocab_id, bias=None, a
     ar, ar_p = _opt_ptr(allowed_row, np.uint32)
     return float(lib().fso_score_at_full(H, W, H.shape[1], b_local, i_local, float(tau), seed, row,
                                          vocab_id, bb_p, ar_p))
+
+
+GROUPED_PARALLEL, GROUPED_ONLINE = 0, 1
+
+
+def group_word(seed: int, row: int, group_id: int, stream: int) -> int:
+    return int(lib().fso_group_word(seed, row, group_id, stream))
+
+
+def group_stats(z, g: int, seed: int, row: int, vocab_offset: int = 0):
+    """Per-group local sample, its top-two perturbed scores and the group log-mass of one row."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    m = (z.size + g - 1) // g
+    zk = np.empty(m, dtype=np.int64)
+    s1, s2, L = (np.empty(m, dtype=np.float64) for _ in range(3))
+    lib().fso_group_stats(z, z.size, g, seed, row, vocab_offset, zk, s1, s2, L)
+    return dict(zk=zk, s1=s1, s2=s2, L=L)
+
+
+def group_choose_parallel(L, seed: int, row: int, group_offset: int = 0):
+    L = np.ascontiguousarray(L, dtype=np.float64)
+    score = np.empty_like(L)
+    k = lib().fso_group_choose_parallel(L, L.size, seed, row, group_offset, score)
+    return int(k), score
+
+
+def group_choose_online(L, seed: int, row: int, group_offset: int = 0):
+    L = np.ascontiguousarray(L, dtype=np.float64)
+    u, p = np.empty_like(L), np.empty_like(L)
+    lse = C.c_double()
+    k = lib().fso_group_choose_online(L, L.size, seed, row, group_offset, u, p, C.byref(lse))
+    return int(k), u, p, lse.value
+
+
+def sample_grouped(H, W, tau, g: int, mode: int, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                   row_ids=None, vocab_offset: int = 0, bias=None, allowed_words=None):
+    """Grouped variants (mode GROUPED_PARALLEL / GROUPED_ONLINE) with groups of g ids.
+    Returns idx, lse and the per-group diagnostics zk, s1, s2, L, outer, p (each [B, m])."""
+    B, D = H.shape
+    V = W.shape[0]
+    assert vocab_offset % g == 0
+    m = (V + g - 1) // g
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    ri, ri_p = _opt_ptr(row_ids, np.int64)
+    bb, bb_p = _opt_ptr(bias, np.float32)
+    aw, aw_p = _opt_ptr(allowed_words, np.uint32)
+    stride = 0
+    if aw is not None and aw.ndim == 2:
+        assert aw.shape[0] == B
+        stride = aw.shape[1]
+    out_idx = np.empty(B, dtype=np.int32)
+    lse = np.empty(B, dtype=np.float64)
+    zk = np.empty((B, m), dtype=np.int64)
+    s1, s2, L, outer, p = (np.full((B, m), np.nan, dtype=np.float64) for _ in range(5))
+    nt = lib().fso_sample_grouped(H, W, B, D, V, tau, seed, rs_p, row_offset, ri_p, vocab_offset, bb_p,
+                                  aw_p, stride, g, mode, out_idx, lse, zk, s1, s2, L, outer, p)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, lse=lse, zk=zk, s1=s1, s2=s2, L=L, outer=outer, p=p, threads=nt)
+
+
+def grouped_draw_counts(z, g: int, mode: int, seed: int, ndraws: int, row0: int = 0) -> np.ndarray:
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    counts = np.zeros(z.size, dtype=np.int64)
+    lib().fso_grouped_draw_counts(z, z.size, g, mode, seed, row0, ndraws, counts)
+    return counts
 
 
 def num_threads() -> int:

@@ -30,7 +30,8 @@
  * GPU's candidate buffer.
  *
  * The full transform (additive bias, temperature, -inf mask) and the log-normaliser
- * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below).
+ * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below); the
+ * grouped variants (parallel and online Group-Gumbel-Max) are the third (fso_group_word and below).
  *
  * NaN scores never win (the strict > comparison is false for NaN); a row with no
  * score > -inf returns idx = -1, val = -inf.
@@ -352,6 +353,184 @@ double fso_score_at_full(const uint16_t* H, const uint16_t* W, int64_t D, int64_
     fso_transform_row(&y, 1, tau, bias ? bias + i_local : NULL, NULL, &z);
     if (allowed_row && !((allowed_row[i_local >> 5] >> (i_local & 31)) & 1u)) return -INFINITY;
     return z + fso_gumbel(seed, row, vocab_id);
+}
+
+/* ------------------------------------------------------------------ grouped variants */
+
+/*
+ * Group-Gumbel-Max (Section "Group-Gumbel-Max: Hierarchical Exact Sampling"; appendix algorithms
+ * "FlashSampling (parallel)" and "FlashSampling (sequential/online)").  The vocabulary is cut into
+ * groups of `g` consecutive ids (the last one may be shorter).  For every group k of a row:
+ *      z_k  = Gumbel-max sample inside the group, with the same per-(row, id) noise as the main
+ *             path (so z_k is also the best of the main path's candidates inside the group)
+ *      L_k  = log sum_{i in group} exp(z_i)                       (group log-mass)
+ * A zero-mass group (L_k = -inf) is skipped.  The two variants differ in how the group is chosen;
+ * both are exact in distribution (Lemma "Exact group factorization", Lemma "binary merge"), not
+ * pathwise equal to the main path.
+ *
+ * Noise of the group choice (this build's reading; the paper only asks for fresh uniforms):
+ * word (k & 3) of Philox4x32-10(counter = (k >> 2, row, stream, 0), same key), k the global group
+ * id, stream = 1 for the parallel variant's outer Gumbels and 2 for the online variant's
+ * accept/reject uniforms (stream 0 is the per-id noise), mapped to x in (0,1) as in fso_uniform_x.
+ */
+uint32_t fso_group_word(uint64_t seed, int64_t row, int64_t group_id, uint32_t stream)
+{
+    uint32_t ctr[4] = { (uint32_t)((uint64_t)group_id >> 2), (uint32_t)(uint64_t)row, stream, 0u };
+    uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    fso_philox4x32_10(ctr, key, out);
+    return out[(uint64_t)group_id & 3u];
+}
+
+/* Per-group local sample (global id, -1 for a zero-mass group), its top-two perturbed scores and
+ * the group log-mass, for one row of transformed logits z[0..V).  m = ceil(V / g) groups. */
+void fso_group_stats(const double* z, int64_t V, int64_t g, uint64_t seed, int64_t row,
+                     int64_t vocab_offset, int64_t* zk, double* s1, double* s2, double* L)
+{
+    int64_t m = (V + g - 1) / g;
+    for (int64_t k = 0; k < m; ++k) {
+        int64_t lo = k * g, n = (V - lo < g) ? V - lo : g;
+        int64_t i1, i2;
+        double m1, m2;
+        fso_gumbel_max_transformed(z + lo, n, seed, row, vocab_offset + lo, &i1, &m1, &i2, &m2);
+        zk[k] = i1;
+        if (s1) s1[k] = m1;
+        if (s2) s2[k] = m2;
+        L[k] = fso_log_sum_exp(z + lo, n);
+    }
+}
+
+/* Parallel variant: k* = argmax_k (L_k - log(-log ubar_k)), lowest k on exact ties; score[k] is
+ * the perturbed log-mass (-inf for a zero-mass group).  Returns k* or -1 when every group has
+ * zero mass. */
+int64_t fso_group_choose_parallel(const double* L, int64_t m, uint64_t seed, int64_t row,
+                                  int64_t group_offset, double* score)
+{
+    double best = -INFINITY;
+    int64_t kstar = -1;
+    for (int64_t k = 0; k < m; ++k) {
+        double s = -INFINITY;
+        if (L[k] > -INFINITY)
+            s = L[k] + fso_gumbel_from_word(fso_group_word(seed, row, group_offset + k, 1u));
+        if (score) score[k] = s;
+        if (s > best) { best = s; kstar = k; }
+    }
+    return kstar;
+}
+
+/* log(e^a + e^b) for a, b in [-inf, +inf). */
+static double lse2(double a, double b)
+{
+    double hi = a > b ? a : b, lo = a > b ? b : a;
+    if (!(hi > -INFINITY)) return -INFINITY;
+    return hi + log1p(exp(lo - hi));
+}
+
+/* Online variant: running (ell, k*) over the groups in ascending order; group k replaces the
+ * running sample when u_k < p_k = exp(L_k - lse(ell, L_k)).  The first nonzero-mass group has
+ * p = 1 and u < 1 always, which is the algorithm's initialisation.  u[k], p[k] are reported for
+ * every nonzero-mass group (NaN otherwise).  Returns k* or -1; *lse_out = final ell. */
+int64_t fso_group_choose_online(const double* L, int64_t m, uint64_t seed, int64_t row,
+                                int64_t group_offset, double* u, double* p, double* lse_out)
+{
+    double ell = -INFINITY;
+    int64_t kstar = -1;
+    for (int64_t k = 0; k < m; ++k) {
+        if (u) u[k] = NAN;
+        if (p) p[k] = NAN;
+        if (!(L[k] > -INFINITY)) continue;
+        double ell_new = lse2(ell, L[k]);
+        double p_replace = exp(L[k] - ell_new);
+        double uk = (double)fso_uniform_x(fso_group_word(seed, row, group_offset + k, 2u));
+        if (u) u[k] = uk;
+        if (p) p[k] = p_replace;
+        if (uk < p_replace) kstar = k;
+        ell = ell_new;
+    }
+    if (lse_out) *lse_out = ell;
+    return kstar;
+}
+
+/* One row, from transformed logits: mode 0 = parallel, 1 = online.  Returns the sampled global id
+ * (-1 when the row has no mass); *lse_out = log sum_i exp(z_i) = lse over the group log-masses. */
+int64_t fso_grouped_row(const double* z, int64_t V, int64_t g, int mode, uint64_t seed, int64_t row,
+                        int64_t vocab_offset, double* lse_out, int64_t* zk, double* s1, double* s2,
+                        double* L, double* outer, double* p)
+{
+    int64_t m = (V + g - 1) / g, kstar;
+    int own = 0;
+    if (!zk) { zk = (int64_t*)malloc(sizeof(int64_t) * (size_t)m); own |= 1; }
+    if (!L) { L = (double*)malloc(sizeof(double) * (size_t)m); own |= 2; }
+    fso_group_stats(z, V, g, seed, row, vocab_offset, zk, s1, s2, L);
+    int64_t group_offset = vocab_offset / g;
+    double lse = -INFINITY;
+    if (mode == 0) {
+        kstar = fso_group_choose_parallel(L, m, seed, row, group_offset, outer);
+        lse = fso_log_sum_exp(L, m);
+    } else {
+        kstar = fso_group_choose_online(L, m, seed, row, group_offset, outer, p, &lse);
+    }
+    int64_t id = kstar < 0 ? -1 : zk[kstar];
+    if (lse_out) *lse_out = lse;
+    if (own & 1) free(zk);
+    if (own & 2) free(L);
+    return id;
+}
+
+/*
+ * Whole batch: logits, full transform, then the grouped choice.  Diagnostics (each NULL or
+ * [B, m], m = ceil(V / g)): zk local samples, s1/s2 their top-two perturbed scores, L log-masses,
+ * outer = perturbed log-mass (parallel) or the uniform u_k (online), p = replace probability
+ * (online only).  vocab_offset must be a multiple of g (global group ids index the noise).
+ */
+int fso_sample_grouped(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V,
+                       const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                       const int64_t* row_ids, int64_t vocab_offset, const float* bias,
+                       const uint32_t* allowed, int64_t mask_stride_words, int64_t g, int mode,
+                       int32_t* out_idx, double* out_lse, int64_t* zk, double* s1, double* s2,
+                       double* L, double* outer, double* p)
+{
+    if (B <= 0 || V <= 0 || g <= 0 || vocab_offset % g != 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits(H, W, B, D, V, Y);
+    int64_t m = (V + g - 1) / g;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        double* z = Y + b * V;
+        const uint32_t* arow = allowed ? allowed + (size_t)b * (size_t)mask_stride_words : NULL;
+        fso_transform_row(z, V, (double)tau[b], bias, arow, z);
+        double lse;
+        int64_t id = fso_grouped_row(z, V, g, mode, row_seed(seed, row_seeds, b),
+                                     row_id(row_ids, row_offset, b), vocab_offset, &lse,
+                                     zk ? zk + b * m : NULL, s1 ? s1 + b * m : NULL,
+                                     s2 ? s2 + b * m : NULL, L ? L + b * m : NULL,
+                                     outer ? outer + b * m : NULL, p ? p + b * m : NULL);
+        out_idx[b] = (int32_t)id;
+        if (out_lse) out_lse[b] = lse;
+    }
+    free(Y);
+    return nthreads;
+}
+
+/* counts[i] += draws of the grouped sampler that picked i, draw d using (seed, row = row0 + d),
+ * on a fixed row of transformed logits z. */
+void fso_grouped_draw_counts(const double* z, int64_t V, int64_t g, int mode, uint64_t seed,
+                             int64_t row0, int64_t ndraws, int64_t* counts)
+{
+#pragma omp parallel
+    {
+        int64_t* local = (int64_t*)calloc((size_t)V, sizeof(int64_t));
+#pragma omp for schedule(static)
+        for (int64_t d = 0; d < ndraws; ++d) {
+            int64_t id = fso_grouped_row(z, V, g, mode, seed, row0 + d, 0, NULL, NULL, NULL, NULL,
+                                         NULL, NULL, NULL);
+            if (id >= 0) local[id] += 1;
+        }
+#pragma omp critical
+        for (int64_t i = 0; i < V; ++i) counts[i] += local[i];
+        free(local);
+    }
 }
 
 /* ------------------------------------------------------------------ helpers for the pins */

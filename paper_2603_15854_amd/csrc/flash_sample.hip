@@ -49,13 +49,22 @@ int current_device_cus(int* dev_out)
     return g_dev[dev].cus;
 }
 
-// Kernels that use more than 64 KiB of dynamic LDS must say so once.
+// Kernels that use more than 64 KiB of dynamic LDS must say so once per device (a function
+// attribute belongs to the device that was current when it was set).
 template <class K>
 hipError_t allow_lds(K kernel, size_t bytes)
 {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
+
+// Per-kernel, per-device set-up state of one launcher instantiation.  Written under g_mu; the
+// values are idempotent, so a reader that misses a concurrent update only repeats the set-up.
+template <int N = 1>
+struct PerDevice {
+    bool attr[kMaxDevices] = {};
+    int resident[kMaxDevices][N] = {};
+};
 
 fs_status check_problem(const void* hidden, const void* W, int B, int D, int V,
                         int64_t row_offset, int32_t vocab_offset)
@@ -102,22 +111,24 @@ fs_status launch_splitk(const Stage1Params& p, int kpw, int nw, int wgs_per_cu_o
     const size_t lds = Cfg::lds_bytes(nw);
     if (nw > Cfg::kMaxWaves || lds > kLdsPerCU) return FS_ERR_UNSUPPORTED;
     auto kernel = stage1_splitk_kernel<Cfg, FULL>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        attr_set = true;
-    }
-    const int cus = current_device_cus(nullptr);
+    int dev = 0;
+    const int cus = current_device_cus(&dev);
     if (cus <= 0) return FS_ERR_HIP;
+    static PerDevice<Cfg::kMaxWaves + 1> state;
+    if (!state.attr[dev]) {
+        if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.attr[dev] = true;
+    }
     // persistent grid: as many workgroups as are resident at once (registers and LDS decide)
-    static int resident[Cfg::kMaxWaves + 1] = {0};
-    if (resident[nw] == 0) {
+    if (state.resident[dev][nw] == 0) {
         int occ = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, nw * kWave, lds) != hipSuccess)
             return FS_ERR_HIP;
-        resident[nw] = occ < 1 ? 1 : occ;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.resident[dev][nw] = occ < 1 ? 1 : occ;
     }
-    int per_cu = resident[nw];
+    int per_cu = state.resident[dev][nw];
     if (wgs_per_cu_override > 0) per_cu = wgs_per_cu_override;
     int grid = cus * per_cu;
     if (grid > p.T) grid = p.T;
@@ -130,10 +141,13 @@ fs_status launch_tiled(const Stage1Params& p, hipStream_t st)
 {
     using Cfg = TiledCfg<NB>;
     auto kernel = stage1_tiled_kernel<NB>;
-    static bool attr_set = false;
-    if (!attr_set) {
+    int dev = 0;
+    if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
+    static PerDevice<> state;
+    if (!state.attr[dev]) {
         if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        attr_set = true;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.attr[dev] = true;
     }
     const int nbt = (p.B + Cfg::kBatchTile - 1) / Cfg::kBatchTile;
     const long long grid = (long long)p.T * nbt;
@@ -158,11 +172,14 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     const int macro_tiles = (p.V + Cfg::VT - 1) / Cfg::VT;
     const long long grid = (long long)((macro_tiles + 7) / 8) * 8 * nbt;
     if (grid > 0x7FFFFFFFll) return FS_ERR_SHAPE;
-    static bool attr_set = false;
-    if (!attr_set) {
+    int dev = 0;
+    if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
+    static PerDevice<> state;
+    if (!state.attr[dev]) {
         if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
         if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        attr_set = true;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.attr[dev] = true;
     }
     if (nbt == 1)
         hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL>), dim3((unsigned)grid), dim3(Cfg::kThreads),
