@@ -143,6 +143,56 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
                             void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
 /*
+ * Grouped variants (Section "Group-Gumbel-Max: Hierarchical Exact Sampling"; appendix algorithms
+ * "FlashSampling (parallel)" and "FlashSampling (sequential/online)").  The vocabulary is cut
+ * into groups of 128 * group_tiles consecutive ids (the last group may be shorter).  Stage 1 is
+ * the fused kernel of flash_sample_full; per group k it yields the local sample z_k (Gumbel-max
+ * inside the group, same per-id noise as the default path) and the group log-mass
+ * L_k = log sum_{i in group} exp(z_i).  The group is then chosen with independent noise:
+ *   FS_GROUPED_PARALLEL  k* = argmax_k (L_k - log(-log ubar_k)), lowest k on ties
+ *   FS_GROUPED_ONLINE    groups taken in ascending order with a running log-mass ell; group k
+ *                        replaces the running sample when u_k < exp(L_k - log(e^ell + e^L_k))
+ * and out_idx[b] = z_{k*}, out_lse[b] = log sum_k exp(L_k).  Zero-mass groups are skipped.  Both
+ * are exact samples of Cat(softmax(z_b)) but, unlike the default path, not the same draw as a
+ * Gumbel-max over the whole row.  ubar_k / u_k are word (k & 3) of
+ * Philox4x32-10(counter = (k >> 2, row word, 1 / 2, 0)) with the row's key, k the global group id
+ * (vocab_offset / (128 * group_tiles) + local group), mapped to (0,1) like the per-id noise.
+ *   group_tiles        >= 1; vocab_offset must be a multiple of 128 * group_tiles
+ *   out_lse            NULL, or fp32 [B]
+ *   group_log_mass     NULL, or fp32 [B, m], m = flash_sample_num_groups(V, group_tiles): L_k
+ *   group_sample       NULL, or int32 [B, m]: z_k as a global id, -1 for a zero-mass group
+ *                      (one (L_k, z_k) pair per group is what a vocabulary-sharded deployment
+ *                      exchanges between ranks, see flash_group_choose)
+ *   workspace          at least flash_sample_full_workspace_bytes(B, V) bytes, 256-byte aligned
+ * Other arguments as in flash_sample_full.  A row with no mass returns idx = -1, lse = -inf.
+ */
+#define FS_GROUPED_PARALLEL 0
+#define FS_GROUPED_ONLINE 1
+int flash_sample_num_groups(int V, int group_tiles);
+fs_status flash_sample_grouped(const void* hidden, const void* W, int B, int D, int V,
+                               const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                               int64_t row_offset, int32_t vocab_offset,
+                               const float* bias, const uint32_t* allowed, int64_t mask_stride_words,
+                               int group_tiles, int mode,
+                               int32_t* out_idx, float* out_lse,
+                               float* group_log_mass, int32_t* group_sample,
+                               void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
+ * The group choice alone, from per-group summaries: the coordinator step of the distributed
+ * variant (appendix algorithm "FlashSampling (distributed, tensor-parallel vocab)"), where group
+ * k is rank k's vocabulary shard and each rank contributes its shard log-mass and local sample.
+ *   group_log_mass [B, m] fp32   L_k (-inf for a zero-mass group)
+ *   group_sample   [B, m] int32  z_k as a global id (-1 for a zero-mass group)
+ *   group_offset   global id of the first group (the noise is indexed by global group ids)
+ *   out_idx [B] int32, out_lse NULL or [B] fp32
+ * Same choice rule and noise as flash_sample_grouped; no workspace.
+ */
+fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_sample, int B, int m,
+                             int mode, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                             int64_t group_offset, int32_t* out_idx, float* out_lse, void* stream);
+
+/*
  * Stage 1 of Alg. 1 alone: writes the candidate buffer
  *   cand_val [B, T] fp32, cand_idx [B, T] int32 (global vocabulary ids), T = flash_sample_num_tiles(V).
  * If `logits` is not NULL the kernel also stores the raw logits y = hidden W^T as fp32 [B, V]

@@ -29,6 +29,7 @@ FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E, FS_VARIANT_TILED2
 EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
+    "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
     "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
     "flash_sample_stream_probe",
@@ -77,6 +78,13 @@ def lib():
     L.flash_sample_full.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
                                     vp, vp, vp, vp, sz, vp, u32]
     L.flash_sample_full.restype = i32
+    L.flash_sample_num_groups.argtypes = [i32, i32]
+    L.flash_sample_num_groups.restype = i32
+    L.flash_sample_grouped.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
+                                       i32, i32, vp, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_grouped.restype = i32
+    L.flash_group_choose.argtypes = [vp, vp, i32, i32, i32, u64, vp, i64, i64, vp, vp, vp]
+    L.flash_group_choose.restype = i32
     L.flash_sample_stage1.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, u32]
     L.flash_sample_stage1.restype = i32
     L.flash_sample_stage2.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -215,6 +223,63 @@ def flash_sample_full(hidden, W, temperature, seed: int = 0, row_seeds=None, row
                                  _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_full")
     return out_idx, out_val, out_lse
+
+
+FS_GROUPED_PARALLEL, FS_GROUPED_ONLINE = 0, 1
+
+
+def flash_sample_num_groups(V: int, group_tiles: int) -> int:
+    return int(lib().flash_sample_num_groups(int(V), int(group_tiles)))
+
+
+def flash_sample_grouped(hidden, W, temperature, group_tiles: int = 1, mode: int = FS_GROUPED_PARALLEL,
+                         seed: int = 0, row_seeds=None, row_offset: int = 0, vocab_offset: int = 0,
+                         bias=None, allowed=None, want_groups: bool = False, out_idx=None, out_lse=None,
+                         workspace=None, stream=None, flags: int = 0):
+    """Grouped draw (groups of 128 * group_tiles ids).  Returns (out_idx, out_lse, group_log_mass,
+    group_sample); the last two are [B, m] tensors when want_groups, else None."""
+    import torch
+    B, D, V = _shapes(hidden, W)
+    if out_idx is None:
+        out_idx = torch.empty(B, dtype=torch.int32, device=hidden.device)
+    if out_lse is None:
+        out_lse = torch.empty(B, dtype=torch.float32, device=hidden.device)
+    gl = gs = None
+    if want_groups:
+        m = flash_sample_num_groups(V, group_tiles)
+        gl = torch.empty((B, m), dtype=torch.float32, device=hidden.device)
+        gs = torch.empty((B, m), dtype=torch.int32, device=hidden.device)
+    stride = 0
+    if allowed is not None and allowed.dim() == 2:
+        stride = allowed.shape[1]
+    need = flash_sample_full_workspace_bytes(B, V)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
+    st = lib().flash_sample_grouped(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+                                    _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(bias),
+                                    _ptr(allowed), int(stride), int(group_tiles), int(mode),
+                                    _ptr(out_idx), _ptr(out_lse), _ptr(gl), _ptr(gs), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+                                    int(flags))
+    _check(st, "flash_sample_grouped")
+    return out_idx, out_lse, gl, gs
+
+
+def flash_group_choose(group_log_mass, group_sample, mode: int = FS_GROUPED_PARALLEL, seed: int = 0,
+                       row_seeds=None, row_offset: int = 0, group_offset: int = 0, out_idx=None,
+                       out_lse=None, stream=None):
+    """Group choice from per-group (log-mass, sample) pairs, [B, m] each.  Returns (out_idx, out_lse)."""
+    import torch
+    B, m = group_log_mass.shape
+    if out_idx is None:
+        out_idx = torch.empty(B, dtype=torch.int32, device=group_log_mass.device)
+    if out_lse is None:
+        out_lse = torch.empty(B, dtype=torch.float32, device=group_log_mass.device)
+    st = lib().flash_group_choose(_ptr(group_log_mass), _ptr(group_sample), B, m, int(mode), int(seed),
+                                  _ptr(row_seeds), int(row_offset), int(group_offset), _ptr(out_idx),
+                                  _ptr(out_lse), _stream_ptr(stream))
+    _check(st, "flash_group_choose")
+    return out_idx, out_lse
 
 
 def flash_sample_stage1(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,

@@ -9,6 +9,7 @@
 #include "flash_sample.h"
 #include "fs_aux_kernels.hpp"
 #include "fs_common.hpp"
+#include "fs_grouped_kernels.hpp"
 #include "fs_stage1_splitk.hpp"
 #include "fs_stage1_tiled.hpp"
 #include "fs_stage1_tiled2.hpp"
@@ -424,6 +425,98 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
     if (s != FS_OK || !out_lse) return s;
     hipLaunchKernelGGL(lse_reduce_kernel, dim3(B), dim3(256), 0, st, p.lse_max, p.lse_sum, p.T, out_lse);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+int flash_sample_num_groups(int V, int group_tiles)
+{
+    if (V <= 0 || group_tiles <= 0) return 0;
+    return (num_tiles(V) + group_tiles - 1) / group_tiles;
+}
+
+namespace {
+
+fs_status launch_group_choose(const GroupInputs& in, int B, int m, int mode, uint64_t seed,
+                              const uint64_t* row_seeds, int64_t row_offset, int64_t group_offset,
+                              int32_t* out_idx, float* out_lse, float* group_log_mass,
+                              int32_t* group_sample, hipStream_t st)
+{
+    if (mode == FS_GROUPED_PARALLEL)
+        hipLaunchKernelGGL(group_choose_kernel<0>, dim3(B), dim3(256), 0, st, in, m, seed, row_seeds,
+                           row_offset, (uint32_t)group_offset, out_idx, out_lse, group_log_mass, group_sample);
+    else
+        hipLaunchKernelGGL(group_choose_kernel<1>, dim3(B), dim3(256), 0, st, in, m, seed, row_seeds,
+                           row_offset, (uint32_t)group_offset, out_idx, out_lse, group_log_mass, group_sample);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
+}  // namespace
+
+fs_status flash_sample_grouped(const void* hidden, const void* W, int B, int D, int V,
+                               const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                               int64_t row_offset, int32_t vocab_offset,
+                               const float* bias, const uint32_t* allowed, int64_t mask_stride_words,
+                               int group_tiles, int mode,
+                               int32_t* out_idx, float* out_lse,
+                               float* group_log_mass, int32_t* group_sample,
+                               void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK) return s;
+    if (group_tiles < 1 || (mode != FS_GROUPED_PARALLEL && mode != FS_GROUPED_ONLINE)) return FS_ERR_SHAPE;
+    const int64_t group_ids = (int64_t)kVocabTile * (int64_t)group_tiles;
+    if ((int64_t)vocab_offset % group_ids != 0) return FS_ERR_SHAPE;
+    if (B == 0) return FS_OK;
+    if (!temperature || !out_idx) return FS_ERR_NULL;
+    if (allowed && mask_stride_words != 0 && mask_stride_words < (int64_t)((V + 31) / 32)) return FS_ERR_SHAPE;
+    if (mask_stride_words < 0) return FS_ERR_SHAPE;
+    if (!aligned(out_idx, 4) || !aligned(out_lse, 4) || !aligned(temperature, 4) || !aligned(row_seeds, 8) ||
+        !aligned(bias, 16) || !aligned(allowed, 4) || !aligned(group_log_mass, 4) || !aligned(group_sample, 4))
+        return FS_ERR_ALIGN;
+    const size_t half = workspace_bytes(B, V);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < 2 * half) return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);
+    const Workspace ws2 = carve(static_cast<unsigned char*>(workspace) + half, B, V);
+    Stage1Params p;
+    p.H = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W);
+    p.B = B; p.D = D; p.V = V; p.T = num_tiles(V);
+    p.tau = temperature;
+    p.seed = seed; p.row_seeds = row_seeds;
+    p.row_offset = row_offset; p.vocab_offset = vocab_offset;
+    p.cand_val = ws.cand_val; p.cand_idx = ws.cand_idx; p.logits = nullptr;
+    p.bias = bias; p.allowed = allowed; p.mask_stride = mask_stride_words;
+    p.lse_max = ws2.cand_val;
+    p.lse_sum = reinterpret_cast<float*>(ws2.cand_idx);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = launch_stage1_full(p, flags, st);
+    if (s != FS_OK) return s;
+    GroupInputs in;
+    in.cand_val = ws.cand_val; in.cand_idx = ws.cand_idx;
+    in.lse_max = p.lse_max; in.lse_sum = p.lse_sum;
+    in.T = p.T; in.gt = group_tiles;
+    const int m = (p.T + group_tiles - 1) / group_tiles;
+    return launch_group_choose(in, B, m, mode, seed, row_seeds, row_offset, (int64_t)vocab_offset / group_ids,
+                               out_idx, out_lse, group_log_mass, group_sample, st);
+}
+
+fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_sample, int B, int m,
+                             int mode, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                             int64_t group_offset, int32_t* out_idx, float* out_lse, void* stream)
+{
+    if (B < 0 || m <= 0 || row_offset < 0 || group_offset < 0 || group_offset + (int64_t)m > 0xFFFFFFFFll)
+        return FS_ERR_SHAPE;
+    if (mode != FS_GROUPED_PARALLEL && mode != FS_GROUPED_ONLINE) return FS_ERR_SHAPE;
+    if (B == 0) return FS_OK;
+    if (!group_log_mass || !group_sample || !out_idx) return FS_ERR_NULL;
+    if (!aligned(group_log_mass, 4) || !aligned(group_sample, 4) || !aligned(out_idx, 4) ||
+        !aligned(out_lse, 4) || !aligned(row_seeds, 8))
+        return FS_ERR_ALIGN;
+    GroupInputs in;
+    in.cand_val = nullptr; in.cand_idx = group_sample;
+    in.lse_max = group_log_mass; in.lse_sum = nullptr;
+    in.T = m; in.gt = 1;
+    return launch_group_choose(in, B, m, mode, seed, row_seeds, row_offset, group_offset, out_idx, out_lse,
+                               nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 fs_status flash_lm_head_logits(const void* hidden, const void* W, int B, int D, int V,

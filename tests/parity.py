@@ -79,3 +79,89 @@ def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_
         else:
             v.failures.append((b, "wrong index", gi, i1, s1, s2, s_pick, tol))
     return v
+
+
+def lse_tol(tau, lse) -> float:
+    """Tolerance of a log-sum-exp of transformed logits: the per-logit budget carried through 1/tau,
+    plus fp32 rounding of the accumulation."""
+    a = abs(float(lse)) if np.isfinite(lse) else 0.0
+    return 2e-3 / min(float(tau), 1.0) + 1e-5 * a + 1e-4
+
+
+def judge_grouped(orc, mode, ref, H, W, tau, gpu_idx, gpu_lse, gpu_L, gpu_z, *, g, seed=0,
+                  row_seeds=None, row_offset=0, vocab_offset=0, bias=None, allowed_words=None) -> Verdict:
+    """Grouped variants against oracle.sample_grouped(...) (`ref`), row by row.
+
+    What is unique is compared exactly: the per-group local samples z_k (up to near-ties of the
+    in-group perturbed scores, judged like the main path) and, given those, the chosen group.
+    The group log-masses and the log-normaliser are compared to lse_tol.  A group decision that
+    sits within tolerance of its threshold in the oracle's fp64 arithmetic may go either way:
+      parallel: any group whose perturbed log-mass is within 1e-3 (1 + |max|) of the maximum;
+      online:   decision k is uncertain when |u_k - p_k| <= 1e-3 p_k / min(tau, 1) + 1e-6; the
+                valid answers are the last certainly accepted group and every uncertain group
+                after it.
+    """
+    B = H.shape[0]
+    m = ref["L"].shape[1]
+    v = Verdict()
+    for b in range(B):
+        v.rows += 1
+        t = float(tau[b])
+        seed_b = int(row_seeds[b]) if row_seeds is not None else int(seed)
+        row_word = row_offset + b
+        arow = None if allowed_words is None else (allowed_words if allowed_words.ndim == 1 else allowed_words[b])
+        bad = False
+        for k in range(m):
+            Lr, Lg = float(ref["L"][b, k]), float(gpu_L[b, k])
+            zr, zg = int(ref["zk"][b, k]), int(gpu_z[b, k])
+            if not np.isfinite(Lr):
+                if Lg != -np.inf or zg != -1:
+                    v.failures.append((b, k, "zero-mass group mismatch", Lg, zg)); bad = True
+                continue
+            if not abs(Lg - Lr) <= lse_tol(t, Lr):
+                v.failures.append((b, k, "group log-mass", Lg, Lr)); bad = True
+            if zg != zr:
+                s1, s2 = float(ref["s1"][b, k]), float(ref["s2"][b, k])
+                tol = 1e-3 * (1.0 + abs(s1))
+                lo = vocab_offset + k * g
+                in_group = lo <= zg < min(lo + g, vocab_offset + W.shape[0])
+                s_pick = orc.score_at_full(H, W, b, zg - vocab_offset, t, seed_b, row_word, zg, bias=bias,
+                                           allowed_row=arow) if in_group else -np.inf
+                if not (in_group and (s1 - s2) < tol and (s1 - s_pick) < tol):
+                    v.failures.append((b, k, "local sample", zg, zr, s1, s2)); bad = True
+        lr, lg = float(ref["lse"][b]), float(gpu_lse[b])
+        if np.isfinite(lr):
+            if not abs(lg - lr) <= lse_tol(t, lr):
+                v.failures.append((b, "log-normaliser", lg, lr)); bad = True
+        elif lg != -np.inf:
+            v.failures.append((b, "log-normaliser of an empty row", lg)); bad = True
+        gi, ri = int(gpu_idx[b]), int(ref["idx"][b])
+        if ri < 0 or gi < 0:
+            if gi != ri:
+                v.failures.append((b, "empty row mismatch", gi, ri)); bad = True
+            elif not bad:
+                v.exact += 1
+            continue
+        kg = (gi - vocab_offset) // g
+        if not (0 <= kg < m) or gi != int(gpu_z[b, kg]):
+            v.failures.append((b, "index is not the chosen group's local sample", gi, kg)); continue
+        kr = (ri - vocab_offset) // g
+        if mode == 0:
+            outer = ref["outer"][b]
+            top = float(outer[kr])
+            valid = {k for k in range(m) if top - float(outer[k]) < 1e-3 * (1.0 + abs(top))}
+        else:
+            u, p = ref["outer"][b], ref["p"][b]
+            tolk = 1e-3 * p / min(t, 1.0) + 1e-6
+            certain = [k for k in range(m) if np.isfinite(p[k]) and u[k] < p[k] - tolk[k]]
+            last = max(certain) if certain else -1
+            valid = {k for k in range(m) if np.isfinite(p[k]) and abs(u[k] - p[k]) <= tolk[k] and k > last}
+            if last >= 0:
+                valid.add(last)
+        if kg == kr and not bad:
+            v.exact += 1
+        elif kg in valid and not bad:
+            v.near_ties += 1
+        elif not bad:
+            v.failures.append((b, "wrong group", kg, kr, sorted(valid)[:8]))
+    return v

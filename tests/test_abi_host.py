@@ -97,6 +97,25 @@ def test_bad_arguments_are_rejected_before_any_device_work():
     assert L.flash_sample_stream_probe(None, FAKE, 24, None, None) == fs.FS_ERR_SHAPE
     assert L.flash_sample_stream_probe(None, None, 32, None, None) == fs.FS_ERR_NULL
 
+    # grouped variants
+    def gr(B=4, V=4096, vocab_offset=0, gt=2, mode=0, out_idx=FAKE, ws=FAKE + 0x100000, ws_bytes=1 << 20):
+        return L.flash_sample_grouped(FAKE, FAKE, B, 256, V, FAKE, 0, None, 0, vocab_offset, None, None, 0,
+                                      gt, mode, out_idx, None, None, None, ws, ws_bytes, None, 0)
+
+    assert gr(B=0) == fs.FS_OK
+    assert gr(gt=0) == fs.FS_ERR_SHAPE and gr(mode=2) == fs.FS_ERR_SHAPE
+    assert gr(vocab_offset=128) == fs.FS_ERR_SHAPE              # not a multiple of the group size
+    assert gr(vocab_offset=256, B=0) == fs.FS_OK
+    assert gr(out_idx=None) == fs.FS_ERR_NULL
+    assert gr(ws_bytes=fs.flash_sample_full_workspace_bytes(4, 4096) - 1) == fs.FS_ERR_WORKSPACE
+    assert fs.flash_sample_num_groups(4096, 1) == 32 and fs.flash_sample_num_groups(4097, 8) == 5
+    assert fs.flash_sample_num_groups(0, 1) == 0 and fs.flash_sample_num_groups(128, 0) == 0
+    assert L.flash_group_choose(FAKE, FAKE, 0, 8, 0, 0, None, 0, 0, FAKE, None, None) == fs.FS_OK
+    assert L.flash_group_choose(None, FAKE, 2, 8, 0, 0, None, 0, 0, FAKE, None, None) == fs.FS_ERR_NULL
+    assert L.flash_group_choose(FAKE, FAKE, 2, 0, 0, 0, None, 0, 0, FAKE, None, None) == fs.FS_ERR_SHAPE
+    assert L.flash_group_choose(FAKE, FAKE, 2, 8, 3, 0, None, 0, 0, FAKE, None, None) == fs.FS_ERR_SHAPE
+    assert L.flash_group_choose(FAKE, FAKE, 2, 8, 0, 0, None, 0, -1, FAKE, None, None) == fs.FS_ERR_SHAPE
+
 
 def test_io_model_matches_the_papers_predicted_overheads():
     # appendix table "Predicted vs. measured overhead of storing logits to HBM": 2B/D in percent
