@@ -195,9 +195,24 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 // 8 waves on 256 vocabulary rows with a 64- or 128-row batch tile, which halves the hidden-tile
 // re-reads per W byte (measured -10 % time at B = 64, -7 % at B = 128, -3 % at B = 256 against
 // the 128-row workgroups).  A 256 x 256 tile does not fit the register file at 2 waves per SIMD.
+// `shape` (1..5) forces one configuration (tuning aid); the forced shapes exist for the plain
+// epilogue only.
 template <bool FULL>
-fs_status launch_tiled2_auto(const Stage1Params& p, hipStream_t st)
+fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
 {
+    if constexpr (!FULL) {
+        switch (shape) {
+        case 0: break;
+        case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
+        case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
+        case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
+        case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
+        case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
+        default: return FS_ERR_UNSUPPORTED;
+        }
+    } else if (shape != 0) {
+        return FS_ERR_UNSUPPORTED;
+    }
     if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
     if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
@@ -216,7 +231,7 @@ fs_status launch_stage1_full(const Stage1Params& p, uint32_t flags, hipStream_t 
         const int nw = (ksteps + 31) / 32;
         return launch_splitk<SplitKCfg<32, 8, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
     }
-    return launch_tiled2_auto<true>(p, st);
+    return launch_tiled2_auto<true>(p, 0, st);
 }
 
 fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
@@ -252,7 +267,7 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     case FS_VARIANT_AUTO:
         if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_B);
         if (p.B <= 16) return launch_tiled_auto(p, st);
-        return launch_tiled2_auto<false>(p, st);
+        return launch_tiled2_auto<false>(p, 0, st);
     case FS_VARIANT_SPLITK_A:
     case FS_VARIANT_SPLITK_B:
     case FS_VARIANT_SPLITK_C:
@@ -262,7 +277,7 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     case FS_VARIANT_TILED:
         return launch_tiled_auto(p, st);
     case FS_VARIANT_TILED2:
-        return launch_tiled2_auto<false>(p, st);
+        return launch_tiled2_auto<false>(p, wgs_override, st);
     default:
         return FS_ERR_UNSUPPORTED;
     }

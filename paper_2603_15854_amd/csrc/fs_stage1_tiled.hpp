@@ -33,9 +33,18 @@ struct TiledCfg {
     static constexpr size_t lds_bytes() { return 2 * (size_t)(kWBytes + kHBytes) + 4 * kBatchTile * 8; }
 };
 
-__device__ __forceinline__ int tiled_slot(int row, int chunk)
+// Byte offset of 16-byte chunk c (0..7) of row r inside an LDS tile of 128-byte rows.
+// Rows are laid out in blocks of 16 (2 KB): rows r and r + 8 of a block share a 256-byte line
+// (row r & 7 picks the line, (r >> 3) & 1 the 128-byte half) and the chunk index is XORed with
+// r & 7.  An MFMA operand read (16 lanes = the 16 rows of a block, one chunk) then touches the 16
+// distinct 16-byte bank groups as  lane -> group 8 (r >> 3) + (c ^ (r & 7)).  Measured on gfx950
+// (ds_read_b128 at two waves per SIMD): this form runs at the rate of a linear read, while the
+// layout r * 128 + ((c ^ (r & 7) ^ (r >> 3 & 1)) << 4) -- also 16 distinct groups per 16 lanes --
+// takes 25 % longer per instruction and counts four bank-conflict cycles per read in
+// SQ_LDS_BANK_CONFLICT.  Row-contiguous ds_write_b128 parking showed no sensitivity to either.
+__device__ __forceinline__ int tile_off(int r, int c)
 {
-    return chunk ^ ((row & 7) ^ ((row >> 3) & 1));
+    return ((r >> 4) << 11) + ((r & 7) << 8) + (((r >> 3) & 1) << 7) + ((c ^ (r & 7)) << 4);
 }
 
 template <int NB>
@@ -93,13 +102,13 @@ stage1_tiled_kernel(const Stage1Params p)
 #pragma unroll
         for (int i = 0; i < Cfg::kWLoads; ++i) {
             const int r = ld_row + 32 * i;
-            *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = wst[i];
+            *reinterpret_cast<uint4*>(w_lds(buf) + tile_off(r, ld_chunk)) = wst[i];
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
             const int r = ld_row + 32 * i;
             if (r < BT)
-                *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = hst[i];
+                *reinterpret_cast<uint4*>(h_lds(buf) + tile_off(r, ld_chunk)) = hst[i];
         }
     };
 
@@ -124,13 +133,13 @@ stage1_tiled_kernel(const Stage1Params p)
             for (int i = 0; i < 2; ++i) {
                 const int r = wave * 32 + i * 16 + n;
                 a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                      w_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+                                                      w_lds(buf) + tile_off(r, c)));
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int r = nb * 16 + n;
                 const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                                h_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+                                                                h_lds(buf) + tile_off(r, c)));
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
                     acc[i][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b, acc[i][nb], 0, 0, 0);

@@ -21,7 +21,7 @@
 #include <type_traits>
 
 #include "fs_common.hpp"
-#include "fs_stage1_tiled.hpp"   // tiled_slot
+#include "fs_stage1_tiled.hpp"   // tile_off
 
 namespace fs {
 
@@ -140,14 +140,14 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             const int r = ld_row + RPP * i;
             uint4 v = wr[i];
             if (zero) v = make_uint4(0u, 0u, 0u, 0u);
-            *reinterpret_cast<uint4*>(w_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
+            *reinterpret_cast<uint4*>(w_lds(buf) + tile_off(r, ld_chunk)) = v;
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
             const int r = ld_row + RPP * i;
             uint4 v = hr[i];
             if (zero) v = make_uint4(0u, 0u, 0u, 0u);
-            *reinterpret_cast<uint4*>(h_lds(buf) + r * 128 + (tiled_slot(r, ld_chunk) << 4)) = v;
+            *reinterpret_cast<uint4*>(h_lds(buf) + tile_off(r, ld_chunk)) = v;
         }
     };
 
@@ -166,13 +166,13 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             for (int i = 0; i < RB; ++i) {
                 const int r = wm * (16 * RB) + i * 16 + n;
                 a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                      w_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+                                                      w_lds(buf) + tile_off(r, c)));
             }
 #pragma unroll
             for (int j = 0; j < CB; ++j) {
                 const int r = wn * (16 * CB) + j * 16 + n;
                 const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                                h_lds(buf) + r * 128 + (tiled_slot(r, c) << 4)));
+                                                                h_lds(buf) + tile_off(r, c)));
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b, acc[i][j], 0, 0, 0);
