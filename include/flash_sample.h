@@ -75,11 +75,12 @@ typedef enum {
 #define FS_VARIANT_SPLITK_C 4 /* 16 k-steps per wave (twice the waves), 8-k-step stages */
 #define FS_VARIANT_SPLITK_D 5 /* 32 k-steps per wave, 8-k-step stages, 4 register sets */
 #define FS_VARIANT_SPLITK_E 6 /* 32 k-steps per wave, 4-k-step stages, two workgroups per CU */
-#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled {128,256} x {32,64,128} tiles, two register sets
+#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled {128,256,512} x {32,64,128} tiles, two register sets
                                  in flight, XCD-paired batch tiles (default for B > 16) */
 /* bits 16..19: tuning aid.  Split-K variants: workgroups per compute unit (0 = automatic).
  * FS_VARIANT_TILED2: tile shape (vocabulary rows x batch rows, waves), 0 = automatic,
- * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4). */
+ * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4),
+ * 6 = 512x32 (8), 7 = 512x64 (8). */
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 #define FS_TUNE_TILE_SHAPE(n) FS_TUNE_WGS_PER_CU(n)
 

@@ -191,31 +191,62 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
-// B > 16: batch tile 32 (4 waves, 128 vocabulary rows per workgroup) up to B = 32; above that
-// 8 waves on 256 vocabulary rows with a 64- or 128-row batch tile, which halves the hidden-tile
-// re-reads per W byte (measured -10 % time at B = 64, -7 % at B = 128, -3 % at B = 256 against
-// the 128-row workgroups).  A 256 x 256 tile does not fit the register file at 2 waves per SIMD.
-// `shape` (1..5) forces one configuration (tuning aid); the forced shapes exist for the plain
-// epilogue only.
+// Tile shapes of the B > 16 kernel (vocabulary rows x batch rows per workgroup):
+//   1: 128 x 32, 4 waves, two workgroups per CU      6: 512 x 32, 8 waves, one workgroup per CU
+//   2: 256 x 64, 8 waves, one per CU                 7: 512 x 64, 8 waves, one per CU
+//   3: 256 x 128, 8 waves, one per CU                4, 5: 128 x 128 / 128 x 64, 4 waves (tuning only)
+// Every workgroup re-reads its hidden tile once per W tile, and the kernels are bound by the
+// bytes that enter the CUs, so more vocabulary rows per workgroup is better (measured at
+// D = 4096, V = 128256: B = 32 165 -> 161 us with 512 rows, B = 64 174 -> 168 us) -- as long as
+// the coarser tiles still fill the CUs evenly.  The choice below prices a shape as
+// rounds x workgroups per CU x (vocabulary rows + batch rows), rounds = ceil(workgroups /
+// resident slots): the last round of a 512-row grid can be mostly empty (V = 152064 gives 297
+// workgroups for 256 CUs), and then the finer shape wins.
+struct TileShape {
+    int id, vt, bt, per_cu;
+};
+
+int pick_tile_shape(int B, int V, int cus)
+{
+    static constexpr TileShape small[] = {{1, 128, 32, 2}, {6, 512, 32, 1}};
+    static constexpr TileShape medium[] = {{2, 256, 64, 1}, {7, 512, 64, 1}};
+    if (B > 64) return 3;
+    const TileShape* cand = B <= 32 ? small : medium;
+    int best = cand[0].id;
+    long long best_cost = -1;
+    for (int i = 0; i < 2; ++i) {
+        const long long wgs = (long long)((V + cand[i].vt - 1) / cand[i].vt) * ((B + cand[i].bt - 1) / cand[i].bt);
+        const long long slots = (long long)cus * cand[i].per_cu;
+        const long long rounds = (wgs + slots - 1) / slots;
+        const long long cost = rounds * cand[i].per_cu * (cand[i].vt + cand[i].bt);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = cand[i].id; }
+    }
+    return best;
+}
+
+// `shape` = 0 picks automatically; 1..7 forces one shape (tuning aid; shapes 4 and 5 exist for
+// the plain epilogue only).
 template <bool FULL>
 fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
 {
-    if constexpr (!FULL) {
-        switch (shape) {
-        case 0: break;
-        case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
-        case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
-        case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
-        case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
-        case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
-        default: return FS_ERR_UNSUPPORTED;
-        }
-    } else if (shape != 0) {
-        return FS_ERR_UNSUPPORTED;
+    if (shape == 0) {
+        const int cus = current_device_cus(nullptr);
+        if (cus <= 0) return FS_ERR_HIP;
+        shape = pick_tile_shape(p.B, p.V, cus);
     }
-    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
-    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
-    return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
+    switch (shape) {
+    case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
+    case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
+    case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
+    case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
+    case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, FULL>(p, st);
+    default: break;
+    }
+    if constexpr (!FULL) {
+        if (shape == 4) return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
+        if (shape == 5) return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
+    }
+    return FS_ERR_UNSUPPORTED;
 }
 
 // stage 1 with the full transform / log-normaliser epilogue: the default kernels only

@@ -25,7 +25,7 @@
 
 namespace fs {
 
-// VT: vocabulary rows per workgroup (128 or 256 = one or two candidate tiles); BT: batch rows;
+// VT: vocabulary rows per workgroup (128, 256 or 512 = one, two or four candidate tiles); BT: batch rows;
 // WM x WN waves (4 or 8); GS: K steps per W prefetch group; OCC: waves per SIMD asked for.
 template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2, int VT_ = kVocabTile>
 struct Tiled2Cfg {
@@ -45,8 +45,12 @@ struct Tiled2Cfg {
     static constexpr int kBufBytes = kWBytes + kHBytes;
     static constexpr int kRowsPerPass = kThreads / 8;    // rows one workgroup-wide load covers
     static constexpr int kWLoads = VT / kRowsPerPass;
-    static constexpr int kHLoads = BT / kRowsPerPass;
-    static_assert(kWLoads >= 1 && kHLoads >= 1 && BT % kRowsPerPass == 0, "tile rows per load pass");
+    // a batch tile with fewer rows than one load pass: every thread still loads (rows repeat
+    // modulo BT, so the loads stay unconditional) and only the first BT rows are parked
+    static constexpr bool kHPartial = BT < kRowsPerPass;
+    static constexpr int kHLoads = kHPartial ? 1 : BT / kRowsPerPass;
+    static_assert(kWLoads >= 1 && (kHPartial ? kRowsPerPass % BT == 0 : BT % kRowsPerPass == 0),
+                  "tile rows per load pass");
     static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8 * 2; }
 };
 
@@ -127,7 +131,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         k = over ? ld_chunk * 8 : k;
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
-            int r = b0 + ld_row + RPP * i;
+            int r = b0 + (Cfg::kHPartial ? (ld_row & (BT - 1)) : ld_row + RPP * i);
             r = r < B - 1 ? r : B - 1;
             hr[i] = ld_global_16B(p.H + (size_t)r * D + k);
         }
@@ -147,7 +151,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             const int r = ld_row + RPP * i;
             uint4 v = hr[i];
             if (zero) v = make_uint4(0u, 0u, 0u, 0u);
-            *reinterpret_cast<uint4*>(h_lds(buf) + tile_off(r, ld_chunk)) = v;
+            if (!Cfg::kHPartial || r < BT) *reinterpret_cast<uint4*>(h_lds(buf) + tile_off(r, ld_chunk)) = v;
         }
     };
 

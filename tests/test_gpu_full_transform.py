@@ -179,3 +179,24 @@ def test_full_entry_rejects_bad_arguments(fs):
     with pytest.raises(fs.FlashSampleError) as e:
         fs.flash_sample_full(H, W, tau, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert e.value.status == fs.FS_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("B", [24, 48])
+def test_full_transform_at_full_vocabulary_width(fs, orc, B):
+    # V = 128256 makes the launcher pick its 512-row tile shapes (one workgroup per CU);
+    # the hidden size is kept small so that the oracle finishes in seconds
+    D, V = 128, 128256
+    print(f"full transform, V={V}, B={B}", flush=True)
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=330 + B)
+    rng = np.random.default_rng(B)
+    tau = np.linspace(0.7, 1.4, B).astype(np.float32)
+    bias = rng.normal(0, 1.0, V).astype(np.float32)
+    allowed = rng.random(V) < 0.6
+    allowed[V - 1] = True
+    words = orc.pack_allowed(allowed)
+    ref = orc.sample_full(H, W, tau, seed=8, bias=bias, allowed_words=words)
+    gi, gv, gl = run_full(fs, H, W, tau, seed=8, bias=bias, words=words)
+    v = judge(orc, H, W, tau, gi, gv, ref, seed=8, bias=bias, allowed_words=words)
+    assert v.ok, (B, str(v), v.failures[:3])
+    for b in range(B):
+        assert abs(gl[b] - ref["lse"][b]) <= lse_tol(tau[b], ref["lse"][b])

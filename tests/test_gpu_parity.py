@@ -79,16 +79,17 @@ def test_noise_tap_matches_oracle_counter_layout(fs, orc):
 # ----------------------------------------------------------------------------- small shapes
 
 def _small_case(fs, orc, B, D, V, variant, data_seed, tau=None, seed=5, row_seeds=None,
-                row_offset=0, vocab_offset=0, scale=1.0):
+                row_offset=0, vocab_offset=0, scale=1.0, tune=0):
     H, W = wl.make_small(D=D, V=V, B=B, data_seed=data_seed, w_row_scale=scale)
     tau = np.linspace(0.6, 1.6, B).astype(np.float32) if tau is None else np.asarray(tau, np.float32)
     ref = orc.sample(H, W, tau, seed=seed, row_seeds=row_seeds, row_offset=row_offset,
                      vocab_offset=vocab_offset)
     gi, gv = run_fused(fs, to_device_bf16(H), to_device_bf16(W), tau, seed=seed, row_seeds=row_seeds,
-                       row_offset=row_offset, vocab_offset=vocab_offset, flags=fs.FS_VARIANT(variant))
+                       row_offset=row_offset, vocab_offset=vocab_offset,
+                       flags=fs.FS_VARIANT(variant) | fs.FS_TUNE_WGS_PER_CU(tune))
     v = judge(orc, H, W, tau, gi, gv, ref, seed=seed, row_seeds=row_seeds, row_offset=row_offset,
               vocab_offset=vocab_offset)
-    assert v.ok, (B, D, V, variant, str(v), v.failures[:3])
+    assert v.ok, (B, D, V, variant, tune, str(v), v.failures[:3])
     return v
 
 
@@ -152,6 +153,15 @@ def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
     B, D, V = shape
     for variant in (0, 3, 7):
         _small_case(fs, orc, B, D, V, variant, data_seed=70 + B)
+
+
+@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7])
+def test_every_tile_shape_of_the_tiled_kernel(fs, orc, tile_shape):
+    # the shapes the launcher can pick (128/256/512 vocabulary rows x 32/64/128 batch rows), each on
+    # ragged V, B smaller and larger than its batch tile, and a K tail (D % 64 != 0)
+    for B, D, V in [(20, 520, 1100), (70, 256, 3000), (150, 1032, 700), (33, 64, 513)]:
+        print(f"tile shape {tile_shape} B={B} D={D} V={V}", flush=True)
+        _small_case(fs, orc, B, D, V, 7, data_seed=140 + B, tune=tile_shape)
 
 
 def test_split_k_variants_refuse_what_they_cannot_run(fs):
