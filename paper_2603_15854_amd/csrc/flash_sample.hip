@@ -192,40 +192,36 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 }
 
 // Tile shapes of the B > 16 kernel (vocabulary rows x batch rows per workgroup):
-//   1: 128 x 32, 4 waves, two workgroups per CU      6: 512 x 32, 8 waves, one workgroup per CU
-//   2: 256 x 64, 8 waves, one per CU                 7: 512 x 64, 8 waves, one per CU
-//   3: 256 x 128, 8 waves, one per CU                4, 5: 128 x 128 / 128 x 64, 4 waves (tuning only)
-// Every workgroup re-reads its hidden tile once per W tile, and the kernels are bound by the
-// bytes that enter the CUs, so more vocabulary rows per workgroup is better (measured at
-// D = 4096, V = 128256: B = 32 165 -> 161 us with 512 rows, B = 64 174 -> 168 us) -- as long as
-// the coarser tiles still fill the CUs evenly.  The choice below prices a shape as
-// rounds x workgroups per CU x (vocabulary rows + batch rows), rounds = ceil(workgroups /
-// resident slots): the last round of a 512-row grid can be mostly empty (V = 152064 gives 297
-// workgroups for 256 CUs), and then the finer shape wins.
-struct TileShape {
-    int id, vt, bt, per_cu;
-};
+//   1: 128 x 32   4 waves, two workgroups per CU      5: 128 x 64   4 waves, two per CU
+//   2: 256 x 64   8 waves, one per CU                 6: 512 x 32   8 waves, one per CU
+//   3: 256 x 128  8 waves, one per CU                 7: 512 x 64   8 waves, one per CU
+//   4: 128 x 128  4 waves, two per CU                 8: 256 x 32   4 waves, two per CU
+// Every workgroup re-reads its hidden tile once per W tile and the kernels are bound by the bytes
+// that enter the CUs, so more vocabulary rows per workgroup is better -- as long as the coarser
+// grid still fills the CUs evenly.  Measured, fused call in us (D = 4096, V = 128256: 1002 tiles
+// of 128 rows | D = 3584, V = 152064: 1188 tiles, where 256- and 512-row grids leave the last
+// round mostly empty):
+//   B = 32:   shape 8 160 | 187    shape 6 161 | 230    shape 1 165-173 | 190
+//   B = 64:   shape 7 168 | 247    shape 5 170 | 190    shape 2 174 | 212
+//   B = 128:  shape 3 195 | 243    shape 4 217 | 236
+// Hence: 256 x 32 up to B = 32; above that the one-per-CU shape when its grid fills at least 90 %
+// of its last round, else the four-wave shape with two workgroups per CU, whose finer grid and
+// overlapped epilogues tolerate a ragged tail.
+bool fills_rounds(long long wgs, int cus)
+{
+    const long long rounds = (wgs + cus - 1) / cus;
+    return wgs * 10 >= rounds * cus * 9;
+}
 
 int pick_tile_shape(int B, int V, int cus)
 {
-    static constexpr TileShape small[] = {{1, 128, 32, 2}, {6, 512, 32, 1}};
-    static constexpr TileShape medium[] = {{2, 256, 64, 1}, {7, 512, 64, 1}};
-    if (B > 64) return 3;
-    const TileShape* cand = B <= 32 ? small : medium;
-    int best = cand[0].id;
-    long long best_cost = -1;
-    for (int i = 0; i < 2; ++i) {
-        const long long wgs = (long long)((V + cand[i].vt - 1) / cand[i].vt) * ((B + cand[i].bt - 1) / cand[i].bt);
-        const long long slots = (long long)cus * cand[i].per_cu;
-        const long long rounds = (wgs + slots - 1) / slots;
-        const long long cost = rounds * cand[i].per_cu * (cand[i].vt + cand[i].bt);
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = cand[i].id; }
-    }
-    return best;
+    if (B <= 32) return 8;
+    if (B <= 64) return fills_rounds((V + 511) / 512, cus) ? 7 : 5;
+    const long long nbt = (B + 127) / 128;
+    return fills_rounds((long long)((V + 255) / 256) * nbt, cus) ? 3 : 4;
 }
 
-// `shape` = 0 picks automatically; 1..7 forces one shape (tuning aid; shapes 4 and 5 exist for
-// the plain epilogue only).
+// `shape` = 0 picks automatically; 1..8 forces one shape (tuning aid).
 template <bool FULL>
 fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
 {
@@ -235,16 +231,17 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
         shape = pick_tile_shape(p.B, p.V, cus);
     }
     switch (shape) {
-    case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
-    case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
-    case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
+    case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
+    case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, FULL>(p, st);
+    case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, FULL>(p, st);
     default: break;
     }
-    if constexpr (!FULL) {
-        if (shape == 4) return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
-        if (shape == 5) return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
+    if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
+        if (shape == 1) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
+        if (shape == 2) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
+        if (shape == 6) return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
     }
     return FS_ERR_UNSUPPORTED;
 }

@@ -181,9 +181,9 @@ def test_full_entry_rejects_bad_arguments(fs):
     assert e.value.status == fs.FS_ERR_WORKSPACE
 
 
-@pytest.mark.parametrize("B", [24, 48])
+@pytest.mark.parametrize("B", [24, 48, 80])
 def test_full_transform_at_full_vocabulary_width(fs, orc, B):
-    # V = 128256 makes the launcher pick its 512-row tile shapes (one workgroup per CU);
+    # V = 128256 makes the launcher pick its one-workgroup-per-CU tile shapes (256 and 512 rows);
     # the hidden size is kept small so that the oracle finishes in seconds
     D, V = 128, 128256
     print(f"full transform, V={V}, B={B}", flush=True)
