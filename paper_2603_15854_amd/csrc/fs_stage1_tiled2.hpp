@@ -1,16 +1,16 @@
-// Stage 1 of Alg. 1 for B > 16: LDS-tiled matmul with the sampling epilogue, built so that two
-// (or more) workgroups are resident per compute unit.  While one workgroup runs its VALU-heavy
-// epilogue (Philox, logs, argmax) the other keeps the MFMA pipe and the HBM stream busy.
+// Stage 1 of Alg. 1 for B > 16: LDS-tiled matmul with the sampling epilogue.
 //
-// Workgroup: 4 waves as WM x WN; tile = 128 vocabulary ids x BT batch rows; wave tile =
-// (128/WM) x (BT/WN).  MFMA A operand = W rows (M = vocabulary), B operand = hidden rows
-// (N = batch), v_mfma_f32_16x16x32_bf16, fp32 accumulators.
+// Workgroup: 4 or 8 waves as WM x WN; tile = VT vocabulary ids (128, 256 or 512) x BT batch rows;
+// wave tile = (VT/WM) x (BT/WN).  MFMA A operand = W rows (M = vocabulary), B operand = hidden rows
+// (N = batch), v_mfma_f32_16x16x32_bf16, fp32 accumulators.  The four-wave shapes leave room for
+// two workgroups per compute unit, so that one workgroup's VALU-heavy epilogue (Philox, logs,
+// argmax) overlaps the other's main loop; the eight-wave shapes run one workgroup per compute
+// unit and re-read the hidden tile less often per W byte.
 //
 // K loop, 64 elements per step, two LDS buffers (steps k and k+1), one barrier per step.
 // Global loads run ahead of use in registers: the hidden tile two steps ahead, the W tile in
-// groups of GS steps (GS*128 contiguous bytes of every row are requested back to back, which
-// HBM serves better than isolated 128-byte pieces), two groups in flight.
-// LDS rows are 128 bytes, chunk c of row r in slot c ^ ((r & 7) ^ ((r >> 3) & 1)).
+// groups of GS steps (GS*128 contiguous bytes of every row are requested back to back), two
+// groups in flight.  LDS tiles have 128-byte rows placed by tile_off().
 //
 // When the batch needs several tiles (B > BT), the workgroups that share a W tile get dispatch
 // ids 8 apart: workgroups are dealt round-robin to the 8 XCDs, so they land on the same XCD at
