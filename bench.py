@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--no-sweep", action="store_true", help="skip the B = 1..256 sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-paper-shape", action="store_true",
+                    help="skip the D=8192, V=128256 legs that sit beside the paper's absolute kernel times")
     ap.add_argument("--variant", type=int, default=0, help="stage-1 kernel variant (0 = automatic)")
     ap.add_argument("--calibrate", type=int, default=0,
                     help="also launch N plain read and N plain copy kernels over a W-sized buffer "
@@ -209,6 +211,44 @@ def main() -> int:
             })
             del ss
         out["sweep"] = sweep
+
+    # ------------------------------------------------------------------ the paper's absolute-time shape
+    # The paper prints absolute kernel times only for D=8192, V=128256 (appendix table of
+    # tensor-parallel runtimes, TP=1 column; an 8 TB/s-class NVIDIA GPU, Triton kernel).  Same shape
+    # here, as context beside those figures: another machine's numbers, not a target.
+    if not args.no_sweep and not args.no_paper_shape:
+        w4 = wl.WORKLOADS["C4"]
+        W4 = to_device_bf16(wl.make_weights(w4))
+        paper_us = {16: (333.8, 385.0), 64: (344.1, 439.2), 256: (676.8, 669.7)}
+        rows = []
+        for Bq in (16, 64, 256):
+            q = dict(Hd=to_device_bf16(wl.make_hidden(w4, Bq)),
+                     tau=torch.from_numpy(wl.make_temperature(w4, Bq)).cuda(),
+                     ws=torch.empty(max(256, fs.flash_sample_workspace_bytes(Bq, w4.V)), dtype=torch.uint8, device="cuda"),
+                     oi=torch.empty(Bq, dtype=torch.int32, device="cuda"),
+                     ov=torch.empty(Bq, dtype=torch.float32, device="cuda"),
+                     lg=torch.empty((Bq, w4.V), dtype=torch.float32, device="cuda"))
+
+            def fused4(q):
+                fs.flash_sample_ex(q["Hd"], W4, q["tau"], seed=w4.seed, out_idx=q["oi"], out_val=q["ov"],
+                                   workspace=q["ws"], stream=stream)
+
+            def unfused4(q):
+                fs.flash_sample_unfused(q["Hd"], W4, q["tau"], seed=w4.seed, logits=q["lg"], out_idx=q["oi"],
+                                        out_val=q["ov"], workspace=q["ws"], stream=stream)
+
+            f_ms = timed(fused4, q, 50, 10)
+            u_ms = timed(unfused4, q, 50, 10)
+            rows.append({"B": Bq, "fused_us": round(f_ms * 1e3, 2), "unfused_us": round(u_ms * 1e3, 2),
+                         "paper_fused_us": paper_us[Bq][0], "paper_gumbel_on_stored_logits_us": paper_us[Bq][1]})
+            del q
+        out["paper_shape"] = {
+            "D": w4.D, "V": w4.V, "rows": rows,
+            "paper_numbers": "appendix table of tensor-parallel runtimes, TP=1 column: the paper's fused "
+                             "kernel and its FlashInfer Gumbel-max baseline on an 8 TB/s-class NVIDIA GPU; "
+                             "context only (other hardware, other software)",
+        }
+        del W4
 
     # ------------------------------------------------------------------ CPU oracle baseline
     if not args.no_cpu:
