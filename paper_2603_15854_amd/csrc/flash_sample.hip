@@ -204,9 +204,11 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   B = 32:   shape 8 160 | 187    shape 6 161 | 230    shape 1 165-173 | 190
 //   B = 64:   shape 7 168 | 247    shape 5 170 | 190    shape 2 174 | 212
 //   B = 128:  shape 3 195 | 243    shape 4 217 | 236
-// Hence: 256 x 32 up to B = 32; above that the one-per-CU shape when its grid fills at least 90 %
-// of its last round, else the four-wave shape with two workgroups per CU, whose finer grid and
-// overlapped epilogues tolerate a ragged tail.
+// and at D = 8192, V = 128256, B <= 16: shape 6 307 us, shape 8 315, shape 1 317 (the split-K
+// kernel with 64 k-steps per wave: 325-335).
+// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 256 x 128 above) when its
+// grid fills at least 90 % of its last round, else the four-wave shape with two workgroups per CU
+// (256 x 32, 128 x 64, 128 x 128), whose finer grid and overlapped epilogues tolerate a ragged tail.
 bool fills_rounds(long long wgs, int cus)
 {
     const long long rounds = (wgs + cus - 1) / cus;
@@ -215,7 +217,7 @@ bool fills_rounds(long long wgs, int cus)
 
 int pick_tile_shape(int B, int V, int cus)
 {
-    if (B <= 32) return 8;
+    if (B <= 32) return fills_rounds((V + 511) / 512, cus) ? 6 : 8;
     if (B <= 64) return fills_rounds((V + 511) / 512, cus) ? 7 : 5;
     const long long nbt = (B + 127) / 128;
     return fills_rounds((long long)((V + 255) / 256) * nbt, cus) ? 3 : 4;
@@ -234,6 +236,7 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
     case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
+    case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, FULL>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, FULL>(p, st);
     default: break;
@@ -241,7 +244,6 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
         if (shape == 1) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
         if (shape == 2) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
-        if (shape == 6) return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
     }
     return FS_ERR_UNSUPPORTED;
 }
@@ -251,11 +253,7 @@ fs_status launch_stage1_full(const Stage1Params& p, uint32_t flags, hipStream_t 
 {
     if (flags != FS_FLAG_NONE) return FS_ERR_UNSUPPORTED;
     const int ksteps = (p.D + 31) / 32;
-    if (p.B <= 16 && ksteps <= 64 * 4) {
-        if (ksteps > 32 * 4) {
-            const int nw = (ksteps + 63) / 64;
-            return launch_splitk<SplitKCfg<64, 16, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
-        }
+    if (p.B <= 16 && ksteps <= 32 * 4) {
         const int nw = (ksteps + 31) / 32;
         return launch_splitk<SplitKCfg<32, 8, 2, 4>, true>(p, (ksteps + nw - 1) / nw, nw, 0, st);
     }
@@ -293,8 +291,10 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     };
     switch (variant) {
     case FS_VARIANT_AUTO:
-        if (p.B <= 16 && ksteps <= 64 * 4) return splitk(FS_VARIANT_SPLITK_B);
-        if (p.B <= 16) return launch_tiled_auto(p, st);
+        // B <= 16: the split-K kernel while a wave's hidden slice fits 128 registers (D <= 4096);
+        // for wider hidden sizes the tiled kernel is faster (D = 8192: 307 us against 325-335 us
+        // for split-K with 64 k-steps per wave; D = 7168: 272 against 275-282)
+        if (p.B <= 16 && ksteps <= 32 * 4) return splitk(FS_VARIANT_SPLITK_B);
         return launch_tiled2_auto<false>(p, 0, st);
     case FS_VARIANT_SPLITK_A:
     case FS_VARIANT_SPLITK_B:
