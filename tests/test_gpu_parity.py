@@ -411,3 +411,36 @@ def test_config_c5_temperature_to_zero_is_argmax(fs, orc):
             checked += 1
     assert checked >= B // 2
     _full_config(fs, orc, "C5", B, tau=tau)     # and the general acceptance rule still holds
+
+
+def test_graph_capture_and_replay_matches_eager(fs, orc):
+    # The explicit entry points allocate nothing and launch only on the caller's stream, so a call
+    # can be recorded into a HIP graph (after one eager call, which does the per-kernel set-up).
+    # Every replay is checked against the eager result for the inputs it ran on.
+    for B, D, V in [(8, 1024, 5000), (48, 512, 3000)]:
+        H, W = wl.make_small(D=D, V=V, B=B, data_seed=600 + B)
+        Hd, Wd = to_device_bf16(H), to_device_bf16(W)
+        tau = torch.full((B,), 0.9, device="cuda")
+        ws = torch.empty(fs.flash_sample_full_workspace_bytes(B, V), dtype=torch.uint8, device="cuda")
+        oi = torch.empty(B, dtype=torch.int32, device="cuda")
+        ov = torch.empty(B, dtype=torch.float32, device="cuda")
+        ol = torch.empty(B, dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fs.flash_sample_full(Hd, Wd, tau, seed=3, out_idx=oi, out_val=ov, out_lse=ol, workspace=ws, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fs.flash_sample_full(Hd, Wd, tau, seed=3, out_idx=oi, out_val=ov, out_lse=ol, workspace=ws, stream=side)
+        for rep in range(3):
+            Hnew, _ = wl.make_small(D=D, V=8, B=B, data_seed=700 + rep)
+            Hd.copy_(to_device_bf16(Hnew))
+            e_i, e_v, e_l = fs.flash_sample_full(Hd, Wd, tau, seed=3)      # eager, fresh outputs
+            torch.cuda.synchronize()
+            oi.fill_(-7)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(oi, e_i), (B, rep)
+            assert torch.equal(ov, e_v) and torch.equal(ol, e_l), (B, rep)
