@@ -144,6 +144,18 @@ def make_small(D: int, V: int, B: int, data_seed: int, w_row_scale: float = 1.0)
     return H, W
 
 
+def quantize_e4m3(W_bits: np.ndarray):
+    """Input preparation for the FP8-weight path: bf16 weights [V, D] -> (codes uint8 [V, D],
+    scale float32 [V]) with one scale per row, scale = max|w| / 448 (448 = largest E4M3 value) and
+    round-to-nearest-even onto the OCP E4M3 grid.  The rounding is torch's float8_e4m3fn cast."""
+    import torch
+    Wf = torch.from_numpy(bf16_bits_to_f32(W_bits))
+    amax = Wf.abs().amax(dim=1).clamp_min(1e-30)
+    scale = (amax / 448.0).to(torch.float32)
+    q = (Wf / scale[:, None]).clamp(-448.0, 448.0).to(torch.float8_e4m3fn)
+    return q.view(torch.uint8).numpy().copy(), scale.numpy().copy()
+
+
 def to_device_bf16(bits: np.ndarray):
     """bf16 bit patterns (uint16) -> torch.bfloat16 tensor on the current GPU (a plain upload)."""
     import torch

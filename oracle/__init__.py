@@ -100,6 +100,19 @@ def lib():
     L.fso_score_at_full.restype = C.c_double
     L.fso_num_threads.argtypes = []
     L.fso_num_threads.restype = C.c_int
+    _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
+    L.fso_e4m3_to_double.argtypes = [C.c_uint8]
+    L.fso_e4m3_to_double.restype = C.c_double
+    L.fso_logit_w8.argtypes = [_u16p, _u8p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64]
+    L.fso_logit_w8.restype = C.c_double
+    L.fso_logits_w8.argtypes = [_u16p, _u8p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, _f64p]
+    L.fso_logits_w8.restype = C.c_int
+    L.fso_sample_w8.argtypes = [_u16p, _u8p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                                C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, _i32p, _f32p, _f64p, _i64p, _f64p]
+    L.fso_sample_w8.restype = C.c_int
+    L.fso_score_at_w8.argtypes = [_u16p, _u8p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                  C.c_uint64, C.c_int64, C.c_int64]
+    L.fso_score_at_w8.restype = C.c_double
     L.fso_group_word.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_uint32]
     L.fso_group_word.restype = C.c_uint32
     L.fso_group_stats.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_uint64, C.c_int64, C.c_int64,
@@ -322,6 +335,45 @@ def score_at_full(H, W, b_local, i_local, tau, seed, row, vocab_id, bias=None, a
     ar, ar_p = _opt_ptr(allowed_row, np.uint32)
     return float(lib().fso_score_at_full(H, W, H.shape[1], b_local, i_local, float(tau), seed, row,
                                          vocab_id, bb_p, ar_p))
+
+
+def e4m3_to_double(code: int) -> float:
+    return float(lib().fso_e4m3_to_double(int(code) & 0xFF))
+
+
+def logits_w8(H, W8, scale=None) -> np.ndarray:
+    B, D = H.shape
+    V = W8.shape[0]
+    sc, sc_p = _opt_ptr(scale, np.float32)
+    Y = np.empty((B, V), dtype=np.float64)
+    lib().fso_logits_w8(H, W8, sc_p, B, D, V, Y)
+    return Y
+
+
+def sample_w8(H, W8, scale, tau, seed: int = 0, row_seeds=None, row_offset: int = 0, row_ids=None,
+              vocab_offset: int = 0):
+    """Default path on FP8 (E4M3) weights with per-row scales.  Returns dict(idx, val, top1, idx2, top2)."""
+    B, D = H.shape
+    V = W8.shape[0]
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    sc, sc_p = _opt_ptr(scale, np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    ri, ri_p = _opt_ptr(row_ids, np.int64)
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    top1 = np.empty(B, dtype=np.float64)
+    idx2 = np.empty(B, dtype=np.int64)
+    top2 = np.empty(B, dtype=np.float64)
+    nt = lib().fso_sample_w8(H, W8, sc_p, B, D, V, tau, seed, rs_p, row_offset, ri_p, vocab_offset,
+                             out_idx, out_val, top1, idx2, top2)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, top1=top1, idx2=idx2, top2=top2, threads=nt)
+
+
+def score_at_w8(H, W8, scale, b_local, i_local, tau, seed, row, vocab_id) -> float:
+    sc, sc_p = _opt_ptr(scale, np.float32)
+    return float(lib().fso_score_at_w8(H, W8, sc_p, H.shape[1], b_local, i_local, float(tau), seed, row, vocab_id))
 
 
 GROUPED_PARALLEL, GROUPED_ONLINE = 0, 1

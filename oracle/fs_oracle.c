@@ -31,7 +31,8 @@
  *
  * The full transform (additive bias, temperature, -inf mask) and the log-normaliser
  * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below); the
- * grouped variants (parallel and online Group-Gumbel-Max) are the third (fso_group_word and below).
+ * grouped variants (parallel and online Group-Gumbel-Max) are the third (fso_group_word and below);
+ * FP8 (E4M3) weights with per-row scales are the fourth (fso_e4m3_to_double and below).
  *
  * NaN scores never win (the strict > comparison is false for NaN); a row with no
  * score > -inf returns idx = -1, val = -inf.
@@ -531,6 +532,81 @@ void fso_grouped_draw_counts(const double* z, int64_t V, int64_t g, int mode, ui
         for (int64_t i = 0; i < V; ++i) counts[i] += local[i];
         free(local);
     }
+}
+
+/* ------------------------------------------------------------------ FP8 weights */
+
+/*
+ * Lower-precision weights (Section "Limitations and Future Work": FP8 weights as the next byte
+ * saving in the bandwidth-bound regime).  This build's reading: W is stored as OCP FP8 E4M3
+ * ("e4m3fn": 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities, S.1111.111 = NaN,
+ * subnormals m/8 * 2^-6) with one fp32 scale per vocabulary row; the hidden states stay bf16:
+ *      y_i = scale_i * sum_d H[b,d] * e4m3(W8[i,d])
+ * Every e4m3 value is exactly representable in bf16, so the products are the same exact products
+ * as on the bf16 path; everything after y is unchanged.
+ */
+double fso_e4m3_to_double(uint8_t code)
+{
+    int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+double fso_logit_w8(const uint16_t* H, const uint8_t* W8, const float* scale, int64_t D, int64_t b, int64_t i)
+{
+    const uint16_t* h = H + b * D;
+    const uint8_t* w = W8 + i * D;
+    double acc = 0.0;
+    for (int64_t d = 0; d < D; ++d) acc += bf16_to_double(h[d]) * fso_e4m3_to_double(w[d]);
+    return scale ? (double)scale[i] * acc : acc;
+}
+
+int fso_logits_w8(const uint16_t* H, const uint8_t* W8, const float* scale, int64_t B, int64_t D, int64_t V,
+                  double* Y)
+{
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < V; ++i)
+        for (int64_t b = 0; b < B; ++b) Y[b * V + i] = fso_logit_w8(H, W8, scale, D, b, i);
+    return nthreads;
+}
+
+/* The default path on FP8 weights: i*_b ~ Cat(softmax(y_b / tau_b)), y as above. */
+int fso_sample_w8(const uint16_t* H, const uint8_t* W8, const float* scale, int64_t B, int64_t D, int64_t V,
+                  const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                  const int64_t* row_ids, int64_t vocab_offset, int32_t* out_idx, float* out_val,
+                  double* top1_val, int64_t* top2_idx, double* top2_val)
+{
+    if (B <= 0 || V <= 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits_w8(H, W8, scale, B, D, V, Y);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t i1, i2;
+        double m1, m2;
+        fso_gumbel_max_row(Y + b * V, V, (double)tau[b], row_seed(seed, row_seeds, b),
+                           row_id(row_ids, row_offset, b), vocab_offset, &i1, &m1, &i2, &m2);
+        out_idx[b] = (int32_t)i1;
+        if (out_val) out_val[b] = (float)m1;
+        if (top1_val) top1_val[b] = m1;
+        if (top2_idx) top2_idx[b] = i2;
+        if (top2_val) top2_val[b] = m2;
+    }
+    free(Y);
+    return nthreads;
+}
+
+double fso_score_at_w8(const uint16_t* H, const uint8_t* W8, const float* scale, int64_t D, int64_t b_local,
+                       int64_t i_local, double tau, uint64_t seed, int64_t row, int64_t vocab_id)
+{
+    return fso_logit_w8(H, W8, scale, D, b_local, i_local) / tau + fso_gumbel(seed, row, vocab_id);
 }
 
 /* ------------------------------------------------------------------ helpers for the pins */
