@@ -197,6 +197,31 @@ fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_s
                              int64_t group_offset, int32_t* out_idx, float* out_lse, void* stream);
 
 /*
+ * The same draw on FP8 weights (Section "Limitations and Future Work" names lower-precision
+ * weights as the next saving: W is the dominant 2 V D byte term of the bandwidth-bound regime).
+ * This library's reading: W8 [V, D] holds OCP FP8 E4M3 codes (one byte per element, row-major),
+ * w_scale [V] one fp32 scale per vocabulary row (NULL = all ones), hidden stays bf16:
+ *      y_{b,i} = w_scale_i * sum_d hidden[b,d] * e4m3(W8[i,d]),   i*_b ~ Cat(softmax(y_b / temperature_b))
+ * The codes are widened to bf16 on chip (exactly: every E4M3 value is a bf16 value) and contracted
+ * with the same bf16 MFMA as the bf16 path, so the arithmetic and its tolerance are those of
+ * flash_sample_ex on the decoded weights; noise, tie-breaking and outputs are identical.
+ *   W8, w_scale   device pointers, 16-byte aligned; D % 16 == 0
+ *   logits        NULL, or fp32 [B, V]: also store y (for tests and the comparison path)
+ *   workspace     at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
+ *   flags         FS_FLAG_NONE
+ * NaN codes (S.1111.111) propagate to NaN logits, which never win.
+ */
+fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_scale, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset, float* logits,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/* Debug tap: the on-chip E4M3 -> bf16 conversion applied to n codes (n % 8 == 0, codes 8-byte
+ * aligned), widened to fp32 out[n]. */
+fs_status flash_sample_e4m3_decode(const uint8_t* codes, int n, float* out, void* stream);
+
+/*
  * Stage 1 of Alg. 1 alone: writes the candidate buffer
  *   cand_val [B, T] fp32, cand_idx [B, T] int32 (global vocabulary ids), T = flash_sample_num_tiles(V).
  * If `logits` is not NULL the kernel also stores the raw logits y = hidden W^T as fp32 [B, V]

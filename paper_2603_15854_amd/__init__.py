@@ -30,6 +30,7 @@ EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
+    "flash_sample_w8", "flash_sample_e4m3_decode",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
     "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
     "flash_sample_stream_probe",
@@ -85,6 +86,10 @@ def lib():
     L.flash_sample_grouped.restype = i32
     L.flash_group_choose.argtypes = [vp, vp, i32, i32, i32, u64, vp, i64, i64, vp, vp, vp]
     L.flash_group_choose.restype = i32
+    L.flash_sample_w8.argtypes = [vp, vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_w8.restype = i32
+    L.flash_sample_e4m3_decode.argtypes = [vp, i32, vp, vp]
+    L.flash_sample_e4m3_decode.restype = i32
     L.flash_sample_stage1.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, u32]
     L.flash_sample_stage1.restype = i32
     L.flash_sample_stage2.argtypes = [vp, vp, i32, i32, vp, vp, vp]
@@ -223,6 +228,36 @@ def flash_sample_full(hidden, W, temperature, seed: int = 0, row_seeds=None, row
                                  _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_full")
     return out_idx, out_val, out_lse
+
+
+def flash_sample_w8(hidden, W8, w_scale, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                    vocab_offset: int = 0, logits=None, out_idx=None, out_val=None, workspace=None,
+                    stream=None, flags: int = 0):
+    """Draw on FP8 (E4M3) weights: W8 is a uint8 tensor [V, D], w_scale fp32 [V] or None."""
+    import torch
+    if hidden.dtype != torch.bfloat16 or W8.dtype != torch.uint8:
+        raise ValueError("hidden must be bfloat16 and W8 uint8")
+    if hidden.dim() != 2 or W8.dim() != 2 or hidden.shape[1] != W8.shape[1]:
+        raise ValueError("hidden must be [B, D] and W8 [V, D]")
+    B, D, V = hidden.shape[0], hidden.shape[1], W8.shape[0]
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
+    st = lib().flash_sample_w8(_ptr(hidden), _ptr(W8), _ptr(w_scale), B, D, V, _ptr(temperature), int(seed),
+                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+                               _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream),
+                               int(flags))
+    _check(st, "flash_sample_w8")
+    return out_idx, out_val
+
+
+def flash_sample_e4m3_decode(codes, out=None, stream=None):
+    import torch
+    n = codes.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _check(lib().flash_sample_e4m3_decode(_ptr(codes), n, _ptr(out), _stream_ptr(stream)),
+           "flash_sample_e4m3_decode")
+    return out
 
 
 FS_GROUPED_PARALLEL, FS_GROUPED_ONLINE = 0, 1

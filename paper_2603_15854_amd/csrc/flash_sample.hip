@@ -311,6 +311,17 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
     }
 }
 
+// stage 1 on FP8 (E4M3) weights: one-byte W elements, otherwise the kernels of the bf16 path
+fs_status launch_stage1_w8(const Stage1Params& p, hipStream_t st)
+{
+    const int ksteps = (p.D + 31) / 32;
+    if (p.B <= 16 && ksteps <= 32 * 4) {
+        const int nw = (ksteps + 31) / 32;
+        return launch_splitk<SplitKCfg<32, 16, 2, 4, 1>>(p, (ksteps + nw - 1) / nw, nw, 0, st);
+    }
+    return FS_ERR_UNSUPPORTED;
+}
+
 fs_status launch_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
                         int32_t* out_idx, float* out_val, hipStream_t st)
 {
@@ -560,6 +571,52 @@ fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_s
     in.T = m; in.gt = 1;
     return launch_group_choose(in, B, m, mode, seed, row_seeds, row_offset, group_offset, out_idx, out_lse,
                                nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_scale, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset, float* logits,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W8, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK) return s;
+    if ((D & 15) != 0) return FS_ERR_SHAPE;
+    if (flags != FS_FLAG_NONE) return FS_ERR_UNSUPPORTED;
+    if (B == 0) return FS_OK;
+    if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(temperature, 4) || !aligned(row_seeds, 8) ||
+        !aligned(w_scale, 16) || !aligned(logits, 16))
+        return FS_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < workspace_bytes(B, V))
+        return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);
+    Stage1Params p;
+    p.H = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W8);
+    p.B = B; p.D = D; p.V = V; p.T = num_tiles(V);
+    p.tau = temperature;
+    p.seed = seed; p.row_seeds = row_seeds;
+    p.row_offset = row_offset; p.vocab_offset = vocab_offset;
+    p.cand_val = ws.cand_val; p.cand_idx = ws.cand_idx; p.logits = logits;
+    p.bias = nullptr; p.allowed = nullptr; p.mask_stride = 0;
+    p.lse_max = nullptr; p.lse_sum = nullptr;
+    p.w_scale = w_scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = launch_stage1_w8(p, st);
+    if (s != FS_OK) return s;
+    return launch_stage2(ws.cand_val, ws.cand_idx, B, p.T, out_idx, out_val, st);
+}
+
+fs_status flash_sample_e4m3_decode(const uint8_t* codes, int n, float* out, void* stream)
+{
+    if (n < 0 || (n & 7) != 0) return FS_ERR_SHAPE;
+    if (n == 0) return FS_OK;
+    if (!codes || !out) return FS_ERR_NULL;
+    if (!aligned(codes, 8) || !aligned(out, 4)) return FS_ERR_ALIGN;
+    hipLaunchKernelGGL(e4m3_decode_kernel, dim3((n / 8 + 255) / 256), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t*>(codes), n / 8, out);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
 fs_status flash_lm_head_logits(const void* hidden, const void* W, int B, int D, int V,

@@ -150,6 +150,23 @@ gumbel_transform_kernel(const uint32_t* __restrict__ words, int n, float* __rest
     if (k < n) g_out[k] = gumbel_from_word(words[k]);
 }
 
+// Decode tap: the FP8 E4M3 -> bf16 conversion of the FP8-weight kernels on caller-given codes
+// (eight per thread, as in the kernels), widened to fp32.
+__global__ void __launch_bounds__(256)
+e4m3_decode_kernel(const uint32_t* __restrict__ codes, int n8, float* __restrict__ out)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= n8) return;
+    const bf16x8 v = e4m3x8_to_bf16x8(codes[2 * k], codes[2 * k + 1]);
+    const uint4 bits = __builtin_bit_cast(uint4, v);
+    const uint32_t w[4] = {bits.x, bits.y, bits.z, bits.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        out[8 * k + 2 * j] = __uint_as_float(w[j] << 16);
+        out[8 * k + 2 * j + 1] = __uint_as_float(w[j] & 0xFFFF0000u);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Streaming probe: grid-stride 128-bit reads (xor-folded so they cannot be dropped) or a copy.
 __global__ void __launch_bounds__(256)

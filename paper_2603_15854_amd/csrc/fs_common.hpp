@@ -33,6 +33,8 @@ struct Stage1Params {
     int64_t mask_stride;      // 32-bit words per batch row of `allowed`; 0 = one row for all
     float* lse_max;           // [B, T] running maximum of z per (row, tile), or nullptr
     float* lse_sum;           // [B, T] sum of exp(z - max) per (row, tile)
+    // FP8 weights (kernels instantiated for one-byte W elements only): W points at E4M3 codes
+    const float* w_scale = nullptr;   // [V] fp32 per-row scale of the logits, or nullptr (= 1)
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -238,6 +240,23 @@ __device__ __forceinline__ uint4 ld_global_16B_stream(const uint16_t* p)
 {
     const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Eight OCP FP8 E4M3 codes (two dwords, element k in byte k) -> eight bf16 values, exactly: every
+// E4M3 value is representable in bf16.  The hardware convert takes two codes per instruction.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi)
+{
+    const bf16x2_t a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+    const bf16x2_t b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+    const bf16x2_t c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+    const bf16x2_t d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+    uint4 v;
+    v.x = __builtin_bit_cast(uint32_t, a);
+    v.y = __builtin_bit_cast(uint32_t, b);
+    v.z = __builtin_bit_cast(uint32_t, c);
+    v.w = __builtin_bit_cast(uint32_t, d);
+    return __builtin_bit_cast(bf16x8, v);
 }
 
 }  // namespace fs

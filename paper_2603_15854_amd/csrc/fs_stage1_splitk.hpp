@@ -28,14 +28,17 @@ namespace fs {
 
 // KPW: k-steps per wave (register-resident hidden slice); SK: k-steps per LDS stage;
 // PF: stage register sets in flight; MAXW: upper bound on waves per workgroup (launch bounds).
-template <int KPW, int SK, int PF, int MAXW>
+// WB: bytes per W element (2 = bf16; 1 = FP8 E4M3 codes, converted to bf16 after the LDS hop).
+template <int KPW, int SK, int PF, int MAXW, int WB = 2>
 struct SplitKCfg {
+    static constexpr int kWB = WB;
+    static constexpr int kElemsPerChunk = 16 / WB;            // W elements in one 16-byte load
     static constexpr int kKPW = KPW;
     static constexpr int kSK = SK;
     static constexpr int kPF = PF;
     static constexpr int kMaxWaves = MAXW;
     static constexpr int kStagesPerRowTile = KPW / SK;
-    static constexpr int kRowBytes = SK * 64;                 // bytes of one row inside a stage
+    static constexpr int kRowBytes = SK * 32 * WB;            // bytes of one row inside a stage
     static constexpr int kStageBytes = 16 * kRowBytes;        // 16 rows
     static constexpr int kLanesPerRow = kRowBytes / 16;       // lanes that cover one row
     static constexpr int kRowsPerInstr = kWave / kLanesPerRow;
@@ -61,6 +64,7 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     constexpr int LPR = Cfg::kLanesPerRow;
     constexpr int RPI = Cfg::kRowsPerInstr;
     constexpr int ROWB = Cfg::kRowBytes;
+    constexpr int WB = Cfg::kWB, EPC = Cfg::kElemsPerChunk;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -97,7 +101,7 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     // stage load geometry of this lane
     const int ld_row = lane / LPR;           // row within one load instruction
     const int ld_chunk = lane % LPR;         // 16-byte chunk within the row
-    const int ld_k = kbeg + ld_chunk * 8;    // + h * SK * 32
+    const int ld_k = kbeg + ld_chunk * EPC;  // + h * SK * 32
 
     uint4 wreg[PF][NI];
 
@@ -114,13 +118,13 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     auto issue_loads = [&](uint4 (&dst)[NI], int rtl, int h) {
         const int rb = row_base(rtl);
         int k = ld_k + h * (SK * 32);
-        k = k < kend - 8 ? k : kend - 8;
-        const uint16_t* src = p.W + k;
+        k = k < kend - EPC ? k : kend - EPC;
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(p.W) + (size_t)k * WB;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             int row = rb + j * RPI + ld_row;
             row = row < V - 1 ? row : V - 1;
-            dst[j] = ld_global_16B_stream(src + (size_t)row * D);
+            dst[j] = ld_global_16B_stream(reinterpret_cast<const uint16_t*>(src + (size_t)row * D * WB));
         }
     };
 
@@ -168,10 +172,16 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
             if (active) {
 #pragma unroll
                 for (int s = 0; s < SK; ++s) {
-                    const int c = 4 * s + g;
-                    const uint4 a = *reinterpret_cast<const uint4*>(stage + rd_row_off + ((c ^ n) << 4));
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                                  hreg[h * SK + s], acc, 0, 0, 0);
+                    bf16x8 a;
+                    if constexpr (WB == 2) {
+                        const int c = 4 * s + g;
+                        a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stage + rd_row_off + ((c ^ n) << 4)));
+                    } else {   // 8 one-byte elements: half of chunk 2 s + g / 2
+                        const int c = 2 * s + (g >> 1);
+                        const uint2 q = *reinterpret_cast<const uint2*>(stage + rd_row_off + ((c ^ n) << 4) + ((g & 1) << 3));
+                        a = e4m3x8_to_bf16x8(q.x, q.y);
+                    }
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, hreg[h * SK + s], acc, 0, 0, 0);
                 }
             }
         }
@@ -189,6 +199,12 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
                 f32x4 y = partial[(r8 * nw) * 64 + lane];
                 for (int w = 1; w < nw; ++w) y += partial[(r8 * nw + w) * 64 + lane];
                 const int v0 = tile_row0 + r8 * 16 + 4 * g;   // local vocabulary row of y[0]
+                if constexpr (WB == 1) {   // per-row scale of the FP8 weights
+                    if (p.w_scale && v0 < V) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) y[j] *= p.w_scale[v0 + j < V ? v0 + j : V - 1];
+                    }
+                }
                 if (v0 < V && n < B) {
                     if (p.logits) {
                         float* dst = p.logits + (size_t)n * V + v0;

@@ -36,8 +36,9 @@ class Verdict:
 
 def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_ids=None,
           row_offset=0, vocab_offset=0, rows: Optional[Sequence[int]] = None,
-          bias=None, allowed_words=None) -> Verdict:
-    """ref = oracle.sample(...) over the rows being judged (same order as `rows`, which index
+          bias=None, allowed_words=None, w8_scale=False) -> Verdict:
+    """w8_scale: not False when W holds FP8 (E4M3) codes; then it is the per-row scale array or None.
+    ref = oracle.sample(...) over the rows being judged (same order as `rows`, which index
     into H / gpu_idx; default all rows).  row_ids gives the global row word per judged row."""
     B = H.shape[0]
     rows = list(range(B)) if rows is None else list(rows)
@@ -60,7 +61,9 @@ def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_
         if gi < vocab_offset or gi >= vocab_offset + W.shape[0]:
             v.failures.append((b, "index out of range", gi, gv))
             continue
-        if bias is None and allowed_words is None:
+        if w8_scale is not False:
+            s_pick = orc.score_at_w8(H, W, w8_scale, b, gi - vocab_offset, t, seed_b, row_word, gi)
+        elif bias is None and allowed_words is None:
             s_pick = orc.score_at(H, W, b, gi - vocab_offset, t, seed_b, row_word, gi)
         else:   # full transform: (y + bias) / tau, -inf when the id is masked for this row
             arow = None if allowed_words is None else (allowed_words if allowed_words.ndim == 1 else allowed_words[b])
