@@ -166,7 +166,7 @@ fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
     return launch_tiled<16>(p, st);
 }
 
-template <class Cfg, bool FULL = false>
+template <class Cfg, bool FULL = false, int WB = 2>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
@@ -177,16 +177,16 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
     static PerDevice<> state;
     if (!state.attr[dev]) {
-        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL, WB>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL, WB>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
         std::lock_guard<std::mutex> lk(g_mu);
         state.attr[dev] = true;
     }
     if (nbt == 1)
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL, WB>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            Cfg::lds_bytes(), st, p, nbt);
     else
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL, WB>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            Cfg::lds_bytes(), st, p, nbt);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
@@ -312,14 +312,43 @@ fs_status launch_stage1(const Stage1Params& p, uint32_t flags, hipStream_t st)
 }
 
 // stage 1 on FP8 (E4M3) weights: one-byte W elements, otherwise the kernels of the bf16 path
-fs_status launch_stage1_w8(const Stage1Params& p, hipStream_t st)
+fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st)
 {
+    if (flags & ~0x000FFF00u) return FS_ERR_UNSUPPORTED;
+    const int variant = (int)((flags >> 8) & 0xFFu);
+    const int wgs = (int)((flags >> 16) & 0xFu);
     const int ksteps = (p.D + 31) / 32;
     if (p.B <= 16 && ksteps <= 32 * 4) {
-        const int nw = (ksteps + 31) / 32;
-        return launch_splitk<SplitKCfg<32, 16, 2, 4, 1>>(p, (ksteps + nw - 1) / nw, nw, 0, st);
+        if (variant == 2 || variant == 3) {
+            const int nw = (ksteps + 15) / 16;
+            const int kpw = (ksteps + nw - 1) / nw;
+            if (variant == 2) return launch_splitk<SplitKCfg<16, 16, 1, 8, 1>>(p, kpw, nw, wgs, st);
+            return launch_splitk<SplitKCfg<16, 8, 2, 8, 1>>(p, kpw, nw, wgs, st);
+        }
+        if (variant == 1) {
+            const int nw = (ksteps + 31) / 32;
+            return launch_splitk<SplitKCfg<32, 16, 2, 4, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
+        }
+        if (variant == 0) {   // eight waves of 16 k-steps: 82 us against 90 us for four waves of 32
+            const int nw = (ksteps + 15) / 16;
+            return launch_splitk<SplitKCfg<16, 16, 1, 8, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
+        }
     }
-    return FS_ERR_UNSUPPORTED;
+    if (variant >= 1 && variant <= 3) return FS_ERR_UNSUPPORTED;   // a split-K form was asked for
+    // larger batches and wider hidden sizes: the tiled kernel, shapes chosen as for bf16
+    const int cus = current_device_cus(nullptr);
+    if (cus <= 0) return FS_ERR_HIP;
+    switch (variant >= 4 ? variant - 3 : pick_tile_shape(p.B, p.V, cus)) {
+    // a K step covers only 64 bytes of a row here, half a cache line: the W prefetch groups are
+    // twice as long as on the bf16 path, so that both halves of a line are requested back to back
+    case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 2, 2, 256>, false, 1>(p, st);
+    case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 4, 2>, false, 1>(p, st);
+    case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 4, 2>, false, 1>(p, st);
+    case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 2, 1, 512>, false, 1>(p, st);
+    case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 1, 512>, false, 1>(p, st);
+    case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 2, 2, 256>, false, 1>(p, st);
+    default: return FS_ERR_UNSUPPORTED;
+    }
 }
 
 fs_status launch_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
@@ -582,7 +611,6 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
     fs_status s = check_problem(hidden, W8, B, D, V, row_offset, vocab_offset);
     if (s != FS_OK) return s;
     if ((D & 15) != 0) return FS_ERR_SHAPE;
-    if (flags != FS_FLAG_NONE) return FS_ERR_UNSUPPORTED;
     if (B == 0) return FS_OK;
     if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
     if (!aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(temperature, 4) || !aligned(row_seeds, 8) ||
@@ -603,7 +631,7 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
     p.lse_max = nullptr; p.lse_sum = nullptr;
     p.w_scale = w_scale;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    s = launch_stage1_w8(p, st);
+    s = launch_stage1_w8(p, flags, st);
     if (s != FS_OK) return s;
     return launch_stage2(ws.cand_val, ws.cand_idx, B, p.T, out_idx, out_val, st);
 }

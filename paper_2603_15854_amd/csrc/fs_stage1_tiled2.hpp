@@ -54,12 +54,20 @@ struct Tiled2Cfg {
     static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8 * 2; }
 };
 
-template <class Cfg, bool STREAM_W, bool FULL = false>
+// WB: bytes per W element.  2 = bf16.  1 = FP8 E4M3 codes: a 16-byte load then carries 16
+// elements (four loads cover the 64 elements of a row and K step), the codes are widened to bf16
+// when the step is parked, and LDS and the MFMA path see the same bf16 tiles as on the bf16 path.
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
     constexpr int KS = Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
+    constexpr int WEPC = 16 / WB;                    // W elements per 16-byte load
+    constexpr int WCH = KS / WEPC;                   // loads per W row and K step (8 or 4)
+    constexpr int WRPP = Cfg::kThreads / WCH;        // W rows one workgroup-wide load covers
+    constexpr int NWL = VT / WRPP;                   // W loads per thread and K step
+    static_assert(VT % WRPP == 0 && NWL >= 1, "W tile rows per load pass");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
@@ -97,7 +105,9 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 
     const int ld_chunk = tid & 7;
     const int ld_row = tid >> 3;   // 0..RPP-1
-    uint4 wst[2][GS][Cfg::kWLoads];   // two groups of GS steps
+    const int wld_chunk = tid % WCH;
+    const int wld_row = tid / WCH;   // 0..WRPP-1
+    uint4 wst[2][GS][NWL];           // two groups of GS steps
     uint4 hst[2][Cfg::kHLoads];       // two steps
 
     // Every load of the K loop is unconditional, so the compiler can count the loads in flight and
@@ -106,21 +116,22 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     // output row/column depends on its own operand row only); a prefetch that runs past the end
     // of K reads one fixed cache line; a chunk past D inside the last step is zeroed when parked.
     const bool k_ragged = (D & (KS - 1)) != 0;
-    auto fetch_w = [&](uint4 (&wr)[Cfg::kWLoads], int k0) {
+    auto fetch_w = [&](uint4 (&wr)[NWL], int k0) {
         const bool over = k0 >= D;                          // uniform
-        int k = k0 + ld_chunk * 8;
-        k = k < D - 8 ? k : D - 8;
-        k = over ? ld_chunk * 8 : k;
+        int k = k0 + wld_chunk * WEPC;
+        k = k < D - WEPC ? k : D - WEPC;
+        k = over ? wld_chunk * WEPC : k;
 #pragma unroll
-        for (int i = 0; i < Cfg::kWLoads; ++i) {
-            int row = tile_row0 + ld_row + RPP * i;
+        for (int i = 0; i < NWL; ++i) {
+            int row = tile_row0 + wld_row + WRPP * i;
             row = row < V - 1 ? row : V - 1;
             row = over ? tile_row0 : row;
-            const uint16_t* src = p.W + (size_t)row * D + k;
+            const uint16_t* src = reinterpret_cast<const uint16_t*>(
+                reinterpret_cast<const unsigned char*>(p.W) + ((size_t)row * D + k) * WB);
             wr[i] = STREAM_W ? ld_global_16B_stream(src) : ld_global_16B(src);
         }
     };
-    auto fetch_w_group = [&](uint4 (&grp)[GS][Cfg::kWLoads], int group) {
+    auto fetch_w_group = [&](uint4 (&grp)[GS][NWL], int group) {
 #pragma unroll
         for (int s = 0; s < GS; ++s) fetch_w(grp[s], kmap(group * GS + s) * KS);
     };
@@ -137,14 +148,20 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
     };
     // park K step `step` (registers -> LDS buffer buf)
-    auto park = [&](const uint4 (&wr)[Cfg::kWLoads], const uint4 (&hr)[Cfg::kHLoads], int buf, int step) {
+    auto park = [&](const uint4 (&wr)[NWL], const uint4 (&hr)[Cfg::kHLoads], int buf, int step) {
         const bool zero = k_ragged && (step * KS + ld_chunk * 8 >= D);   // only in the last step
+        const bool wzero = k_ragged && (step * KS + wld_chunk * WEPC >= D);
 #pragma unroll
-        for (int i = 0; i < Cfg::kWLoads; ++i) {
-            const int r = ld_row + RPP * i;
+        for (int i = 0; i < NWL; ++i) {
+            const int r = wld_row + WRPP * i;
             uint4 v = wr[i];
-            if (zero) v = make_uint4(0u, 0u, 0u, 0u);
-            *reinterpret_cast<uint4*>(w_lds(buf) + tile_off(r, ld_chunk)) = v;
+            if (wzero) v = make_uint4(0u, 0u, 0u, 0u);
+            if constexpr (WB == 2) {
+                *reinterpret_cast<uint4*>(w_lds(buf) + tile_off(r, wld_chunk)) = v;
+            } else {   // 16 codes -> two bf16 chunks
+                *reinterpret_cast<bf16x8*>(w_lds(buf) + tile_off(r, 2 * wld_chunk)) = e4m3x8_to_bf16x8(v.x, v.y);
+                *reinterpret_cast<bf16x8*>(w_lds(buf) + tile_off(r, 2 * wld_chunk + 1)) = e4m3x8_to_bf16x8(v.z, v.w);
+            }
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kHLoads; ++i) {
@@ -230,8 +247,14 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             if (p.cand_val) repi = make_row_epi<FULL>(p, b);
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
-                const f32x4 y = acc[i][j];
+                f32x4 y = acc[i][j];
                 const int v0 = tile_row0 + wm * (16 * RB) + i * 16 + 4 * g;
+                if constexpr (WB == 1) {   // per-row scale of the FP8 weights
+                    if (p.w_scale && v0 < V) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) y[q] *= p.w_scale[v0 + q < V ? v0 + q : V - 1];
+                    }
+                }
                 if (v0 < V) {
                     if (p.logits) {
                         float* dst = p.logits + (size_t)b * V + v0;

@@ -97,6 +97,19 @@ def test_bad_arguments_are_rejected_before_any_device_work():
     assert L.flash_sample_stream_probe(None, FAKE, 24, None, None) == fs.FS_ERR_SHAPE
     assert L.flash_sample_stream_probe(None, None, 32, None, None) == fs.FS_ERR_NULL
 
+    # FP8 weights
+    def w8(B=4, D=256, out_idx=FAKE, ws=FAKE + 0x100000, flags=0):
+        return L.flash_sample_w8(FAKE, FAKE, None, B, D, 4096, FAKE, 0, None, 0, 0, None, out_idx, FAKE,
+                                 ws, 1 << 20, None, flags)
+
+    assert w8(B=0) == fs.FS_OK
+    assert w8(D=248) == fs.FS_ERR_SHAPE                         # D % 16 != 0
+    assert w8(out_idx=None) == fs.FS_ERR_NULL
+    assert w8(ws=None) == fs.FS_ERR_WORKSPACE
+    assert L.flash_sample_e4m3_decode(FAKE, 12, FAKE, None) == fs.FS_ERR_SHAPE
+    assert L.flash_sample_e4m3_decode(None, 16, FAKE, None) == fs.FS_ERR_NULL
+    assert L.flash_sample_e4m3_decode(FAKE, 0, None, None) == fs.FS_OK
+
     # grouped variants
     def gr(B=4, V=4096, vocab_offset=0, gt=2, mode=0, out_idx=FAKE, ws=FAKE + 0x100000, ws_bytes=1 << 20):
         return L.flash_sample_grouped(FAKE, FAKE, B, 256, V, FAKE, 0, None, 0, vocab_offset, None, None, 0,
