@@ -196,6 +196,7 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   2: 256 x 64   8 waves, one per CU                 6: 512 x 32   8 waves, one per CU
 //   3: 256 x 128  8 waves, one per CU                 7: 512 x 64   8 waves, one per CU
 //   4: 128 x 128  4 waves, two per CU                 8: 256 x 32   4 waves, two per CU
+//   9: 256 x 256  8 waves, one per CU, one register set of prefetch (accumulators take 128 VGPRs)
 // Every workgroup re-reads its hidden tile once per W tile and the kernels are bound by the bytes
 // that enter the CUs, so more vocabulary rows per workgroup is better -- as long as the coarser
 // grid still fills the CUs evenly.  Measured, fused call in us (D = 4096, V = 128256: 1002 tiles
@@ -204,9 +205,11 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   B = 32:   shape 8 160 | 187    shape 6 161 | 230    shape 1 165-173 | 190
 //   B = 64:   shape 7 168 | 247    shape 5 170 | 190    shape 2 174 | 212
 //   B = 128:  shape 3 195 | 243    shape 4 217 | 236
+//   B = 256:  shape 9 309          shape 3 376          (D = 8192: 584 against 699)
 // and at D = 8192, V = 128256, B <= 16: shape 6 307 us, shape 8 315, shape 1 317 (the split-K
 // kernel with 64 k-steps per wave: 325-335).
-// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 256 x 128 above) when its
+// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 256 x 128 up to 128,
+// 256 x 256 above, which reads W once instead of once per 128 batch rows) when its
 // grid fills at least 90 % of its last round, else the four-wave shape with two workgroups per CU
 // (256 x 32, 128 x 64, 128 x 128), whose finer grid and overlapped epilogues tolerate a ragged tail.
 bool fills_rounds(long long wgs, int cus)
@@ -219,6 +222,7 @@ int pick_tile_shape(int B, int V, int cus)
 {
     if (B <= 32) return fills_rounds((V + 511) / 512, cus) ? 6 : 8;
     if (B <= 64) return fills_rounds((V + 511) / 512, cus) ? 7 : 5;
+    if (B > 128 && fills_rounds((long long)((V + 255) / 256) * ((B + 255) / 256), cus)) return 9;
     const long long nbt = (B + 127) / 128;
     return fills_rounds((long long)((V + 255) / 256) * nbt, cus) ? 3 : 4;
 }
@@ -239,9 +243,11 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, FULL>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, FULL>(p, st);
+    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 1, 2, 256, 1>, FULL>(p, st);
     default: break;
     }
     if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
+
         if (shape == 1) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
         if (shape == 2) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     }
@@ -347,6 +353,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 2, 1, 512>, false, 1>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 1, 512>, false, 1>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 2, 2, 256>, false, 1>(p, st);
+    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 2, 2, 256, 1>, false, 1>(p, st);
     default: return FS_ERR_UNSUPPORTED;
     }
 }

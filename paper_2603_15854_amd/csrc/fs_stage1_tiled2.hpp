@@ -27,9 +27,12 @@ namespace fs {
 
 // VT: vocabulary rows per workgroup (128, 256 or 512 = one, two or four candidate tiles); BT: batch rows;
 // WM x WN waves (4 or 8); GS: K steps per W prefetch group; OCC: waves per SIMD asked for.
-template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2, int VT_ = kVocabTile>
+// NSET: register sets of prefetched loads (2: hidden two steps and W two groups ahead; 1: one
+// step / one group ahead, for the tile shapes whose accumulators leave no room for more).
+template <int BT_, int WM_, int WN_, int GS_, int OCC_ = 2, int VT_ = kVocabTile, int NSET_ = 2>
 struct Tiled2Cfg {
-    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_, OCC = OCC_, VT = VT_;
+    static constexpr int BT = BT_, WM = WM_, WN = WN_, GS = GS_, OCC = OCC_, VT = VT_, NSET = NSET_;
+    static_assert(NSET_ == 1 || NSET_ == 2, "one or two prefetch register sets");
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
     static_assert(kWaves == 4 || kWaves == 8, "four or eight waves per workgroup");
@@ -107,8 +110,9 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int ld_row = tid >> 3;   // 0..RPP-1
     const int wld_chunk = tid % WCH;
     const int wld_row = tid / WCH;   // 0..WRPP-1
-    uint4 wst[2][GS][NWL];           // two groups of GS steps
-    uint4 hst[2][Cfg::kHLoads];       // two steps
+    constexpr int NSET = Cfg::NSET;
+    uint4 wst[NSET][GS][NWL];        // NSET groups of GS steps
+    uint4 hst[NSET][Cfg::kHLoads];   // NSET steps
 
     // Every load of the K loop is unconditional, so the compiler can count the loads in flight and
     // wait for exactly the step it parks (s_waitcnt vmcnt(N)) instead of draining the prefetch:
@@ -204,12 +208,12 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     // prologue: W groups 0 and 1 and hidden steps 0 and 1 in flight; step 0 parked
     // (fetches past the end of K read one fixed cache line)
     fetch_w_group(wst[0], 0);
-    fetch_w_group(wst[1], 1);
+    if constexpr (NSET == 2) fetch_w_group(wst[1], 1);
     fetch_h(hst[0], kmap(0) * KS);
-    fetch_h(hst[1], kmap(1) * KS);
+    if constexpr (NSET == 2) fetch_h(hst[1], kmap(1) * KS);
     park(wst[0][0], hst[0], 0, kmap(0));
-    fetch_h(hst[0], kmap(2) * KS);
-    if (GS == 1) fetch_w_group(wst[0], 2);
+    fetch_h(hst[0], kmap(NSET) * KS);
+    if (GS == 1) fetch_w_group(wst[0], NSET);
     __syncthreads();
     // One body = 2*GS steps, after which the register sets are back in their starting roles.
     // Full bodies run without any condition (parking a step past the end only fills the LDS
@@ -219,11 +223,12 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         for (int u = 0; u < 2 * GS; ++u) {
             const int t = base + u;                 // step computed now, from LDS buffer u & 1
             if (!decltype(guarded)::value || t < nk) {
-                const int nset = ((u + 1) / GS) & 1;   // register set and slot of step t + 1
+                const int nset = NSET == 2 ? ((u + 1) / GS) & 1 : 0;   // register set and slot of step t + 1
+                const int hset = NSET == 2 ? (u + 1) & 1 : 0;
                 const int nslot = (u + 1) % GS;
-                park(wst[nset][nslot], hst[(u + 1) & 1], (u + 1) & 1, kmap(t + 1));
-                fetch_h(hst[(u + 1) & 1], kmap(t + 3) * KS);
-                if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + 2);   // set is free again
+                park(wst[nset][nslot], hst[hset], (u + 1) & 1, kmap(t + 1));
+                fetch_h(hst[hset], kmap(t + 1 + NSET) * KS);
+                if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + NSET);   // set is free again
                 compute(u & 1);
                 __syncthreads();
             }

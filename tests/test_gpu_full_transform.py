@@ -181,7 +181,7 @@ def test_full_entry_rejects_bad_arguments(fs):
     assert e.value.status == fs.FS_ERR_WORKSPACE
 
 
-@pytest.mark.parametrize("B", [24, 48, 80])
+@pytest.mark.parametrize("B", [24, 48, 80, 140])
 def test_full_transform_at_full_vocabulary_width(fs, orc, B):
     # V = 128256 makes the launcher pick its one-workgroup-per-CU tile shapes (256 and 512 rows);
     # the hidden size is kept small so that the oracle finishes in seconds
