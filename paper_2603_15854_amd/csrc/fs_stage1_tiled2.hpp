@@ -54,7 +54,9 @@ struct Tiled2Cfg {
     static constexpr int kHLoads = kHPartial ? 1 : BT / kRowsPerPass;
     static_assert(kWLoads >= 1 && (kHPartial ? kRowsPerPass % BT == 0 : BT % kRowsPerPass == 0),
                   "tile rows per load pass");
-    static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes + (size_t)WM * BT * 8 * 2; }
+    // the per-wave candidate / log-sum-exp scratch of the epilogue reuses the tile buffers
+    static_assert((size_t)WM * BT * 8 * 2 <= 2 * (size_t)kBufBytes, "epilogue scratch fits the tile buffers");
+    static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes; }
 };
 
 // WB: bytes per W element.  2 = bf16.  1 = FP8 E4M3 codes: a 16-byte load then carries 16
@@ -75,7 +77,9 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
     auto h_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes + Cfg::kWBytes; };
-    float2* wave_cand = reinterpret_cast<float2*>(smem + 2 * Cfg::kBufBytes);   // [WM][BT]
+    // epilogue scratch, aliased onto the tile buffers: first written after the barrier that ends
+    // the last K step, when no wave reads or parks tiles any more
+    float2* wave_cand = reinterpret_cast<float2*>(smem);                        // [WM][BT]
     float2* wave_lse = wave_cand + WM * BT;                                    // [WM][BT]
 
     const int tid = threadIdx.x;
