@@ -340,6 +340,11 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
             return launch_splitk<SplitKCfg<16, 16, 1, 8, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
         }
     }
+    if (p.B <= 16 && ksteps <= 32 * 8 && (variant == 0 || variant == 1)) {
+        // wide hidden sizes: eight waves of 32 k-steps, one register set of prefetch
+        const int nw = (ksteps + 31) / 32;
+        return launch_splitk<SplitKCfg<32, 16, 1, 8, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
+    }
     if (variant >= 1 && variant <= 3) return FS_ERR_UNSUPPORTED;   // a split-K form was asked for
     // larger batches and wider hidden sizes: the tiled kernel, shapes chosen as for bf16
     const int cus = current_device_cus(nullptr);
