@@ -166,9 +166,12 @@ fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
     return launch_tiled<16>(p, st);
 }
 
-template <class Cfg, bool FULL = false, int WB = 2>
+template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
+    // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles
+    constexpr size_t kLds = 2 * ((size_t)Cfg::kWBytes + (WCODES ? 2 : 1) * (size_t)Cfg::kHBytes);
+    static_assert(kLds <= kLdsPerCU, "tile shape does not fit LDS");
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
     const int macro_tiles = (p.V + Cfg::VT - 1) / Cfg::VT;
     const long long grid = (long long)((macro_tiles + 7) / 8) * 8 * nbt;
@@ -177,17 +180,17 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
     static PerDevice<> state;
     if (!state.attr[dev]) {
-        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL, WB>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL, WB>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
         std::lock_guard<std::mutex> lk(g_mu);
         state.attr[dev] = true;
     }
     if (nbt == 1)
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL, WB>), dim3((unsigned)grid), dim3(Cfg::kThreads),
-                           Cfg::lds_bytes(), st, p, nbt);
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+                           kLds, st, p, nbt);
     else
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL, WB>), dim3((unsigned)grid), dim3(Cfg::kThreads),
-                           Cfg::lds_bytes(), st, p, nbt);
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+                           kLds, st, p, nbt);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
@@ -349,9 +352,23 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     // larger batches and wider hidden sizes: the tiled kernel, shapes chosen as for bf16
     const int cus = current_device_cus(nullptr);
     if (cus <= 0) return FS_ERR_HIP;
-    switch (variant >= 4 ? variant - 3 : pick_tile_shape(p.B, p.V, cus)) {
-    // a K step covers only 64 bytes of a row here, half a cache line: the W prefetch groups are
-    // twice as long as on the bf16 path, so that both halves of a line are requested back to back
+    // variants 4..10 force tile shape 3..9 with the codes kept in LDS where that fits (128-element
+    // K steps); variants 14..20 force shape 3..9 in the form that widens the codes when a step is
+    // parked: there a K step covers only 64 bytes of a row, half a cache line, so the W prefetch
+    // groups are twice as long as on the bf16 path (both halves of a line requested back to back)
+    const int shape = variant >= 14 ? variant - 11 : variant >= 4 ? variant - 1 : pick_tile_shape(p.B, p.V, cus);
+    if (variant < 14) {
+        switch (shape) {
+        case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
+        case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 1, 2>, false, 1, true>(p, st);
+        case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 1, 2>, false, 1, true>(p, st);
+        case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, false, 1, true>(p, st);
+        case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, false, 1, true>(p, st);
+        case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, false, 1, true>(p, st);
+        default: break;   // 256 x 256: two hidden sub-tiles per step do not fit LDS
+        }
+    }
+    switch (shape) {
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 2, 2, 256>, false, 1>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 4, 2>, false, 1>(p, st);
     case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 4, 2>, false, 1>(p, st);

@@ -59,24 +59,33 @@ struct Tiled2Cfg {
     static constexpr size_t lds_bytes() { return 2 * (size_t)kBufBytes; }
 };
 
-// WB: bytes per W element.  2 = bf16.  1 = FP8 E4M3 codes: a 16-byte load then carries 16
-// elements (four loads cover the 64 elements of a row and K step), the codes are widened to bf16
-// when the step is parked, and LDS and the MFMA path see the same bf16 tiles as on the bf16 path.
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2>
+// WB: bytes per W element.  2 = bf16.  1 = FP8 E4M3 codes, in one of two forms:
+//   WCODES = false: a K step stays 64 elements (four 16-byte loads per row), the codes are widened
+//     to bf16 when the step is parked, and LDS and the MFMA loop are those of the bf16 path;
+//   WCODES = true: a K step is 128 elements, i.e. the same 128 bytes (one cache line) of a W row
+//     as on the bf16 path; LDS holds the codes (same W tile bytes, half the LDS writes per
+//     element), the hidden tile of a step is two 64-element sub-tiles, and a lane widens the 8
+//     codes of its MFMA operand after reading them (ds_read_b64).
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
+    static_assert(!WCODES || WB == 1, "codes in LDS only for one-byte W elements");
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
-    constexpr int KS = Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
+    constexpr int KS = WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
+    constexpr int HH = KS / 64;                      // 64-element hidden sub-tiles per K step
+    constexpr int NHL = Cfg::kHLoads * HH;           // hidden loads per thread and K step
     constexpr int WEPC = 16 / WB;                    // W elements per 16-byte load
     constexpr int WCH = KS / WEPC;                   // loads per W row and K step (8 or 4)
     constexpr int WRPP = Cfg::kThreads / WCH;        // W rows one workgroup-wide load covers
     constexpr int NWL = VT / WRPP;                   // W loads per thread and K step
     static_assert(VT % WRPP == 0 && NWL >= 1, "W tile rows per load pass");
+    constexpr int HSUB = BT * 128;                   // bytes of one hidden sub-tile
+    constexpr int BUFB = Cfg::kWBytes + HH * HSUB;   // bytes of one LDS buffer (one K step)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    auto w_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes; };
-    auto h_lds = [&](int buf) { return smem + buf * Cfg::kBufBytes + Cfg::kWBytes; };
+    auto w_lds = [&](int buf) { return smem + buf * BUFB; };
+    auto h_lds = [&](int buf) { return smem + buf * BUFB + Cfg::kWBytes; };
     // epilogue scratch, aliased onto the tile buffers: first written after the barrier that ends
     // the last K step, when no wave reads or parks tiles any more
     float2* wave_cand = reinterpret_cast<float2*>(smem);                        // [WM][BT]
@@ -116,7 +125,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int wld_row = tid / WCH;   // 0..WRPP-1
     constexpr int NSET = Cfg::NSET;
     uint4 wst[NSET][GS][NWL];        // NSET groups of GS steps
-    uint4 hst[NSET][Cfg::kHLoads];   // NSET steps
+    uint4 hst[NSET][NHL];            // NSET steps
 
     // Every load of the K loop is unconditional, so the compiler can count the loads in flight and
     // wait for exactly the step it parks (s_waitcnt vmcnt(N)) instead of draining the prefetch:
@@ -143,28 +152,30 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 #pragma unroll
         for (int s = 0; s < GS; ++s) fetch_w(grp[s], kmap(group * GS + s) * KS);
     };
-    auto fetch_h = [&](uint4 (&hr)[Cfg::kHLoads], int k0) {
+    auto fetch_h = [&](uint4 (&hr)[NHL], int k0) {
         const bool over = k0 >= D;
-        int k = k0 + ld_chunk * 8;
-        k = k < D - 8 ? k : D - 8;
-        k = over ? ld_chunk * 8 : k;
 #pragma unroll
-        for (int i = 0; i < Cfg::kHLoads; ++i) {
-            int r = b0 + (Cfg::kHPartial ? (ld_row & (BT - 1)) : ld_row + RPP * i);
-            r = r < B - 1 ? r : B - 1;
-            hr[i] = ld_global_16B(p.H + (size_t)r * D + k);
+        for (int hh = 0; hh < HH; ++hh) {
+            int k = k0 + hh * 64 + ld_chunk * 8;
+            k = k < D - 8 ? k : D - 8;
+            k = over ? ld_chunk * 8 : k;
+#pragma unroll
+            for (int i = 0; i < Cfg::kHLoads; ++i) {
+                int r = b0 + (Cfg::kHPartial ? (ld_row & (BT - 1)) : ld_row + RPP * i);
+                r = r < B - 1 ? r : B - 1;
+                hr[hh * Cfg::kHLoads + i] = ld_global_16B(p.H + (size_t)r * D + k);
+            }
         }
     };
     // park K step `step` (registers -> LDS buffer buf)
-    auto park = [&](const uint4 (&wr)[NWL], const uint4 (&hr)[Cfg::kHLoads], int buf, int step) {
-        const bool zero = k_ragged && (step * KS + ld_chunk * 8 >= D);   // only in the last step
-        const bool wzero = k_ragged && (step * KS + wld_chunk * WEPC >= D);
+    auto park = [&](const uint4 (&wr)[NWL], const uint4 (&hr)[NHL], int buf, int step) {
+        const bool wzero = k_ragged && (step * KS + wld_chunk * WEPC >= D);   // only in the last step
 #pragma unroll
         for (int i = 0; i < NWL; ++i) {
             const int r = wld_row + WRPP * i;
             uint4 v = wr[i];
             if (wzero) v = make_uint4(0u, 0u, 0u, 0u);
-            if constexpr (WB == 2) {
+            if constexpr (WB == 2 || WCODES) {
                 *reinterpret_cast<uint4*>(w_lds(buf) + tile_off(r, wld_chunk)) = v;
             } else {   // 16 codes -> two bf16 chunks
                 *reinterpret_cast<bf16x8*>(w_lds(buf) + tile_off(r, 2 * wld_chunk)) = e4m3x8_to_bf16x8(v.x, v.y);
@@ -172,11 +183,16 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             }
         }
 #pragma unroll
-        for (int i = 0; i < Cfg::kHLoads; ++i) {
-            const int r = ld_row + RPP * i;
-            uint4 v = hr[i];
-            if (zero) v = make_uint4(0u, 0u, 0u, 0u);
-            if (!Cfg::kHPartial || r < BT) *reinterpret_cast<uint4*>(h_lds(buf) + tile_off(r, ld_chunk)) = v;
+        for (int hh = 0; hh < HH; ++hh) {
+            const bool zero = k_ragged && (step * KS + hh * 64 + ld_chunk * 8 >= D);
+#pragma unroll
+            for (int i = 0; i < Cfg::kHLoads; ++i) {
+                const int r = ld_row + RPP * i;
+                uint4 v = hr[hh * Cfg::kHLoads + i];
+                if (zero) v = make_uint4(0u, 0u, 0u, 0u);
+                if (!Cfg::kHPartial || r < BT)
+                    *reinterpret_cast<uint4*>(h_lds(buf) + hh * HSUB + tile_off(r, ld_chunk)) = v;
+            }
         }
     };
 
@@ -188,20 +204,26 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 
     auto compute = [&](int buf) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int c = 4 * s + g;
+        for (int s = 0; s < KS / 32; ++s) {   // 32 contraction elements per MFMA
+            const int c = 4 * (s & 1) + g;    // hidden chunk inside its 64-element sub-tile
             bf16x8 a[RB];
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
                 const int r = wm * (16 * RB) + i * 16 + n;
-                a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                      w_lds(buf) + tile_off(r, c)));
+                if constexpr (WCODES) {       // 8 codes: half of 16-byte chunk 2 s + g / 2
+                    const uint2 q = *reinterpret_cast<const uint2*>(
+                        w_lds(buf) + tile_off(r, 2 * s + (g >> 1)) + ((g & 1) << 3));
+                    a[i] = e4m3x8_to_bf16x8(q.x, q.y);
+                } else {
+                    a[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+                                                          w_lds(buf) + tile_off(r, c)));
+                }
             }
 #pragma unroll
             for (int j = 0; j < CB; ++j) {
                 const int r = wn * (16 * CB) + j * 16 + n;
                 const bf16x8 b = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
-                                                                h_lds(buf) + tile_off(r, c)));
+                                                                h_lds(buf) + (s >> 1) * HSUB + tile_off(r, c)));
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b, acc[i][j], 0, 0, 0);

@@ -86,10 +86,11 @@ def test_w8_at_llama_shape(fs, orc):
     assert v.ok, (str(v), v.failures[:3])
 
 
-@pytest.mark.parametrize("variant", [1, 6, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("variant", [1, 4, 5, 6, 7, 8, 9, 10, 14, 15, 16, 17, 18, 19, 20])
 def test_w8_every_kernel_choice(fs, orc, variant):
-    # 1: four-wave split-K; 6..12: the tiled shapes 3..9 (256x128, 128x128, 128x64, 512x32, 512x64, 256x32, 256x256)
-    for B, D, V in [(10, 528, 1100), (16, 2048, 700)] if variant == 1 else [(20, 528, 1100), (70, 256, 1500), (150, 1072, 700)]:
+    # 1: four-wave split-K; 4..10: the tiled shapes 3..9 (256x128, 128x128, 128x64, 512x32, 512x64, 256x32,
+    # 256x256) with the codes kept in LDS where that fits; 14..20: the same shapes widening the codes at park time
+    for B, D, V in [(10, 528, 1100), (16, 2048, 700)] if variant == 1 else [(20, 528, 1100), (70, 256, 1500), (150, 1072, 700), (33, 48, 513)]:
         print(f"w8 variant {variant} B={B} D={D} V={V}", flush=True)
         H, W = wl.make_small(D=D, V=V, B=B, data_seed=850 + B)
         codes, scale = wl.quantize_e4m3(W)
