@@ -208,7 +208,9 @@ fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_s
  *   W8, w_scale   device pointers, 16-byte aligned; D % 16 == 0
  *   logits        NULL, or fp32 [B, V]: also store y (for tests and the comparison path)
  *   workspace     at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
- *   flags         FS_FLAG_NONE
+ *   flags         FS_FLAG_NONE; or, as a tuning aid, FS_VARIANT(v): 1..3 split-K forms (B <= 16 only),
+ *                 4..10 tile shapes 3..9 of FS_TUNE_TILE_SHAPE with the codes kept in LDS where that
+ *                 fits, 14..20 the same shapes widening the codes when a K step is parked
  * NaN codes (S.1111.111) propagate to NaN logits, which never win.
  */
 fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_scale, int B, int D, int V,
