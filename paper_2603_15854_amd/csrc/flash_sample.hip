@@ -166,9 +166,10 @@ fs_status launch_tiled_auto(const Stage1Params& p, hipStream_t st)
     return launch_tiled<16>(p, st);
 }
 
-template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false>
+template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
+    if (!KRAG && p.D % (WCODES ? 128 : 64) != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
     // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles
     constexpr size_t kLds = 2 * ((size_t)Cfg::kWBytes + (WCODES ? 2 : 1) * (size_t)Cfg::kHBytes);
     static_assert(kLds <= kLdsPerCU, "tile shape does not fit LDS");
@@ -180,16 +181,16 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     if (current_device_cus(&dev) <= 0) return FS_ERR_HIP;
     static PerDevice<> state;
     if (!state.attr[dev]) {
-        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
-        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES, KRAG>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        if (allow_lds(stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES, KRAG>, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
         std::lock_guard<std::mutex> lk(g_mu);
         state.attr[dev] = true;
     }
     if (nbt == 1)
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES, KRAG>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            kLds, st, p, nbt);
     else
-        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES>), dim3((unsigned)grid), dim3(Cfg::kThreads),
+        hipLaunchKernelGGL((stage1_tiled2_kernel<Cfg, false, FULL, WB, WCODES, KRAG>), dim3((unsigned)grid), dim3(Cfg::kThreads),
                            kLds, st, p, nbt);
     return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
@@ -199,7 +200,8 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   2: 256 x 64   8 waves, one per CU                 6: 512 x 32   8 waves, one per CU
 //   3: 256 x 128  8 waves, one per CU                 7: 512 x 64   8 waves, one per CU
 //   4: 128 x 128  4 waves, two per CU                 8: 256 x 32   4 waves, two per CU
-//   9: 256 x 256  8 waves, one per CU, one register set of prefetch (accumulators take 128 VGPRs)
+//   9: 256 x 256  8 waves, one per CU (accumulators take 128 VGPRs)
+//  10: 512 x 128  8 waves, one per CU, one register set of prefetch (128 accumulator VGPRs, 160 KB of LDS)
 // Every workgroup re-reads its hidden tile once per W tile and the kernels are bound by the bytes
 // that enter the CUs, so more vocabulary rows per workgroup is better -- as long as the coarser
 // grid still fills the CUs evenly.  Measured, fused call in us (D = 4096, V = 128256: 1002 tiles
@@ -207,12 +209,13 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 // round mostly empty):
 //   B = 32:   shape 8 160 | 187    shape 6 161 | 230    shape 1 165-173 | 190
 //   B = 64:   shape 7 168 | 247    shape 5 170 | 190    shape 2 174 | 212
-//   B = 128:  shape 3 195 | 243    shape 4 217 | 236
-//   B = 256:  shape 9 309          shape 3 376          (D = 8192: 584 against 699)
+//   B = 128:  shape 10 182         shape 3 195-203 | 243    shape 4 217 | 236
+//   B = 256:  shape 9 301          shape 3 376          (D = 8192: 562 against 699)
 // and at D = 8192, V = 128256, B <= 16: shape 6 307 us, shape 8 315, shape 1 317 (the split-K
 // kernel with 64 k-steps per wave: 325-335).
-// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 256 x 128 up to 128,
-// 256 x 256 above, which reads W once instead of once per 128 batch rows) when its
+// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 512 x 128 up to 128 -- or
+// 256 x 128 when only the 256-row grid fills its rounds --, 256 x 256 above, which reads W once
+// instead of once per 128 batch rows) when its
 // grid fills at least 90 % of its last round, else the four-wave shape with two workgroups per CU
 // (256 x 32, 128 x 64, 128 x 128), whose finer grid and overlapped epilogues tolerate a ragged tail.
 bool fills_rounds(long long wgs, int cus)
@@ -226,14 +229,28 @@ int pick_tile_shape(int B, int V, int cus)
     if (B <= 32) return fills_rounds((V + 511) / 512, cus) ? 6 : 8;
     if (B <= 64) return fills_rounds((V + 511) / 512, cus) ? 7 : 5;
     if (B > 128 && fills_rounds((long long)((V + 255) / 256) * ((B + 255) / 256), cus)) return 9;
+    if (B <= 128 && fills_rounds((V + 511) / 512, cus)) return 10;
     const long long nbt = (B + 127) / 128;
     return fills_rounds((long long)((V + 255) / 256) * nbt, cus) ? 3 : 4;
 }
 
-// `shape` = 0 picks automatically; 1..8 forces one shape (tuning aid).
+// A hidden size that is not a multiple of the 64-element K step runs on the three two-per-CU
+// shapes, built with the zeroing of the last step's tail; every other shape exists for whole K
+// steps only.
+template <bool FULL, int WB = 2>
+fs_status launch_tiled2_ragged(const Stage1Params& p, hipStream_t st)
+{
+    if (p.B <= 32) return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, FULL, WB, false, true>(p, st);
+    if (p.B <= 64) return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL, WB, false, true>(p, st);
+    return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL, WB, false, true>(p, st);
+}
+
+// `shape` = 0 picks automatically; 1..9 forces one shape (tuning aid; honoured for whole-K-step
+// hidden sizes only).
 template <bool FULL>
 fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
 {
+    if (p.D % 64 != 0) return launch_tiled2_ragged<FULL>(p, st);
     if (shape == 0) {
         const int cus = current_device_cus(nullptr);
         if (cus <= 0) return FS_ERR_HIP;
@@ -246,7 +263,8 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, FULL>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, FULL>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, FULL>(p, st);
-    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 1, 2, 256, 1>, FULL>(p, st);
+    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 1, 2, 256, 2>, FULL>(p, st);
+    case 10: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 512, 1>, FULL>(p, st);
     default: break;
     }
     if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
@@ -356,16 +374,20 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     // K steps); variants 14..20 force shape 3..9 in the form that widens the codes when a step is
     // parked: there a K step covers only 64 bytes of a row, half a cache line, so the W prefetch
     // groups are twice as long as on the bf16 path (both halves of a line requested back to back)
+    if (p.D % 64 != 0) return launch_tiled2_ragged<false, 1>(p, st);
     const int shape = variant >= 14 ? variant - 11 : variant >= 4 ? variant - 1 : pick_tile_shape(p.B, p.V, cus);
-    if (variant < 14) {
+    if (variant < 14 && p.D % 128 == 0) {
         switch (shape) {
         case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
         case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 1, 2>, false, 1, true>(p, st);
         case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 1, 2>, false, 1, true>(p, st);
         case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 1, 1, 512>, false, 1, true>(p, st);
-        case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512>, false, 1, true>(p, st);
+        case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512, 1>, false, 1, true>(p, st);
         case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, false, 1, true>(p, st);
-        default: break;   // 256 x 256: two hidden sub-tiles per step do not fit LDS
+        case 9:    // 256 x 256 and 512 x 128 do not fit LDS with two hidden sub-tiles per step:
+        case 10:   // both run as shape 3 (B = 256: 299 us, no slower than the 256 x 256 park-time form)
+            return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
+        default: break;
         }
     }
     switch (shape) {
@@ -375,7 +397,8 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     case 6: return launch_tiled2<Tiled2Cfg<32, 8, 1, 2, 1, 512>, false, 1>(p, st);
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 1, 512>, false, 1>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 2, 2, 256>, false, 1>(p, st);
-    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 2, 2, 256, 1>, false, 1>(p, st);
+    case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 1, 2, 256, 1>, false, 1>(p, st);
+    case 10: return launch_tiled2<Tiled2Cfg<128, 4, 2, 2, 2, 256>, false, 1>(p, st);   // 512 x 128 does not exist here
     default: return FS_ERR_UNSUPPORTED;
     }
 }

@@ -66,7 +66,10 @@ struct Tiled2Cfg {
 //     as on the bf16 path; LDS holds the codes (same W tile bytes, half the LDS writes per
 //     element), the hidden tile of a step is two 64-element sub-tiles, and a lane widens the 8
 //     codes of its MFMA operand after reading them (ds_read_b64).
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false>
+// KRAG: D need not be a multiple of the K step (the chunks of the last step that lie past D are
+// zeroed when parked).  The zeroing selects cost registers and time in the main loop (256 x 128:
+// 202 -> 158 VGPRs and -5 % time without them), so whole-step hidden sizes get KRAG = false.
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
@@ -132,7 +135,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     // rows past V (or B) re-read the last valid row and only feed outputs nobody reads (each
     // output row/column depends on its own operand row only); a prefetch that runs past the end
     // of K reads one fixed cache line; a chunk past D inside the last step is zeroed when parked.
-    const bool k_ragged = (D & (KS - 1)) != 0;
+    const bool k_ragged = KRAG && (D & (KS - 1)) != 0;
     auto fetch_w = [&](uint4 (&wr)[NWL], int k0) {
         const bool over = k0 >= D;                          // uniform
         int k = k0 + wld_chunk * WEPC;

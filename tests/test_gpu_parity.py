@@ -155,7 +155,7 @@ def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
         _small_case(fs, orc, B, D, V, variant, data_seed=70 + B)
 
 
-@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 9])
+@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_every_tile_shape_of_the_tiled_kernel(fs, orc, tile_shape):
     # the shapes the launcher can pick (128/256/512 vocabulary rows x 32/64/128 batch rows), each on
     # ragged V, B smaller and larger than its batch tile, and a K tail (D % 64 != 0)
