@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
-MEASURED_TRAFFIC_C2_B16 = int((514428.8 * 2.0 + 1010.4) * 1024)   # bytes per stage-1 launch (rocprofv3)
+MEASURED_TRAFFIC_C2_B16 = int((514427.6 * 2.0 + 1009.6) * 1024)   # bytes per stage-1 launch (rocprofv3)
 
 
 def main() -> int:
