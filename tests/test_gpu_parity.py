@@ -444,3 +444,28 @@ def test_graph_capture_and_replay_matches_eager(fs, orc):
             torch.cuda.synchronize()
             assert torch.equal(oi, e_i), (B, rep)
             assert torch.equal(ov, e_v) and torch.equal(ol, e_l), (B, rep)
+
+
+def test_calls_on_two_streams_do_not_share_state(fs, orc):
+    # the explicit entry points keep everything per call (workspace, outputs): interleaved calls on two
+    # streams must give what each gives alone
+    B, D, V = 12, 2048, 20000
+    H1, W1 = wl.make_small(D=D, V=V, B=B, data_seed=610)
+    H2, W2 = wl.make_small(D=D, V=V, B=B, data_seed=611)
+    tau = torch.full((B,), 1.1, device="cuda")
+    ins = [(to_device_bf16(H1), to_device_bf16(W1), 21), (to_device_bf16(H2), to_device_bf16(W2), 22)]
+    alone = []
+    for Hd, Wd, seed in ins:
+        i, v = fs.flash_sample_ex(Hd, Wd, tau, seed=seed)
+        torch.cuda.synchronize()
+        alone.append((i.clone(), v.clone()))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    for rep in range(6):
+        for s, (Hd, Wd, seed) in enumerate(ins):
+            with torch.cuda.stream(streams[s]):
+                outs[s].append(fs.flash_sample_ex(Hd, Wd, tau, seed=seed, stream=streams[s]))
+    torch.cuda.synchronize()
+    for s in range(2):
+        for i, v in outs[s]:
+            assert torch.equal(i, alone[s][0]) and torch.equal(v, alone[s][1])
