@@ -156,6 +156,33 @@ def quantize_e4m3(W_bits: np.ndarray):
     return q.view(torch.uint8).numpy().copy(), scale.numpy().copy()
 
 
+def quantize_mxfp4(W_bits: np.ndarray):
+    """Input preparation for the MXFP4-weight path: bf16 weights [V, D] (D % 32 == 0) ->
+    (codes uint8 [V, D/2], two E2M1 codes per byte with the even element in the low nibble;
+    scales uint8 [V, D/32], E8M0).  Per block of 32: scale exponent = floor(log2(max|w|)) - 2 (the
+    largest E2M1 magnitude is 6 = 1.5 * 2^2), elements rounded to the nearest E2M1 magnitude
+    (ties to the even code), saturating at 6."""
+    Wf = bf16_bits_to_f32(W_bits).astype(np.float64)
+    V, D = Wf.shape
+    assert D % 32 == 0
+    blocks = Wf.reshape(V, D // 32, 32)
+    amax = np.abs(blocks).max(axis=2)
+    exp = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 2, -127.0)
+    exp = np.clip(exp, -127, 127)
+    scaled = np.abs(blocks) / np.exp2(exp)[:, :, None]
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    # nearest grid point, ties to the even code
+    d = np.abs(scaled[..., None] - grid)
+    code = d.argmin(axis=-1)
+    nxt = np.minimum(code + 1, 7)
+    tie = (np.abs(scaled - grid[code]) == np.abs(scaled - grid[nxt])) & (nxt != code) & (code % 2 == 1)
+    code = np.where(tie, nxt, code).astype(np.uint8)
+    code |= (blocks < 0).astype(np.uint8) << 3
+    code = code.reshape(V, D)
+    packed = (code[:, 0::2] | (code[:, 1::2] << 4)).astype(np.uint8)
+    return np.ascontiguousarray(packed), np.ascontiguousarray((exp + 127).astype(np.uint8))
+
+
 def to_device_bf16(bits: np.ndarray):
     """bf16 bit patterns (uint16) -> torch.bfloat16 tensor on the current GPU (a plain upload)."""
     import torch

@@ -113,6 +113,18 @@ def lib():
     L.fso_score_at_w8.argtypes = [_u16p, _u8p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
                                   C.c_uint64, C.c_int64, C.c_int64]
     L.fso_score_at_w8.restype = C.c_double
+    L.fso_e2m1_to_double.argtypes = [C.c_uint8]
+    L.fso_e2m1_to_double.restype = C.c_double
+    L.fso_e8m0_to_double.argtypes = [C.c_uint8]
+    L.fso_e8m0_to_double.restype = C.c_double
+    L.fso_logits_w4.argtypes = [_u16p, _u8p, _u8p, C.c_int64, C.c_int64, C.c_int64, _f64p]
+    L.fso_logits_w4.restype = C.c_int
+    L.fso_sample_w4.argtypes = [_u16p, _u8p, _u8p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64,
+                                C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, _i32p, _f32p, _f64p, _i64p, _f64p]
+    L.fso_sample_w4.restype = C.c_int
+    L.fso_score_at_w4.argtypes = [_u16p, _u8p, _u8p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                  C.c_uint64, C.c_int64, C.c_int64]
+    L.fso_score_at_w4.restype = C.c_double
     L.fso_group_word.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_uint32]
     L.fso_group_word.restype = C.c_uint32
     L.fso_group_stats.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_uint64, C.c_int64, C.c_int64,
@@ -374,6 +386,47 @@ def sample_w8(H, W8, scale, tau, seed: int = 0, row_seeds=None, row_offset: int 
 def score_at_w8(H, W8, scale, b_local, i_local, tau, seed, row, vocab_id) -> float:
     sc, sc_p = _opt_ptr(scale, np.float32)
     return float(lib().fso_score_at_w8(H, W8, sc_p, H.shape[1], b_local, i_local, float(tau), seed, row, vocab_id))
+
+
+def e2m1_to_double(nibble: int) -> float:
+    return float(lib().fso_e2m1_to_double(int(nibble) & 0xF))
+
+
+def e8m0_to_double(e: int) -> float:
+    return float(lib().fso_e8m0_to_double(int(e) & 0xFF))
+
+
+def logits_w4(H, W4, S) -> np.ndarray:
+    B, D = H.shape
+    V = W4.shape[0]
+    Y = np.empty((B, V), dtype=np.float64)
+    lib().fso_logits_w4(H, W4, S, B, D, V, Y)
+    return Y
+
+
+def sample_w4(H, W4, S, tau, seed: int = 0, row_seeds=None, row_offset: int = 0, row_ids=None,
+              vocab_offset: int = 0):
+    """Default path on MXFP4 weights (E2M1 codes, two per byte, one E8M0 scale per 32 elements)."""
+    B, D = H.shape
+    V = W4.shape[0]
+    assert W4.shape == (V, D // 2) and S.shape == (V, D // 32)
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    ri, ri_p = _opt_ptr(row_ids, np.int64)
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    top1 = np.empty(B, dtype=np.float64)
+    idx2 = np.empty(B, dtype=np.int64)
+    top2 = np.empty(B, dtype=np.float64)
+    nt = lib().fso_sample_w4(H, W4, S, B, D, V, tau, seed, rs_p, row_offset, ri_p, vocab_offset,
+                             out_idx, out_val, top1, idx2, top2)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, top1=top1, idx2=idx2, top2=top2, threads=nt)
+
+
+def score_at_w4(H, W4, S, b_local, i_local, tau, seed, row, vocab_id) -> float:
+    return float(lib().fso_score_at_w4(H, W4, S, H.shape[1], b_local, i_local, float(tau), seed, row, vocab_id))
 
 
 GROUPED_PARALLEL, GROUPED_ONLINE = 0, 1

@@ -32,7 +32,8 @@
  * The full transform (additive bias, temperature, -inf mask) and the log-normaliser
  * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below); the
  * grouped variants (parallel and online Group-Gumbel-Max) are the third (fso_group_word and below);
- * FP8 (E4M3) weights with per-row scales are the fourth (fso_e4m3_to_double and below).
+ * FP8 (E4M3) weights with per-row scales are the fourth (fso_e4m3_to_double and below), MXFP4
+ * weights the fifth (fso_e2m1_to_double and below).
  *
  * NaN scores never win (the strict > comparison is false for NaN); a row with no
  * score > -inf returns idx = -1, val = -inf.
@@ -607,6 +608,89 @@ double fso_score_at_w8(const uint16_t* H, const uint8_t* W8, const float* scale,
                        int64_t i_local, double tau, uint64_t seed, int64_t row, int64_t vocab_id)
 {
     return fso_logit_w8(H, W8, scale, D, b_local, i_local) / tau + fso_gumbel(seed, row, vocab_id);
+}
+
+/* ------------------------------------------------------------------ MXFP4 weights */
+
+/*
+ * Four-bit weights in the OCP microscaling format MXFP4 (the second lower-precision format the
+ * paper names as future work): elements are FP4 E2M1 codes (1 sign, 2 exponent bits with bias 1,
+ * 1 mantissa bit: magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), two per byte (element 2j in the low
+ * nibble of byte j), and every block of 32 consecutive elements of a row shares one E8M0 scale
+ * byte e, worth 2^(e - 127) (e = 255 is NaN).  Hidden states stay bf16:
+ *      y_i = sum_d H[b,d] * e2m1(W4[i,d]) * 2^(S[i, d / 32] - 127)
+ * A scaled element is a bf16 value (a power-of-two multiple of a one-mantissa-bit number), so the
+ * products are again the exact products of the bf16 path.
+ */
+double fso_e2m1_to_double(uint8_t nibble)
+{
+    static const double mag[8] = { 0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0 };
+    double v = mag[nibble & 7];
+    return (nibble & 8) ? -v : v;
+}
+
+double fso_e8m0_to_double(uint8_t e)
+{
+    if (e == 255) return NAN;
+    return ldexp(1.0, (int)e - 127);
+}
+
+double fso_logit_w4(const uint16_t* H, const uint8_t* W4, const uint8_t* S, int64_t D, int64_t b, int64_t i)
+{
+    const uint16_t* h = H + b * D;
+    const uint8_t* w = W4 + i * (D / 2);
+    const uint8_t* sc = S + i * (D / 32);
+    double acc = 0.0;
+    for (int64_t d = 0; d < D; ++d) {
+        uint8_t byte = w[d >> 1];
+        uint8_t nib = (d & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15);
+        acc += bf16_to_double(h[d]) * (fso_e2m1_to_double(nib) * fso_e8m0_to_double(sc[d >> 5]));
+    }
+    return acc;
+}
+
+int fso_logits_w4(const uint16_t* H, const uint8_t* W4, const uint8_t* S, int64_t B, int64_t D, int64_t V,
+                  double* Y)
+{
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = omp_get_max_threads();
+#endif
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < V; ++i)
+        for (int64_t b = 0; b < B; ++b) Y[b * V + i] = fso_logit_w4(H, W4, S, D, b, i);
+    return nthreads;
+}
+
+int fso_sample_w4(const uint16_t* H, const uint8_t* W4, const uint8_t* S, int64_t B, int64_t D, int64_t V,
+                  const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                  const int64_t* row_ids, int64_t vocab_offset, int32_t* out_idx, float* out_val,
+                  double* top1_val, int64_t* top2_idx, double* top2_val)
+{
+    if (B <= 0 || V <= 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits_w4(H, W4, S, B, D, V, Y);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t i1, i2;
+        double m1, m2;
+        fso_gumbel_max_row(Y + b * V, V, (double)tau[b], row_seed(seed, row_seeds, b),
+                           row_id(row_ids, row_offset, b), vocab_offset, &i1, &m1, &i2, &m2);
+        out_idx[b] = (int32_t)i1;
+        if (out_val) out_val[b] = (float)m1;
+        if (top1_val) top1_val[b] = m1;
+        if (top2_idx) top2_idx[b] = i2;
+        if (top2_val) top2_val[b] = m2;
+    }
+    free(Y);
+    return nthreads;
+}
+
+double fso_score_at_w4(const uint16_t* H, const uint8_t* W4, const uint8_t* S, int64_t D, int64_t b_local,
+                       int64_t i_local, double tau, uint64_t seed, int64_t row, int64_t vocab_id)
+{
+    return fso_logit_w4(H, W4, S, D, b_local, i_local) / tau + fso_gumbel(seed, row, vocab_id);
 }
 
 /* ------------------------------------------------------------------ helpers for the pins */
