@@ -220,6 +220,33 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
                           int32_t* out_idx, float* out_val,
                           void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
+/*
+ * The same draw on MXFP4 weights (OCP microscaling FP4, the other lower-precision format the paper
+ * names): W4 [V, D/2] bytes holds FP4 E2M1 codes, two per byte (element 2j of a row in the low
+ * nibble of byte j); w_scales [V, D/32] bytes holds one E8M0 scale per 32 consecutive elements of
+ * a row, worth 2^(e - 127); hidden stays bf16:
+ *      y_{b,i} = sum_d hidden[b,d] * e2m1(W4[i,d]) * 2^(w_scales[i, d/32] - 127)
+ * Codes and scale are combined into bf16 values on chip (exactly), then contracted like the bf16
+ * path.  Built for the bandwidth-bound decode regime only:
+ *   B <= 16 and D % 512 == 0, D <= 4096, or D % 1024 == 0, D <= 8192; anything else returns
+ *   FS_ERR_UNSUPPORTED
+ *   W4, w_scales   device pointers, 16-byte aligned; scale bytes above 252 must not occur (253 and
+ *                  254 overflow the bf16 range of a scaled element, 255 is NaN)
+ *   logits         NULL, or fp32 [B, V]: also store y
+ *   workspace      at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
+ *   flags          FS_FLAG_NONE, or FS_TUNE_WGS_PER_CU(n) / FS_VARIANT(1|2|4: row-tiles in flight;
+ *                  9|10: the 32-K-step form with 1|2 row-tiles in flight)
+ */
+fs_status flash_sample_w4(const void* hidden, const void* W4, const void* w_scales, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset, float* logits,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/* Debug tap: the on-chip MXFP4 -> bf16 conversion: out[8 k + j] = e2m1(nibble j of dword k of
+ * codes) * 2^(scales[k] - 127) for k < n8 (codes 4-byte aligned), widened to fp32. */
+fs_status flash_sample_mxfp4_decode(const void* codes, const uint8_t* scales, int n8, float* out, void* stream);
+
 /* Debug tap: the on-chip E4M3 -> bf16 conversion applied to n codes (n % 8 == 0, codes 8-byte
  * aligned), widened to fp32 out[n]. */
 fs_status flash_sample_e4m3_decode(const uint8_t* codes, int n, float* out, void* stream);

@@ -30,7 +30,7 @@ EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
-    "flash_sample_w8", "flash_sample_e4m3_decode",
+    "flash_sample_w8", "flash_sample_e4m3_decode", "flash_sample_w4", "flash_sample_mxfp4_decode",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
     "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
     "flash_sample_stream_probe",
@@ -88,6 +88,10 @@ def lib():
     L.flash_group_choose.restype = i32
     L.flash_sample_w8.argtypes = [vp, vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, sz, vp, u32]
     L.flash_sample_w8.restype = i32
+    L.flash_sample_w4.argtypes = [vp, vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_w4.restype = i32
+    L.flash_sample_mxfp4_decode.argtypes = [vp, vp, i32, vp, vp]
+    L.flash_sample_mxfp4_decode.restype = i32
     L.flash_sample_e4m3_decode.argtypes = [vp, i32, vp, vp]
     L.flash_sample_e4m3_decode.restype = i32
     L.flash_sample_stage1.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, vp, u32]
@@ -248,6 +252,37 @@ def flash_sample_w8(hidden, W8, w_scale, temperature, seed: int = 0, row_seeds=N
                                int(flags))
     _check(st, "flash_sample_w8")
     return out_idx, out_val
+
+
+def flash_sample_w4(hidden, W4, w_scales, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
+                    vocab_offset: int = 0, logits=None, out_idx=None, out_val=None, workspace=None,
+                    stream=None, flags: int = 0):
+    """Draw on MXFP4 weights: W4 uint8 [V, D/2] (two E2M1 codes per byte), w_scales uint8 [V, D/32]."""
+    import torch
+    if hidden.dtype != torch.bfloat16 or W4.dtype != torch.uint8 or w_scales.dtype != torch.uint8:
+        raise ValueError("hidden must be bfloat16, W4 and w_scales uint8")
+    B, D, V = hidden.shape[0], hidden.shape[1], W4.shape[0]
+    if W4.dim() != 2 or W4.shape[1] * 2 != D or tuple(w_scales.shape) != (V, D // 32):
+        raise ValueError("W4 must be [V, D/2] and w_scales [V, D/32]")
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
+    st = lib().flash_sample_w4(_ptr(hidden), _ptr(W4), _ptr(w_scales), B, D, V, _ptr(temperature), int(seed),
+                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+                               _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream),
+                               int(flags))
+    _check(st, "flash_sample_w4")
+    return out_idx, out_val
+
+
+def flash_sample_mxfp4_decode(codes, scales, out=None, stream=None):
+    """codes: uint8 tensor of 4 * n8 bytes (eight codes per dword), scales: uint8 [n8]."""
+    import torch
+    n8 = scales.numel()
+    if out is None:
+        out = torch.empty(8 * n8, dtype=torch.float32, device=codes.device)
+    _check(lib().flash_sample_mxfp4_decode(_ptr(codes), _ptr(scales), n8, _ptr(out), _stream_ptr(stream)),
+           "flash_sample_mxfp4_decode")
+    return out
 
 
 def flash_sample_e4m3_decode(codes, out=None, stream=None):

@@ -13,6 +13,7 @@
 #include "fs_stage1_splitk.hpp"
 #include "fs_stage1_tiled.hpp"
 #include "fs_stage1_tiled2.hpp"
+#include "fs_stage1_w4.hpp"
 
 namespace {
 
@@ -403,6 +404,36 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     }
 }
 
+template <int KPW, int MAXW, int PFD>
+fs_status launch_w4(const Stage1Params& p, const uint8_t* scales, int nw, int wgs_override, hipStream_t st)
+{
+    const size_t lds = w4_lds_bytes(KPW, nw);
+    if (nw > MAXW || lds > kLdsPerCU) return FS_ERR_UNSUPPORTED;
+    auto kernel = stage1_w4_kernel<KPW, MAXW, PFD, false>;
+    int dev = 0;
+    const int cus = current_device_cus(&dev);
+    if (cus <= 0) return FS_ERR_HIP;
+    static PerDevice<MAXW + 1> state;
+    if (!state.attr[dev]) {
+        if (allow_lds(kernel, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.attr[dev] = true;
+    }
+    if (state.resident[dev][nw] == 0) {
+        int occ = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, nw * kWave, lds) != hipSuccess)
+            return FS_ERR_HIP;
+        std::lock_guard<std::mutex> lk(g_mu);
+        state.resident[dev][nw] = occ < 1 ? 1 : occ;
+    }
+    int per_cu = state.resident[dev][nw];
+    if (wgs_override > 0) per_cu = wgs_override;
+    int grid = cus * per_cu;
+    if (grid > p.T) grid = p.T;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(nw * kWave), lds, st, p, scales, nw);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
+}
+
 fs_status launch_stage2(const float* cand_val, const int32_t* cand_idx, int B, int T,
                         int32_t* out_idx, float* out_val, hipStream_t st)
 {
@@ -686,6 +717,68 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
     s = launch_stage1_w8(p, flags, st);
     if (s != FS_OK) return s;
     return launch_stage2(ws.cand_val, ws.cand_idx, B, p.T, out_idx, out_val, st);
+}
+
+fs_status flash_sample_w4(const void* hidden, const void* W4, const void* w_scales, int B, int D, int V,
+                          const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                          int64_t row_offset, int32_t vocab_offset, float* logits,
+                          int32_t* out_idx, float* out_val,
+                          void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W4, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK) return s;
+    if (flags & ~0x000FFF00u) return FS_ERR_UNSUPPORTED;
+    if (B == 0) return FS_OK;
+    if (B > 16 || (D & 511) != 0 || D > 8192) return FS_ERR_UNSUPPORTED;
+    if (!w_scales || !temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(w_scales, 16) || !aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(temperature, 4) ||
+        !aligned(row_seeds, 8) || !aligned(logits, 16))
+        return FS_ERR_ALIGN;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < workspace_bytes(B, V))
+        return FS_ERR_WORKSPACE;
+    const Workspace ws = carve(workspace, B, V);
+    Stage1Params p;
+    p.H = static_cast<const uint16_t*>(hidden);
+    p.W = static_cast<const uint16_t*>(W4);
+    p.B = B; p.D = D; p.V = V; p.T = num_tiles(V);
+    p.tau = temperature;
+    p.seed = seed; p.row_seeds = row_seeds;
+    p.row_offset = row_offset; p.vocab_offset = vocab_offset;
+    p.cand_val = ws.cand_val; p.cand_idx = ws.cand_idx; p.logits = logits;
+    p.bias = nullptr; p.allowed = nullptr; p.mask_stride = 0;
+    p.lse_max = nullptr; p.lse_sum = nullptr;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint8_t* sc = static_cast<const uint8_t*>(w_scales);
+    const int variant = (int)((flags >> 8) & 0xFFu);
+    const int wgs = (int)((flags >> 16) & 0xFu);
+    if (D <= 4096 && variant < 8) {   // eight waves of 16 K steps
+        switch (variant) {
+        case 0: case 2: s = launch_w4<16, 8, 2>(p, sc, D / 512, wgs, st); break;
+        case 1: s = launch_w4<16, 8, 1>(p, sc, D / 512, wgs, st); break;
+        case 4: s = launch_w4<16, 8, 4>(p, sc, D / 512, wgs, st); break;
+        default: return FS_ERR_UNSUPPORTED;
+        }
+    } else {                          // 32 K steps per wave (D % 1024 == 0 then)
+        if ((D & 1023) != 0) return FS_ERR_UNSUPPORTED;
+        switch (variant) {
+        case 0: case 1: case 9: s = launch_w4<32, 8, 1>(p, sc, D / 1024, wgs, st); break;
+        case 2: case 10: s = launch_w4<32, 8, 2>(p, sc, D / 1024, wgs, st); break;
+        default: return FS_ERR_UNSUPPORTED;
+        }
+    }
+    if (s != FS_OK) return s;
+    return launch_stage2(ws.cand_val, ws.cand_idx, B, p.T, out_idx, out_val, st);
+}
+
+fs_status flash_sample_mxfp4_decode(const void* codes, const uint8_t* scales, int n8, float* out, void* stream)
+{
+    if (n8 < 0) return FS_ERR_SHAPE;
+    if (n8 == 0) return FS_OK;
+    if (!codes || !scales || !out) return FS_ERR_NULL;
+    if (!aligned(codes, 4) || !aligned(out, 4)) return FS_ERR_ALIGN;
+    hipLaunchKernelGGL(mxfp4_decode_kernel, dim3((n8 + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint32_t*>(codes), scales, n8, out);
+    return hipGetLastError() == hipSuccess ? FS_OK : FS_ERR_HIP;
 }
 
 fs_status flash_sample_e4m3_decode(const uint8_t* codes, int n, float* out, void* stream)

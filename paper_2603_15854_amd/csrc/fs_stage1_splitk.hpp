@@ -54,6 +54,78 @@ struct SplitKCfg {
     }
 };
 
+// End of one vocabulary tile in the split-K kernels.  Every wave has stored its eight partial
+// 16 x 16 tiles (rows 16 r8 .. 16 r8 + 15 of the tile, this wave's slice of K) in `partial`
+// ([8][nw][64] f32x4).  Two barriers: after the first the partials are summed in a fixed wave
+// order (deterministic), scaled if the weights carry per-row scales, optionally stored as logits,
+// and run through the sampling epilogue; after the second one lane per batch column merges the
+// waves' candidates (and log-sum-exp states) and writes the tile's entry of the candidate buffer.
+template <bool FULL, bool ROW_SCALE>
+__device__ __forceinline__ void splitk_finish_tile(const Stage1Params& p, const RowEpi& repi, const f32x4* partial,
+                                                   float2* wave_cand, float2* wave_lse, int nw, int wave,
+                                                   int lane, int tile)
+{
+    const int n = lane & 15, g = lane >> 4;
+    const int B = p.B, V = p.V, T = p.T;
+    const int tile_row0 = tile * kVocabTile;
+    __syncthreads();   // all partial tiles of this vocabulary tile are in LDS
+    float best = -__builtin_inff();
+    int best_id = -1;
+    float lmax = -__builtin_inff(), lsum = 0.0f;
+    for (int r8 = wave; r8 < 8; r8 += nw) {
+        f32x4 y = partial[(r8 * nw) * 64 + lane];
+        for (int w = 1; w < nw; ++w) y += partial[(r8 * nw + w) * 64 + lane];
+        const int v0 = tile_row0 + r8 * 16 + 4 * g;   // local vocabulary row of y[0]
+        if constexpr (ROW_SCALE) {   // per-row scale of the FP8 weights
+            if (p.w_scale && v0 < V) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) y[j] *= p.w_scale[v0 + j < V ? v0 + j : V - 1];
+            }
+        }
+        if (v0 < V && n < B) {
+            if (p.logits) {
+                float* dst = p.logits + (size_t)n * V + v0;
+                if (v0 + 3 < V && (V & 3) == 0) {
+                    *reinterpret_cast<f32x4*>(dst) = y;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (v0 + j < V) dst[j] = y[j];
+                }
+            }
+            if (p.cand_val) epilogue_quad<FULL>(p, repi, y, v0, V, best, best_id, lmax, lsum);
+        }
+    }
+    cand_reduce_lane_groups(best, best_id);
+    if (g == 0) wave_cand[wave * 16 + n] = make_float2(best, __int_as_float(best_id));
+    if constexpr (FULL) {
+        lse_reduce_lane_groups(lmax, lsum);
+        if (g == 0) wave_lse[wave * 16 + n] = make_float2(lmax, lsum);
+    }
+    __syncthreads();   // wave candidates visible; partial buffer free again
+    if (wave == 0 && lane < 16 && n < B && p.cand_val) {
+        float bv = -__builtin_inff();
+        int bi = -1;
+        for (int w = 0; w < nw; ++w) {
+            const float2 c = wave_cand[w * 16 + n];
+            cand_merge(bv, bi, c.x, __float_as_int(c.y));
+        }
+        p.cand_val[(size_t)n * T + tile] = bv;
+        p.cand_idx[(size_t)n * T + tile] = bi;
+        if constexpr (FULL) {
+            if (p.lse_max) {
+                float m = -__builtin_inff(), sacc = 0.0f;
+                for (int w = 0; w < nw; ++w) {
+                    const float2 c = wave_lse[w * 16 + n];
+                    lse_merge(m, sacc, c.x, c.y);
+                }
+                p.lse_max[(size_t)n * T + tile] = m;
+                p.lse_sum[(size_t)n * T + tile] = sacc;
+            }
+        }
+    }
+}
+
 template <class Cfg, bool FULL = false>
 __global__ void __launch_bounds__(Cfg::kMaxWaves * kWave)
 stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
@@ -190,63 +262,7 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
 
         if (rt == 7) {
             const int tile = (int)blockIdx.x + (rtl >> 3) * (int)gridDim.x;
-            const int tile_row0 = tile * kVocabTile;
-            __syncthreads();   // all partial tiles of this vocabulary tile are in LDS
-            float best = -__builtin_inff();
-            int best_id = -1;
-            float lmax = -__builtin_inff(), lsum = 0.0f;
-            for (int r8 = wave; r8 < 8; r8 += nw) {
-                f32x4 y = partial[(r8 * nw) * 64 + lane];
-                for (int w = 1; w < nw; ++w) y += partial[(r8 * nw + w) * 64 + lane];
-                const int v0 = tile_row0 + r8 * 16 + 4 * g;   // local vocabulary row of y[0]
-                if constexpr (WB == 1) {   // per-row scale of the FP8 weights
-                    if (p.w_scale && v0 < V) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) y[j] *= p.w_scale[v0 + j < V ? v0 + j : V - 1];
-                    }
-                }
-                if (v0 < V && n < B) {
-                    if (p.logits) {
-                        float* dst = p.logits + (size_t)n * V + v0;
-                        if (v0 + 3 < V && (V & 3) == 0) {
-                            *reinterpret_cast<f32x4*>(dst) = y;
-                        } else {
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                if (v0 + j < V) dst[j] = y[j];
-                        }
-                    }
-                    if (p.cand_val) epilogue_quad<FULL>(p, repi, y, v0, V, best, best_id, lmax, lsum);
-                }
-            }
-            cand_reduce_lane_groups(best, best_id);
-            if (g == 0) wave_cand[wave * 16 + n] = make_float2(best, __int_as_float(best_id));
-            if constexpr (FULL) {
-                lse_reduce_lane_groups(lmax, lsum);
-                if (g == 0) wave_lse[wave * 16 + n] = make_float2(lmax, lsum);
-            }
-            __syncthreads();   // wave candidates visible; partial buffer free again
-            if (wave == 0 && lane < 16 && n < B && p.cand_val) {
-                float bv = -__builtin_inff();
-                int bi = -1;
-                for (int w = 0; w < nw; ++w) {
-                    const float2 c = wave_cand[w * 16 + n];
-                    cand_merge(bv, bi, c.x, __float_as_int(c.y));
-                }
-                p.cand_val[(size_t)n * T + tile] = bv;
-                p.cand_idx[(size_t)n * T + tile] = bi;
-                if constexpr (FULL) {
-                    if (p.lse_max) {
-                        float m = -__builtin_inff(), sacc = 0.0f;
-                        for (int w = 0; w < nw; ++w) {
-                            const float2 c = wave_lse[w * 16 + n];
-                            lse_merge(m, sacc, c.x, c.y);
-                        }
-                        p.lse_max[(size_t)n * T + tile] = m;
-                        p.lse_sum[(size_t)n * T + tile] = sacc;
-                    }
-                }
-            }
+            splitk_finish_tile<FULL, WB == 1>(p, repi, partial, wave_cand, wave_lse, nw, wave, lane, tile);
         }
     }
 }

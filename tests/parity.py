@@ -36,8 +36,9 @@ class Verdict:
 
 def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_ids=None,
           row_offset=0, vocab_offset=0, rows: Optional[Sequence[int]] = None,
-          bias=None, allowed_words=None, w8_scale=False) -> Verdict:
+          bias=None, allowed_words=None, w8_scale=False, w4_scales=None) -> Verdict:
     """w8_scale: not False when W holds FP8 (E4M3) codes; then it is the per-row scale array or None.
+    w4_scales: the E8M0 scale bytes when W holds MXFP4 codes.
     ref = oracle.sample(...) over the rows being judged (same order as `rows`, which index
     into H / gpu_idx; default all rows).  row_ids gives the global row word per judged row."""
     B = H.shape[0]
@@ -58,10 +59,12 @@ def judge(orc, H, W, tau, gpu_idx, gpu_val, ref, *, seed=0, row_seeds=None, row_
             else:
                 v.exact += 1
             continue
-        if gi < vocab_offset or gi >= vocab_offset + W.shape[0]:
+        if gi < vocab_offset or gi >= vocab_offset + W.shape[0]:   # W.shape[0] = V for every weight format
             v.failures.append((b, "index out of range", gi, gv))
             continue
-        if w8_scale is not False:
+        if w4_scales is not None:
+            s_pick = orc.score_at_w4(H, W, w4_scales, b, gi - vocab_offset, t, seed_b, row_word, gi)
+        elif w8_scale is not False:
             s_pick = orc.score_at_w8(H, W, w8_scale, b, gi - vocab_offset, t, seed_b, row_word, gi)
         elif bias is None and allowed_words is None:
             s_pick = orc.score_at(H, W, b, gi - vocab_offset, t, seed_b, row_word, gi)
