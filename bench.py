@@ -237,6 +237,27 @@ def main() -> int:
                               "rows": rows8}
         del W8d, scd, codes
 
+        # and on MXFP4 codes (E2M1, one E8M0 scale per 32 elements): the decode regime only
+        c4, s4 = wl.quantize_mxfp4(Wb)
+        W4d = torch.from_numpy(c4).cuda()
+        S4d = torch.from_numpy(s4).cuda()
+        rows4 = []
+        for Bq in (1, 16):
+            q = setup(Bq)
+
+            def fused4b(q):
+                fs.flash_sample_w4(q["Hd"], W4d, S4d, q["tau"], seed=w.seed, row_seeds=q["seeds"],
+                                   out_idx=q["oi"], out_val=q["ov"], workspace=q["ws"], stream=stream)
+
+            ms4 = timed(fused4b, q, 50, 10)
+            by4 = V * (D // 2 + D // 32) + 2 * Bq * D + 16 * Bq * T + 8 * Bq
+            rows4.append({"B": Bq, "fused_us": round(ms4 * 1e3, 2), "hbm_gbs": round(by4 / (ms4 * 1e-3) / 1e9, 1),
+                          "pct_hbm_peak": round(100.0 * by4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)})
+            del q
+        out["mxfp4_weights"] = {"format": "OCP MXFP4: E2M1 codes, one E8M0 scale per 32 elements, hidden bf16",
+                                "rows": rows4}
+        del W4d, S4d, c4, s4
+
     # ------------------------------------------------------------------ the paper's absolute-time shape
     # The paper prints absolute kernel times only for D=8192, V=128256 (appendix table of
     # tensor-parallel runtimes, TP=1 column; an 8 TB/s-class NVIDIA GPU, Triton kernel).  Same shape

@@ -162,25 +162,30 @@ def quantize_mxfp4(W_bits: np.ndarray):
     scales uint8 [V, D/32], E8M0).  Per block of 32: scale exponent = floor(log2(max|w|)) - 2 (the
     largest E2M1 magnitude is 6 = 1.5 * 2^2), elements rounded to the nearest E2M1 magnitude
     (ties to the even code), saturating at 6."""
-    Wf = bf16_bits_to_f32(W_bits).astype(np.float64)
-    V, D = Wf.shape
+    V, D = W_bits.shape
     assert D % 32 == 0
-    blocks = Wf.reshape(V, D // 32, 32)
-    amax = np.abs(blocks).max(axis=2)
-    exp = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 2, -127.0)
-    exp = np.clip(exp, -127, 127)
-    scaled = np.abs(blocks) / np.exp2(exp)[:, :, None]
-    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
-    # nearest grid point, ties to the even code
-    d = np.abs(scaled[..., None] - grid)
-    code = d.argmin(axis=-1)
-    nxt = np.minimum(code + 1, 7)
-    tie = (np.abs(scaled - grid[code]) == np.abs(scaled - grid[nxt])) & (nxt != code) & (code % 2 == 1)
-    code = np.where(tie, nxt, code).astype(np.uint8)
-    code |= (blocks < 0).astype(np.uint8) << 3
-    code = code.reshape(V, D)
-    packed = (code[:, 0::2] | (code[:, 1::2] << 4)).astype(np.uint8)
-    return np.ascontiguousarray(packed), np.ascontiguousarray((exp + 127).astype(np.uint8))
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
+    mid = (grid[:-1] + grid[1:]) / 2          # decision points between neighbouring magnitudes
+    packed = np.empty((V, D // 2), dtype=np.uint8)
+    scales = np.empty((V, D // 32), dtype=np.uint8)
+    for r0 in range(0, V, 2048):              # row chunks keep the temporaries small
+        Wf = bf16_bits_to_f32(W_bits[r0:r0 + 2048])
+        rows = Wf.shape[0]
+        blocks = Wf.reshape(rows, D // 32, 32)
+        amax = np.abs(blocks).max(axis=2)
+        exp = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 2, -127.0)
+        exp = np.clip(exp, -127, 125).astype(np.float32)
+        scaled = (np.abs(blocks) / np.exp2(exp)[:, :, None]).astype(np.float32)
+        # nearest magnitude; a value exactly on a decision point goes to the even code
+        code = np.searchsorted(mid, scaled.reshape(-1), side="left").astype(np.uint8)
+        on_mid = code < 7
+        on_mid &= scaled.reshape(-1) == mid[np.minimum(code, 6)]
+        code = np.where(on_mid & (code % 2 == 1), code + 1, code).astype(np.uint8)
+        code = code.reshape(rows, D)
+        code |= (Wf < 0).astype(np.uint8) << 3
+        packed[r0:r0 + rows] = code[:, 0::2] | (code[:, 1::2] << 4)
+        scales[r0:r0 + rows] = (exp + 127).astype(np.uint8)
+    return packed, scales
 
 
 def to_device_bf16(bits: np.ndarray):
