@@ -37,6 +37,11 @@
  *   - Returns FS_OK or an error code; never throws, never aborts.  Outputs are written only
  *     when FS_OK is returned.  B == 0 is a successful no-op.
  *   - Results are deterministic: the same inputs give the same outputs on every call.
+ *   - Entry points that take a workspace allocate nothing and touch only `stream`, so a call can
+ *     be recorded into a HIP graph.  The first call that uses a kernel configuration on a device
+ *     does one-time set-up (function attributes, an occupancy query): issue one eager call of the
+ *     same shape before capturing.  Calls on different streams share no state as long as their
+ *     workspaces and outputs differ.
  */
 #ifndef FLASH_SAMPLE_H
 #define FLASH_SAMPLE_H
