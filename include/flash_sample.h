@@ -70,7 +70,7 @@ typedef enum {
 /* bits 8..15: kernel variant for stage 1 (0 = automatic choice).  Every variant computes the
  * same candidates up to fp32 summation order; the tests use them to show tiling invariance. */
 #define FS_VARIANT(v) (((uint32_t)(v) & 0xFFu) << 8)
-#define FS_VARIANT_AUTO 0
+#define FS_VARIANT_AUTO 0   /* B <= 16 and D <= 4096: FS_VARIANT_SPLITK_B; otherwise FS_VARIANT_TILED2 */
 /* Split-K family (B <= 16, D <= 8192): the contraction dimension is split over the waves of a
  * workgroup and each wave keeps its slice of the hidden states in registers.  For D > 4096 all of
  * them run the same 64-k-steps-per-wave kernel; for D <= 4096 they differ in staging: */
@@ -80,8 +80,8 @@ typedef enum {
 #define FS_VARIANT_SPLITK_C 4 /* 16 k-steps per wave (twice the waves), 8-k-step stages */
 #define FS_VARIANT_SPLITK_D 5 /* 32 k-steps per wave, 8-k-step stages, 4 register sets */
 #define FS_VARIANT_SPLITK_E 6 /* 32 k-steps per wave, 4-k-step stages, two workgroups per CU */
-#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled {128,256,512} x {32,64,128} tiles, two register sets
-                                 in flight, XCD-paired batch tiles (default for B > 16) */
+#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled {128,256,512} x {32,64,128,256} tiles, one or two
+                                 register sets of prefetch, XCD-paired batch tiles */
 /* bits 16..19: tuning aid.  Split-K variants: workgroups per compute unit (0 = automatic).
  * FS_VARIANT_TILED2: tile shape (vocabulary rows x batch rows, waves), 0 = automatic,
  * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4),

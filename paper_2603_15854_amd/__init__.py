@@ -4,11 +4,11 @@ only -- every step of the method runs in the HIP kernels of ``libflashsample.so`
 PyTorch is used for device memory and streams, nothing else.  There is no CPU fallback: if the
 library is missing or a call fails, an exception is raised.
 
-Functions mirror the C names: ``flash_sample``, ``flash_sample_ex``, ``flash_sample_stage1``,
-``flash_sample_stage2``, ``flash_sample_unfused``, ``flash_lm_head_logits``,
-``flash_gumbel_argmax_logits``, ``flash_sample_noise``, ``flash_sample_gumbel_transform``,
-``flash_sample_stream_probe``,
-``flash_sample_num_tiles``, ``flash_sample_workspace_bytes``, ``fs_status_string``.
+Functions mirror the C names (``EXPORTS`` lists every symbol of the header): ``flash_sample``,
+``flash_sample_ex``, ``flash_sample_full``, ``flash_sample_grouped``, ``flash_group_choose``,
+``flash_sample_w8``, ``flash_sample_w4``, the stages ``flash_sample_stage1`` / ``flash_sample_stage2``,
+the comparison path ``flash_sample_unfused`` / ``flash_lm_head_logits`` /
+``flash_gumbel_argmax_logits``, the debug taps and ``flash_sample_stream_probe``.
 """
 from __future__ import annotations
 
