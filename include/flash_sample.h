@@ -90,6 +90,11 @@ typedef enum {
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 #define FS_TUNE_TILE_SHAPE(n) FS_TUNE_WGS_PER_CU(n)
 
+/* Which stage-1 kernel the automatic choice takes for a bf16 problem (B, D, V) on a device with
+ * `compute_units` CUs: 0 = the split-K kernel, otherwise the tile shape number of
+ * FS_TUNE_TILE_SHAPE.  Pure host logic (no device call); -1 for an invalid shape. */
+int flash_sample_kernel_choice(int B, int D, int V, int compute_units);
+
 /* Number of stage-1 candidates per row, T = ceil(V / FS_VOCAB_TILE). */
 int flash_sample_num_tiles(int V);
 

@@ -27,7 +27,7 @@ FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E, FS_VARIANT_TILED2
 
 # every symbol include/flash_sample.h declares
 EXPORTS = (
-    "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
+    "flash_sample_num_tiles", "flash_sample_kernel_choice", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
     "flash_sample_w8", "flash_sample_e4m3_decode", "flash_sample_w4", "flash_sample_mxfp4_decode",
@@ -68,6 +68,8 @@ def lib():
     vp, i32, i64, u32, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_uint64, C.c_size_t
     L.flash_sample_num_tiles.argtypes = [i32]
     L.flash_sample_num_tiles.restype = i32
+    L.flash_sample_kernel_choice.argtypes = [i32, i32, i32, i32]
+    L.flash_sample_kernel_choice.restype = i32
     L.flash_sample_workspace_bytes.argtypes = [i32, i32]
     L.flash_sample_workspace_bytes.restype = sz
     L.flash_sample.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, vp]
@@ -122,6 +124,10 @@ def fs_status_string(status: int) -> str:
 
 def flash_sample_num_tiles(V: int) -> int:
     return int(lib().flash_sample_num_tiles(int(V)))
+
+
+def flash_sample_kernel_choice(B: int, D: int, V: int, compute_units: int = 256) -> int:
+    return int(lib().flash_sample_kernel_choice(int(B), int(D), int(V), int(compute_units)))
 
 
 def flash_sample_workspace_bytes(B: int, V: int) -> int:

@@ -448,6 +448,14 @@ extern "C" {
 
 int flash_sample_num_tiles(int V) { return V > 0 ? num_tiles(V) : 0; }
 
+int flash_sample_kernel_choice(int B, int D, int V, int compute_units)
+{
+    if (B <= 0 || D <= 0 || V <= 0 || (D & 7) != 0 || compute_units <= 0) return -1;
+    if (B <= 16 && (D + 31) / 32 <= 32 * 4) return 0;
+    if (D % 64 != 0) return B <= 32 ? 8 : B <= 64 ? 5 : 4;
+    return pick_tile_shape(B, V, compute_units);
+}
+
 size_t flash_sample_workspace_bytes(int B, int V) { return workspace_bytes(B, V); }
 
 const char* fs_status_string(fs_status s)
