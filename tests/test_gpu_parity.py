@@ -469,3 +469,12 @@ def test_calls_on_two_streams_do_not_share_state(fs, orc):
     for s in range(2):
         for i, v in outs[s]:
             assert torch.equal(i, alone[s][0]) and torch.equal(v, alone[s][1])
+
+
+@pytest.mark.parametrize("shape", [(40, 64, 3), (300, 128, 1), (20, 8, 200), (17, 16, 129), (70, 24, 127),
+                                   (33, 4096, 2), (129, 64, 130)])
+def test_degenerate_shapes_on_the_tiled_kernels(fs, orc, shape):
+    # fewer vocabulary rows than one tile, one K step or less, batch just past a tile boundary
+    B, D, V = shape
+    print(f"degenerate shape {shape}", flush=True)
+    _small_case(fs, orc, B, D, V, 0, data_seed=640 + B + V)

@@ -113,3 +113,18 @@ def test_w8_shapes_outside_the_kernel_are_refused(fs):
     with pytest.raises(fs.FlashSampleError) as e:    # D % 16 != 0
         fs.flash_sample_w8(H[:4, :248].contiguous(), W8[:, :248].contiguous(), None, tau[:4])
     assert e.value.status == fs.FS_ERR_SHAPE
+
+
+@pytest.mark.parametrize("shape", [(20, 16, 200), (40, 64, 3), (130, 128, 1), (33, 192, 129)])
+def test_w8_degenerate_shapes_on_the_tiled_kernels(fs, orc, shape):
+    B, D, V = shape
+    print(f"w8 degenerate shape {shape}", flush=True)
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=880 + B + V)
+    codes, scale = wl.quantize_e4m3(W)
+    tau = np.linspace(0.7, 1.5, B).astype(np.float32)
+    ref = orc.sample_w8(H, codes, scale, tau, seed=4)
+    gi, gv = fs.flash_sample_w8(to_device_bf16(H), dev(codes, np.uint8), dev(scale, np.float32),
+                                dev(tau, np.float32), seed=4)
+    torch.cuda.synchronize()
+    v = judge(orc, H, codes, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, seed=4, w8_scale=scale)
+    assert v.ok, (shape, str(v), v.failures[:3])
