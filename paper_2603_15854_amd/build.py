@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashsample.so")
+DEMO = os.path.join(HERE, "examples", "c_abi_demo")
 
 
 def build(verbose: bool = False) -> str:
@@ -30,7 +31,25 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
+    build_demo()
     return LIB
+
+
+def build_demo() -> str:
+    """Compile examples/c_abi_demo.c (plain C against the header) and link it with the library."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [
+        "gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+        "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"),
+        os.path.join(HERE, "examples", "c_abi_demo.c"),
+        "-L", HERE, "-lflashsample", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+        "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", DEMO,
+    ]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stderr + "\n")
+        raise RuntimeError("building c_abi_demo failed")
+    return DEMO
 
 
 if __name__ == "__main__":
