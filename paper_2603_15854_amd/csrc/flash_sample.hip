@@ -204,35 +204,44 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   9: 256 x 256  8 waves, one per CU (accumulators take 128 VGPRs)
 //  10: 512 x 128  8 waves, one per CU, one register set of prefetch (128 accumulator VGPRs, 160 KB of LDS)
 // Every workgroup re-reads its hidden tile once per W tile and the kernels are bound by the bytes
-// that enter the CUs, so more vocabulary rows per workgroup is better -- as long as the coarser
-// grid still fills the CUs evenly.  Measured, fused call in us (D = 4096, V = 128256: 1002 tiles
-// of 128 rows | D = 3584, V = 152064: 1188 tiles, where 256- and 512-row grids leave the last
-// round mostly empty):
-//   B = 32:   shape 8 160 | 187    shape 6 161 | 230    shape 1 165-173 | 190
-//   B = 64:   shape 7 168 | 247    shape 5 170 | 190    shape 2 174 | 212
-//   B = 128:  shape 10 182         shape 3 195-203 | 243    shape 4 217 | 236
-//   B = 256:  shape 9 301          shape 3 376          (D = 8192: 562 against 699)
-// and at D = 8192, V = 128256, B <= 16: shape 6 307 us, shape 8 315, shape 1 317 (the split-K
-// kernel with 64 k-steps per wave: 325-335).
-// Hence: the one-per-CU shape (512 x 32 up to B = 32, 512 x 64 up to 64, 512 x 128 up to 128 -- or
-// 256 x 128 when only the 256-row grid fills its rounds --, 256 x 256 above, which reads W once
-// instead of once per 128 batch rows) when its
-// grid fills at least 90 % of its last round, else the four-wave shape with two workgroups per CU
-// (256 x 32, 128 x 64, 128 x 128), whose finer grid and overlapped epilogues tolerate a ragged tail.
-bool fills_rounds(long long wgs, int cus)
-{
-    const long long rounds = (wgs + cus - 1) / cus;
-    return wgs * 10 >= rounds * cus * 9;
-}
+// that enter the CUs (about 14 bytes per clock and CU, whatever the kernel), so a workgroup of
+// VT x BT takes time ~ (VT + BT) D, and a launch takes as long as its busiest CU:
+//      cost(shape) = ceil(workgroups / CUs) x (VT + BT)
+// (two workgroups per CU run side by side but share the CU's ingest rate, so they count like two
+// in a row; see the one correction in the code).  More vocabulary rows per workgroup means fewer hidden re-reads per W byte, until the
+// coarser grid leaves CUs idle in its last round.  The launcher takes the cheapest shape of the
+// batch class, the finer one on ties (its epilogues overlap).  Measured, fused call in us at
+// D = 4096 on 256 CUs (V: shapes by time, the rule's pick first):
+//   B = 32   V = 128256: s6 161, s8 160, s1 165-173 | 152064: s8 187, s6 230 | 201088: s6 257, s8 277
+//   B = 64   V = 50304: s2 74, s5 81, s7 108 | 100352: s7 132, s2 147, s5 150 | 152064: s5 190, s2 212, s7 247
+//   B = 128  V = 50304: s3 84, s4 99, s10 136 | 100352: s10 149, s3 172, s4 187 | 128256: s10 182, s3 195-203, s4 217
+//   B = 256  V = 32000: s3 84, s4 96, s9 124 | 128256: s9 301, s3 376 | 201088: s9 515, s4 570, s3 573
+// and at D = 8192, V = 128256, B <= 16: s6 307, s8 315, s1 317 (the split-K kernel with 64 k-steps
+// per wave: 325-335); B = 256: s9 562 against 699 for s3.
+struct TileShape {
+    int id, vt, bt;
+};
 
 int pick_tile_shape(int B, int V, int cus)
 {
-    if (B <= 32) return fills_rounds((V + 511) / 512, cus) ? 6 : 8;
-    if (B <= 64) return fills_rounds((V + 511) / 512, cus) ? 7 : 5;
-    if (B > 128 && fills_rounds((long long)((V + 255) / 256) * ((B + 255) / 256), cus)) return 9;
-    if (B <= 128 && fills_rounds((V + 511) / 512, cus)) return 10;
-    const long long nbt = (B + 127) / 128;
-    return fills_rounds((long long)((V + 255) / 256) * nbt, cus) ? 3 : 4;
+    static constexpr TileShape b32[] = {{8, 256, 32}, {6, 512, 32}};
+    static constexpr TileShape b64[] = {{5, 128, 64}, {2, 256, 64}, {7, 512, 64}};
+    static constexpr TileShape b128[] = {{4, 128, 128}, {3, 256, 128}, {10, 512, 128}};
+    static constexpr TileShape big[] = {{4, 128, 128}, {3, 256, 128}, {9, 256, 256}};
+    const TileShape* cand = B <= 32 ? b32 : B <= 64 ? b64 : B <= 128 ? b128 : big;
+    const int n = B <= 32 ? 2 : 3;
+    int best = cand[0].id;
+    long long best_cost = -1;
+    for (int i = 0; i < n; ++i) {   // fine to coarse; a coarser shape must be strictly cheaper
+        const long long wgs = (long long)((V + cand[i].vt - 1) / cand[i].vt) * ((B + cand[i].bt - 1) / cand[i].bt);
+        long long cost = ((wgs + cus - 1) / cus) * (cand[i].vt + cand[i].bt) * 10;
+        // the 128-row shapes with 64 or 128 columns run two workgroups per CU and hide their
+        // epilogues behind each other: measured about a tenth ahead of the count (D = 3584,
+        // V = 152064, B = 128: 128 x 128 233 us, 256 x 128 247 us at equal count)
+        if (cand[i].vt == 128 && cand[i].bt >= 64) cost = cost / 10 * 9;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = cand[i].id; }
+    }
+    return best;
 }
 
 // A hidden size that is not a multiple of the 64-element K step runs on the three two-per-CU
@@ -258,6 +267,7 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
         shape = pick_tile_shape(p.B, p.V, cus);
     }
     switch (shape) {
+    case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
     case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 2, 2>, FULL>(p, st);
@@ -271,7 +281,6 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
 
         if (shape == 1) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
-        if (shape == 2) return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     }
     return FS_ERR_UNSUPPORTED;
 }
@@ -379,6 +388,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     const int shape = variant >= 14 ? variant - 11 : variant >= 4 ? variant - 1 : pick_tile_shape(p.B, p.V, cus);
     if (variant < 14 && p.D % 128 == 0) {
         switch (shape) {
+        case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
         case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
         case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 1, 2>, false, 1, true>(p, st);
         case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 1, 2>, false, 1, true>(p, st);
@@ -392,6 +402,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
         }
     }
     switch (shape) {
+    case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, false, 1>(p, st);
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 2, 2, 256>, false, 1>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 4, 2>, false, 1>(p, st);
     case 5: return launch_tiled2<Tiled2Cfg<64, 2, 2, 4, 2>, false, 1>(p, st);

@@ -132,14 +132,16 @@ def test_bad_arguments_are_rejected_before_any_device_work():
 
 def test_kernel_choice_by_shape():
     # the launcher's rule: split-K while the hidden slice of a wave fits its registers, else the
-    # largest tile shape whose grid fills its last round of workgroups (256 CUs)
+    # tile shape with the cheapest busiest CU, ceil(workgroups / CUs) * (rows + columns), finer on ties
     kc = fs.flash_sample_kernel_choice
     assert [kc(B, 4096, 128256) for B in (1, 16)] == [0, 0]
     assert [kc(B, 4096, 128256) for B in (17, 32, 64, 128, 129, 256, 512)] == [6, 6, 7, 10, 9, 9, 9]
     assert kc(16, 8192, 128256) == 6 and kc(1, 7168, 129280) == 6          # wide hidden sizes: tiled
-    # V = 152064: 297 tiles of 512 rows or 594 of 256 leave the last round mostly empty
-    assert [kc(B, 3584, 152064) for B in (32, 64, 128)] == [8, 5, 4]
-    assert kc(256, 3584, 152064) == 3 and kc(256, 8192, 128256) == 9     # 1188 workgroups of 256 x 128: 4.64 rounds
+    # the choices measured fastest on the machine (D = 4096, 256 CUs)
+    assert [kc(32, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [8, 8, 6, 8, 6]
+    assert [kc(64, 4096, V) for V in (32000, 50304, 100352, 152064)] == [5, 2, 7, 5]
+    assert [kc(128, 4096, V) for V in (32000, 50304, 100352, 152064, 201088, 256000)] == [4, 3, 10, 4, 10, 10]
+    assert [kc(256, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [3, 9, 9, 9, 9]
     assert [kc(B, 520, 128256) for B in (20, 64, 200)] == [8, 5, 4]        # D % 64 != 0
     assert kc(4, 4096, 1000) == 0 and kc(40, 4096, 1000) == 5              # a handful of tiles: fine shapes
     assert kc(0, 4096, 10) == -1 and kc(4, 4100, 10) == -1 and kc(4, 4096, 10, 0) == -1
