@@ -224,12 +224,12 @@ struct TileShape {
 
 int pick_tile_shape(int B, int V, int cus)
 {
-    static constexpr TileShape b32[] = {{8, 256, 32}, {6, 512, 32}};
+    static constexpr TileShape b32[] = {{1, 128, 32}, {8, 256, 32}, {6, 512, 32}};
     static constexpr TileShape b64[] = {{5, 128, 64}, {2, 256, 64}, {7, 512, 64}};
     static constexpr TileShape b128[] = {{4, 128, 128}, {3, 256, 128}, {10, 512, 128}};
     static constexpr TileShape big[] = {{4, 128, 128}, {3, 256, 128}, {9, 256, 256}};
     const TileShape* cand = B <= 32 ? b32 : B <= 64 ? b64 : B <= 128 ? b128 : big;
-    const int n = B <= 32 ? 2 : 3;
+    const int n = 3;
     int best = cand[0].id;
     long long best_cost = -1;
     for (int i = 0; i < n; ++i) {   // fine to coarse; a coarser shape must be strictly cheaper
@@ -267,6 +267,7 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
         shape = pick_tile_shape(p.B, p.V, cus);
     }
     switch (shape) {
+    case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
     case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, FULL>(p, st);
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, FULL>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 2, 2>, FULL>(p, st);
@@ -277,10 +278,6 @@ fs_status launch_tiled2_auto(const Stage1Params& p, int shape, hipStream_t st)
     case 9: return launch_tiled2<Tiled2Cfg<256, 4, 2, 1, 2, 256, 2>, FULL>(p, st);
     case 10: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 512, 1>, FULL>(p, st);
     default: break;
-    }
-    if constexpr (!FULL) {   // shapes the launcher never picks: plain epilogue only
-
-        if (shape == 1) return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, FULL>(p, st);
     }
     return FS_ERR_UNSUPPORTED;
 }
@@ -388,6 +385,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
     const int shape = variant >= 14 ? variant - 11 : variant >= 4 ? variant - 1 : pick_tile_shape(p.B, p.V, cus);
     if (variant < 14 && p.D % 128 == 0) {
         switch (shape) {
+        case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 2>, false, 1, true>(p, st);
         case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
         case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true>(p, st);
         case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 1, 2>, false, 1, true>(p, st);
@@ -402,6 +400,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, uint32_t flags, hipStream_t st
         }
     }
     switch (shape) {
+    case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 4>, false, 1>(p, st);
     case 2: return launch_tiled2<Tiled2Cfg<64, 4, 2, 2, 2, 256>, false, 1>(p, st);
     case 3: return launch_tiled2<Tiled2Cfg<128, 4, 2, 2, 2, 256>, false, 1>(p, st);
     case 4: return launch_tiled2<Tiled2Cfg<128, 2, 2, 4, 2>, false, 1>(p, st);
