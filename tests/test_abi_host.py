@@ -176,3 +176,11 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(fs, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         fs.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
