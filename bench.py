@@ -56,8 +56,10 @@ def main() -> int:
     import numpy as np
     import torch
 
+    import fs_io_model as iom
     import fs_workloads as wl
     import paper_2603_15854_amd as fs
+    from paper_2603_15854_amd import measure as fsm
     from fs_workloads import to_device_bf16
 
     if not torch.cuda.is_available():
@@ -133,7 +135,7 @@ def main() -> int:
     B = args.batch
     s = setup(B)
     ms = timed(fused, s, args.steps, args.warmup)
-    bytes_fused = fs.io_model_bytes(B, D, V, fused=True)
+    bytes_fused = iom.io_model_bytes(B, D, V, fused=True)
     gbs = bytes_fused / (ms * 1e-3) / 1e9
 
     # dominant kernel (stage 1) alone, same stream, same launch configuration
@@ -182,9 +184,9 @@ def main() -> int:
         sink = torch.zeros(1, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(Wd)
         for _ in range(args.calibrate):
-            fs.flash_sample_stream_probe(Wd, sink=sink, stream=stream)            # reads 2*V*D bytes
+            fsm.flash_measure_stream_probe(Wd, sink=sink, stream=stream)            # reads 2*V*D bytes
         for _ in range(args.calibrate):
-            fs.flash_sample_stream_probe(Wd, dst=dst, sink=sink, stream=stream)   # reads and writes 2*V*D
+            fsm.flash_measure_stream_probe(Wd, dst=dst, sink=sink, stream=stream)   # reads and writes 2*V*D
         torch.cuda.synchronize()
         out["calibration"] = {"probe_bytes": int(Wd.numel() * 2), "launches_each": args.calibrate}
         del dst
@@ -198,7 +200,7 @@ def main() -> int:
             ss["lg"] = torch.empty((Bs, V), dtype=torch.float32, device="cuda")
             f_ms = timed(fused, ss, steps, 10)
             u_ms = timed(unfused, ss, steps, 10)
-            bf = fs.io_model_bytes(Bs, D, V, fused=True)
+            bf = iom.io_model_bytes(Bs, D, V, fused=True)
             sweep.append({
                 "B": Bs,
                 "fused_us": round(f_ms * 1e3, 2),
@@ -311,7 +313,7 @@ def main() -> int:
             if time.perf_counter() - t0 >= args.cpu_seconds and calls >= 3:
                 break
         dt = (time.perf_counter() - t0) / calls
-        bytes_c = fs.io_model_bytes(Bc, D, V, fused=True)
+        bytes_c = iom.io_model_bytes(Bc, D, V, fused=True)
         out["cpu_baseline"] = {
             "value": round(bytes_c / dt / 1e9, 4),
             "unit": "GB/s",

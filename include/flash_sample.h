@@ -62,38 +62,38 @@ typedef enum {
     FS_ERR_ALIGN = 3,       /* a pointer is not aligned as required */
     FS_ERR_WORKSPACE = 4,   /* workspace missing or smaller than flash_sample_workspace_bytes */
     FS_ERR_HIP = 5,         /* a HIP runtime call failed (launch, allocation) */
-    FS_ERR_UNSUPPORTED = 6  /* unknown flag or a kernel variant that cannot run this shape */
+    FS_ERR_UNSUPPORTED = 6, /* unknown flag or a kernel variant that cannot run this shape */
+    FS_ERR_DEVICE = 7       /* current device ordinal >= 64 (the size of the per-device tables) */
 } fs_status;
 
 /* flags for the *_ex entry points */
 #define FS_FLAG_NONE 0u
+/* Deterministic decoding: no noise is drawn and every row returns the arg max of its transformed
+ * logits (lowest id on ties), out_val = that logit.  The tau -> 0 limit of the draw; also what
+ * the epilogue costs can be measured against. */
+#define FS_FLAG_GREEDY 0x1u
+/* Evaluate the Gumbel transform g = -log(-log u) with the device library's log1pf / logf instead
+ * of the hardware log2 (the exact-math mode of the appendix "Numerically Stable and Fast Gumbel
+ * Generation"; the default is its fast-math mode: series / v_log_f32).  The two modes differ by
+ * a few ulp of g, so a draw may differ between them on rows whose top two scores are that close. */
+#define FS_FLAG_EXACT_LOG 0x2u
 /* bits 8..15: kernel variant for stage 1 (0 = automatic choice).  Every variant computes the
  * same candidates up to fp32 summation order; the tests use them to show tiling invariance. */
 #define FS_VARIANT(v) (((uint32_t)(v) & 0xFFu) << 8)
-#define FS_VARIANT_AUTO 0   /* B <= 16 and D <= 4096: FS_VARIANT_SPLITK_B; otherwise FS_VARIANT_TILED2 */
-/* Split-K family (B <= 16, D <= 8192): the contraction dimension is split over the waves of a
- * workgroup and each wave keeps its slice of the hidden states in registers.  For D > 4096 all of
- * them run the same 64-k-steps-per-wave kernel; for D <= 4096 they differ in staging: */
-#define FS_VARIANT_SPLITK_A 1 /* 32 k-steps per wave, 16-k-step LDS stages, 2 register sets */
-#define FS_VARIANT_SPLITK_B 2 /* 32 k-steps per wave, 8-k-step stages, 2 register sets */
-#define FS_VARIANT_TILED 3    /* any B, any D: LDS-tiled 128 x (16*NB) workgroup tiles */
-#define FS_VARIANT_SPLITK_C 4 /* 16 k-steps per wave (twice the waves), 8-k-step stages */
-#define FS_VARIANT_SPLITK_D 5 /* 32 k-steps per wave, 8-k-step stages, 4 register sets */
-#define FS_VARIANT_SPLITK_E 6 /* 32 k-steps per wave, 4-k-step stages, two workgroups per CU */
-#define FS_VARIANT_TILED2 7   /* any B, any D: LDS-tiled {128,256,512} x {32,64,128,256} tiles, one or two
-                                 register sets of prefetch, XCD-paired batch tiles */
-/* bits 16..19: tuning aid.  Split-K variants: workgroups per compute unit (0 = automatic).
+#define FS_VARIANT_AUTO 0   /* B <= 16 and D <= 4096: FS_VARIANT_SPLITK; otherwise FS_VARIANT_TILED2 */
+/* B <= 16, D <= 4096: the contraction dimension is split over the waves of a workgroup and each
+ * wave keeps its slice of the hidden states in registers (32 k-steps of 32 elements per wave). */
+#define FS_VARIANT_SPLITK 2
+/* any B, any D: LDS-tiled {128,256,512} x {32,64,128,256} tiles, one or two register sets of
+ * prefetch, XCD-paired batch tiles */
+#define FS_VARIANT_TILED2 7
+/* bits 16..19: tuning aid.  FS_VARIANT_SPLITK: workgroups per compute unit (0 = automatic).
  * FS_VARIANT_TILED2: tile shape (vocabulary rows x batch rows, waves), 0 = automatic,
  * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4),
  * 6 = 512x32 (8), 7 = 512x64 (8), 8 = 256x32 (4), 9 = 256x256 (8), 10 = 512x128 (8).  A hidden size
  * that is not a multiple of 64 always runs on shapes 8, 5 or 4 (by batch size). */
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 #define FS_TUNE_TILE_SHAPE(n) FS_TUNE_WGS_PER_CU(n)
-
-/* Which stage-1 kernel the automatic choice takes for a bf16 problem (B, D, V) on a device with
- * `compute_units` CUs: 0 = the split-K kernel, otherwise the tile shape number of
- * FS_TUNE_TILE_SHAPE.  Pure host logic (no device call); -1 for an invalid shape. */
-int flash_sample_kernel_choice(int B, int D, int V, int compute_units);
 
 /* Number of stage-1 candidates per row, T = ceil(V / FS_VOCAB_TILE). */
 int flash_sample_num_tiles(int V);
@@ -145,7 +145,7 @@ fs_status flash_sample_ex(const void* hidden, const void* W, int B, int D, int V
  *                      (>= ceil(V/32)), or 0: one bit row shared by every batch row
  *   out_lse            NULL, or fp32 [B]
  *   workspace          at least flash_sample_full_workspace_bytes(B, V) bytes, 256-byte aligned
- *   flags              FS_FLAG_NONE (the automatic kernel choice only)
+ *   flags              FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG (the automatic kernel choice only)
  * A row whose ids are all masked returns idx = -1, val = -inf, lse = -inf.  The order
  * bias -> temperature -> mask is this library's reading; the paper does not fix it.
  */
@@ -219,9 +219,9 @@ fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_s
  *   W8, w_scale   device pointers, 16-byte aligned; D % 16 == 0
  *   logits        NULL, or fp32 [B, V]: also store y (for tests and the comparison path)
  *   workspace     at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
- *   flags         FS_FLAG_NONE; or, as a tuning aid, FS_VARIANT(v): 1..3 split-K forms (B <= 16 only),
- *                 4..10 tile shapes 3..9 of FS_TUNE_TILE_SHAPE with the codes kept in LDS where that
- *                 fits, 14..20 the same shapes widening the codes when a K step is parked
+ *   flags         FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG; or, as a tuning aid, FS_VARIANT_SPLITK
+ *                 (B <= 16, D <= 8192) / FS_VARIANT_TILED2 with FS_TUNE_TILE_SHAPE (shapes 9 and 10
+ *                 run as shape 3; D % 128 != 0 always runs on shapes 8, 5 or 4)
  * NaN codes (S.1111.111) propagate to NaN logits, which never win.
  */
 fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_scale, int B, int D, int V,
@@ -244,8 +244,7 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
  *                  254 overflow the bf16 range of a scaled element, 255 is NaN)
  *   logits         NULL, or fp32 [B, V]: also store y
  *   workspace      at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
- *   flags          FS_FLAG_NONE, or FS_TUNE_WGS_PER_CU(n) / FS_VARIANT(1|2|4: row-tiles in flight;
- *                  9|10: the 32-K-step form with 1|2 row-tiles in flight)
+ *   flags          FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG, FS_TUNE_WGS_PER_CU(n)
  */
 fs_status flash_sample_w4(const void* hidden, const void* W4, const void* w_scales, int B, int D, int V,
                           const float* temperature, uint64_t seed, const uint64_t* row_seeds,
@@ -310,14 +309,8 @@ fs_status flash_sample_noise(uint64_t seed, int64_t row, int32_t v0, int n, floa
 
 /* Debug tap of the uniform -> Gumbel map alone: g_out[k] = g(words[k]) for 32-bit words given by
  * the caller (device arrays of n elements), so a test can sweep every exponent and the edge words. */
-fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_out, void* stream);
-
-/* Measurement aid, not part of the method: a plain streaming kernel of known size.
- * dst == NULL: read `bytes` bytes from src (the read-bandwidth ceiling of the device);
- * dst != NULL: copy src to dst.  bytes must be a multiple of 16, pointers 16-byte aligned.
- * `sink` is a 4-byte device location the read variant may write to. */
-fs_status flash_sample_stream_probe(void* dst, const void* src, size_t bytes, uint32_t* sink,
-                                    void* stream);
+fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_out, void* stream,
+                                        uint32_t flags /* FS_FLAG_NONE or FS_FLAG_EXACT_LOG */);
 
 /* Static description of an error code (never NULL). */
 const char* fs_status_string(fs_status s);

@@ -5,10 +5,14 @@ PyTorch is used for device memory and streams, nothing else.  There is no CPU fa
 library is missing or a call fails, an exception is raised.
 
 Functions mirror the C names (``EXPORTS`` lists every symbol of the header): ``flash_sample``,
-``flash_sample_ex``, ``flash_sample_full``, ``flash_sample_grouped``, ``flash_group_choose``,
-``flash_sample_w8``, ``flash_sample_w4``, the stages ``flash_sample_stage1`` / ``flash_sample_stage2``,
-the comparison path ``flash_sample_unfused`` / ``flash_lm_head_logits`` /
-``flash_gumbel_argmax_logits``, the debug taps and ``flash_sample_stream_probe``.
+``flash_sample_ex``, ``flash_sample_full``, ``flash_sample_grouped``,
+``flash_group_choose``, ``flash_sample_w8``, ``flash_sample_w4``, the stages ``flash_sample_stage1`` /
+``flash_sample_stage2``, the comparison path ``flash_sample_unfused`` / ``flash_lm_head_logits`` /
+``flash_gumbel_argmax_logits`` and the debug taps.  The measurement aids of
+``include/flash_sample_measure.h`` are bound in ``paper_2603_15854_amd.measure``.
+
+Every tensor argument is checked for device, dtype, contiguity and length before its pointer is
+handed over: the C side cannot see any of these.
 """
 from __future__ import annotations
 
@@ -21,21 +25,23 @@ LIB_PATH = os.path.join(_HERE, "libflashsample.so")
 
 FS_OK = 0
 FS_ERR_NULL, FS_ERR_SHAPE, FS_ERR_ALIGN, FS_ERR_WORKSPACE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = 1, 2, 3, 4, 5, 6
+FS_ERR_DEVICE = 7
 FS_VOCAB_TILE = 128
-FS_VARIANT_AUTO, FS_VARIANT_SPLITK_A, FS_VARIANT_SPLITK_B, FS_VARIANT_TILED = 0, 1, 2, 3
-FS_VARIANT_SPLITK_C, FS_VARIANT_SPLITK_D, FS_VARIANT_SPLITK_E, FS_VARIANT_TILED2 = 4, 5, 6, 7
+FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG = 0, 1, 2
+FS_VARIANT_AUTO, FS_VARIANT_SPLITK, FS_VARIANT_TILED2 = 0, 2, 7
 
 # every symbol include/flash_sample.h declares
 EXPORTS = (
-    "flash_sample_num_tiles", "flash_sample_kernel_choice", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
+    "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
     "flash_sample_w8", "flash_sample_e4m3_decode", "flash_sample_w4", "flash_sample_mxfp4_decode",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
     "flash_gumbel_argmax_logits", "flash_sample_noise", "flash_sample_gumbel_transform",
-    "flash_sample_stream_probe",
     "fs_status_string",
 )
+# every symbol include/flash_sample_measure.h declares
+MEASURE_EXPORTS = ("flash_measure_stream_probe", "flash_measure_kernel_choice")
 
 
 def FS_VARIANT(v: int) -> int:
@@ -44,6 +50,9 @@ def FS_VARIANT(v: int) -> int:
 
 def FS_TUNE_WGS_PER_CU(n: int) -> int:
     return (n & 0xF) << 16
+
+
+FS_TUNE_TILE_SHAPE = FS_TUNE_WGS_PER_CU
 
 
 class FlashSampleError(RuntimeError):
@@ -68,8 +77,8 @@ def lib():
     vp, i32, i64, u32, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_uint64, C.c_size_t
     L.flash_sample_num_tiles.argtypes = [i32]
     L.flash_sample_num_tiles.restype = i32
-    L.flash_sample_kernel_choice.argtypes = [i32, i32, i32, i32]
-    L.flash_sample_kernel_choice.restype = i32
+    L.flash_measure_kernel_choice.argtypes = [i32, i32, i32, i32]
+    L.flash_measure_kernel_choice.restype = i32
     L.flash_sample_workspace_bytes.argtypes = [i32, i32]
     L.flash_sample_workspace_bytes.restype = sz
     L.flash_sample.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, vp]
@@ -108,10 +117,10 @@ def lib():
     L.flash_gumbel_argmax_logits.restype = i32
     L.flash_sample_noise.argtypes = [u64, i64, C.c_int32, i32, vp, vp]
     L.flash_sample_noise.restype = i32
-    L.flash_sample_gumbel_transform.argtypes = [vp, i32, vp, vp]
+    L.flash_sample_gumbel_transform.argtypes = [vp, i32, vp, vp, u32]
     L.flash_sample_gumbel_transform.restype = i32
-    L.flash_sample_stream_probe.argtypes = [vp, vp, sz, vp, vp]
-    L.flash_sample_stream_probe.restype = i32
+    L.flash_measure_stream_probe.argtypes = [vp, vp, sz, vp, vp]
+    L.flash_measure_stream_probe.restype = i32
     L.fs_status_string.argtypes = [i32]
     L.fs_status_string.restype = C.c_char_p
     _lib = L
@@ -126,25 +135,44 @@ def flash_sample_num_tiles(V: int) -> int:
     return int(lib().flash_sample_num_tiles(int(V)))
 
 
-def flash_sample_kernel_choice(B: int, D: int, V: int, compute_units: int = 256) -> int:
-    return int(lib().flash_sample_kernel_choice(int(B), int(D), int(V), int(compute_units)))
-
-
 def flash_sample_workspace_bytes(B: int, V: int) -> int:
     return int(lib().flash_sample_workspace_bytes(int(B), int(V)))
 
 
 # ----------------------------------------------------------------------------- marshalling
 
-def _ptr(t) -> Optional[int]:
-    """Device pointer of a torch tensor (None -> NULL)."""
+def _ptr(t, dtype=None, numel: Optional[int] = None, name: str = "tensor") -> Optional[int]:
+    """Device pointer of a torch tensor (None -> NULL) after checking what the C side cannot see:
+    device, contiguity, and -- when given -- dtype and the minimum number of elements."""
     if t is None:
         return None
     if not t.is_cuda:
-        raise ValueError("expected a device tensor")
+        raise ValueError(f"{name}: expected a device tensor")
     if not t.is_contiguous():
-        raise ValueError("expected a contiguous tensor")
+        raise ValueError(f"{name}: expected a contiguous tensor")
+    if dtype is not None:
+        ok = t.dtype in dtype if isinstance(dtype, (tuple, list)) else t.dtype == dtype
+        if not ok:
+            raise ValueError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name}: expected at least {numel} elements, got {t.numel()}")
     return t.data_ptr()
+
+
+def _f32(t, n, name):
+    import torch
+    return _ptr(t, torch.float32, n, name)
+
+
+def _i32(t, n, name):
+    import torch
+    return _ptr(t, torch.int32, n, name)
+
+
+def _seeds(t, n):
+    """row_seeds: 64-bit patterns, carried as int64 (torch has no uint64 arithmetic)."""
+    import torch
+    return _ptr(t, (torch.int64, torch.uint64), n, "row_seeds")
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -174,15 +202,26 @@ def _outputs(B, device, out_idx, out_val):
         out_idx = torch.empty(B, dtype=torch.int32, device=device)
     if out_val is None:
         out_val = torch.empty(B, dtype=torch.float32, device=device)
+    _i32(out_idx, B, "out_idx")
+    _f32(out_val, B, "out_val")
     return out_idx, out_val
 
 
-def _workspace(B, V, device, workspace):
+def _scratch(need: int, device, workspace, stream):
+    """The caller's workspace, or a fresh one.  A fresh one is a temporary: when the call runs on a
+    stream other than torch's current one the allocator is told (record_stream), so the block is
+    not handed out again while the kernels still use it."""
     import torch
-    need = flash_sample_workspace_bytes(B, V)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+        if stream is not None and stream != torch.cuda.current_stream():
+            workspace.record_stream(stream)
+    _ptr(workspace, None, None, "workspace")
     return workspace, workspace.numel() * workspace.element_size()
+
+
+def _workspace(B, V, device, workspace, stream=None):
+    return _scratch(flash_sample_workspace_bytes(B, V), device, workspace, stream)
 
 
 # ----------------------------------------------------------------------------- entry points
@@ -192,7 +231,7 @@ def flash_sample(hidden, W, temperature, seed: int = 0, out_idx=None, out_val=No
     Runs on the null stream (the C entry point's contract)."""
     B, D, V = _shapes(hidden, W)
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    st = lib().flash_sample(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
+    st = lib().flash_sample(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
                             _ptr(out_idx), _ptr(out_val))
     _check(st, "flash_sample")
     return out_idx, out_val
@@ -203,9 +242,9 @@ def flash_sample_ex(hidden, W, temperature, seed: int = 0, row_seeds=None, row_o
                     flags: int = 0):
     B, D, V = _shapes(hidden, W)
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
-    st = lib().flash_sample_ex(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
-                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(out_idx),
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace, stream)
+    st = lib().flash_sample_ex(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
+                               _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _ptr(out_idx),
                                _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_ex")
     return out_idx, out_val
@@ -213,6 +252,19 @@ def flash_sample_ex(hidden, W, temperature, seed: int = 0, row_seeds=None, row_o
 
 def flash_sample_full_workspace_bytes(B: int, V: int) -> int:
     return int(lib().flash_sample_full_workspace_bytes(int(B), int(V)))
+
+
+def _mask_args(allowed, B, V):
+    """(pointer, stride in words) of an allowed-id bit mask: [ceil(V/32)] shared or [B, >= ceil(V/32)]."""
+    import torch
+    if allowed is None:
+        return None, 0
+    words = (V + 31) // 32
+    if allowed.dim() == 2:
+        if allowed.shape[0] < B or allowed.shape[1] < words:
+            raise ValueError("allowed: expected [B, >= ceil(V/32)] words")
+        return _ptr(allowed, (torch.int32, torch.uint32), None, "allowed"), allowed.shape[1]
+    return _ptr(allowed, (torch.int32, torch.uint32), words, "allowed"), 0
 
 
 def flash_sample_full(hidden, W, temperature, seed: int = 0, row_seeds=None, row_offset: int = 0,
@@ -225,17 +277,12 @@ def flash_sample_full(hidden, W, temperature, seed: int = 0, row_seeds=None, row
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
     if want_lse and out_lse is None:
         out_lse = torch.empty(B, dtype=torch.float32, device=hidden.device)
-    stride = 0
-    if allowed is not None and allowed.dim() == 2:
-        stride = allowed.shape[1]
-    need = flash_sample_full_workspace_bytes(B, V)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
-    st = lib().flash_sample_full(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
-                                 _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(bias),
-                                 _ptr(allowed), int(stride), _ptr(out_idx), _ptr(out_val), _ptr(out_lse),
-                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                 _stream_ptr(stream), int(flags))
+    mask_ptr, stride = _mask_args(allowed, B, V)
+    workspace, ws_bytes = _scratch(flash_sample_full_workspace_bytes(B, V), hidden.device, workspace, stream)
+    st = lib().flash_sample_full(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
+                                 _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _f32(bias, V, "bias"),
+                                 mask_ptr, int(stride), _ptr(out_idx), _ptr(out_val), _f32(out_lse, B, "out_lse"),
+                                 _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_full")
     return out_idx, out_val, out_lse
 
@@ -251,9 +298,10 @@ def flash_sample_w8(hidden, W8, w_scale, temperature, seed: int = 0, row_seeds=N
         raise ValueError("hidden must be [B, D] and W8 [V, D]")
     B, D, V = hidden.shape[0], hidden.shape[1], W8.shape[0]
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
-    st = lib().flash_sample_w8(_ptr(hidden), _ptr(W8), _ptr(w_scale), B, D, V, _ptr(temperature), int(seed),
-                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace, stream)
+    st = lib().flash_sample_w8(_ptr(hidden), _ptr(W8), _f32(w_scale, V, "w_scale"), B, D, V,
+                               _f32(temperature, B, "temperature"), int(seed),
+                               _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _f32(logits, B * V, "logits"),
                                _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream),
                                int(flags))
     _check(st, "flash_sample_w8")
@@ -271,9 +319,10 @@ def flash_sample_w4(hidden, W4, w_scales, temperature, seed: int = 0, row_seeds=
     if W4.dim() != 2 or W4.shape[1] * 2 != D or tuple(w_scales.shape) != (V, D // 32):
         raise ValueError("W4 must be [V, D/2] and w_scales [V, D/32]")
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
-    st = lib().flash_sample_w4(_ptr(hidden), _ptr(W4), _ptr(w_scales), B, D, V, _ptr(temperature), int(seed),
-                               _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace, stream)
+    st = lib().flash_sample_w4(_ptr(hidden), _ptr(W4), _ptr(w_scales), B, D, V,
+                               _f32(temperature, B, "temperature"), int(seed),
+                               _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _f32(logits, B * V, "logits"),
                                _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream),
                                int(flags))
     _check(st, "flash_sample_w4")
@@ -286,7 +335,8 @@ def flash_sample_mxfp4_decode(codes, scales, out=None, stream=None):
     n8 = scales.numel()
     if out is None:
         out = torch.empty(8 * n8, dtype=torch.float32, device=codes.device)
-    _check(lib().flash_sample_mxfp4_decode(_ptr(codes), _ptr(scales), n8, _ptr(out), _stream_ptr(stream)),
+    _check(lib().flash_sample_mxfp4_decode(_ptr(codes, torch.uint8, 4 * n8, "codes"), _ptr(scales, torch.uint8),
+                                           n8, _f32(out, 8 * n8, "out"), _stream_ptr(stream)),
            "flash_sample_mxfp4_decode")
     return out
 
@@ -296,7 +346,7 @@ def flash_sample_e4m3_decode(codes, out=None, stream=None):
     n = codes.numel()
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=codes.device)
-    _check(lib().flash_sample_e4m3_decode(_ptr(codes), n, _ptr(out), _stream_ptr(stream)),
+    _check(lib().flash_sample_e4m3_decode(_ptr(codes, torch.uint8), n, _f32(out, n, "out"), _stream_ptr(stream)),
            "flash_sample_e4m3_decode")
     return out
 
@@ -325,18 +375,13 @@ def flash_sample_grouped(hidden, W, temperature, group_tiles: int = 1, mode: int
         m = flash_sample_num_groups(V, group_tiles)
         gl = torch.empty((B, m), dtype=torch.float32, device=hidden.device)
         gs = torch.empty((B, m), dtype=torch.int32, device=hidden.device)
-    stride = 0
-    if allowed is not None and allowed.dim() == 2:
-        stride = allowed.shape[1]
-    need = flash_sample_full_workspace_bytes(B, V)
-    if workspace is None:
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hidden.device)
-    st = lib().flash_sample_grouped(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
-                                    _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(bias),
-                                    _ptr(allowed), int(stride), int(group_tiles), int(mode),
-                                    _ptr(out_idx), _ptr(out_lse), _ptr(gl), _ptr(gs), _ptr(workspace),
-                                    workspace.numel() * workspace.element_size(), _stream_ptr(stream),
-                                    int(flags))
+    mask_ptr, stride = _mask_args(allowed, B, V)
+    workspace, ws_bytes = _scratch(flash_sample_full_workspace_bytes(B, V), hidden.device, workspace, stream)
+    st = lib().flash_sample_grouped(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
+                                    _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _f32(bias, V, "bias"),
+                                    mask_ptr, int(stride), int(group_tiles), int(mode),
+                                    _i32(out_idx, B, "out_idx"), _f32(out_lse, B, "out_lse"), _ptr(gl), _ptr(gs),
+                                    _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_grouped")
     return out_idx, out_lse, gl, gs
 
@@ -351,9 +396,10 @@ def flash_group_choose(group_log_mass, group_sample, mode: int = FS_GROUPED_PARA
         out_idx = torch.empty(B, dtype=torch.int32, device=group_log_mass.device)
     if out_lse is None:
         out_lse = torch.empty(B, dtype=torch.float32, device=group_log_mass.device)
-    st = lib().flash_group_choose(_ptr(group_log_mass), _ptr(group_sample), B, m, int(mode), int(seed),
-                                  _ptr(row_seeds), int(row_offset), int(group_offset), _ptr(out_idx),
-                                  _ptr(out_lse), _stream_ptr(stream))
+    st = lib().flash_group_choose(_f32(group_log_mass, B * m, "group_log_mass"),
+                                  _i32(group_sample, B * m, "group_sample"), B, m, int(mode), int(seed),
+                                  _seeds(row_seeds, B), int(row_offset), int(group_offset),
+                                  _i32(out_idx, B, "out_idx"), _f32(out_lse, B, "out_lse"), _stream_ptr(stream))
     _check(st, "flash_group_choose")
     return out_idx, out_lse
 
@@ -370,9 +416,10 @@ def flash_sample_stage1(hidden, W, temperature, seed: int = 0, row_seeds=None, r
             cand_val = torch.empty((B, T), dtype=torch.float32, device=hidden.device)
         if cand_idx is None:
             cand_idx = torch.empty((B, T), dtype=torch.int32, device=hidden.device)
-    st = lib().flash_sample_stage1(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
-                                   _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(cand_val),
-                                   _ptr(cand_idx), _ptr(logits), _stream_ptr(stream), int(flags))
+    st = lib().flash_sample_stage1(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
+                                   _seeds(row_seeds, B), int(row_offset), int(vocab_offset),
+                                   _f32(cand_val, B * T, "cand_val"), _i32(cand_idx, B * T, "cand_idx"),
+                                   _f32(logits, B * V, "logits"), _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_stage1")
     return cand_val, cand_idx
 
@@ -380,8 +427,8 @@ def flash_sample_stage1(hidden, W, temperature, seed: int = 0, row_seeds=None, r
 def flash_sample_stage2(cand_val, cand_idx, out_idx=None, out_val=None, stream=None):
     B, T = cand_val.shape
     out_idx, out_val = _outputs(B, cand_val.device, out_idx, out_val)
-    st = lib().flash_sample_stage2(_ptr(cand_val), _ptr(cand_idx), B, T, _ptr(out_idx), _ptr(out_val),
-                                   _stream_ptr(stream))
+    st = lib().flash_sample_stage2(_f32(cand_val, B * T, "cand_val"), _i32(cand_idx, B * T, "cand_idx"), B, T,
+                                   _ptr(out_idx), _ptr(out_val), _stream_ptr(stream))
     _check(st, "flash_sample_stage2")
     return out_idx, out_val
 
@@ -394,9 +441,10 @@ def flash_sample_unfused(hidden, W, temperature, seed: int = 0, row_seeds=None, 
     if logits is None:
         logits = torch.empty((B, V), dtype=torch.float32, device=hidden.device)
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace)
-    st = lib().flash_sample_unfused(_ptr(hidden), _ptr(W), B, D, V, _ptr(temperature), int(seed),
-                                    _ptr(row_seeds), int(row_offset), int(vocab_offset), _ptr(logits),
+    workspace, ws_bytes = _workspace(B, V, hidden.device, workspace, stream)
+    st = lib().flash_sample_unfused(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed),
+                                    _seeds(row_seeds, B), int(row_offset), int(vocab_offset),
+                                    _f32(logits, B * V, "logits"),
                                     _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes,
                                     _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_unfused")
@@ -408,8 +456,8 @@ def flash_lm_head_logits(hidden, W, logits=None, stream=None, flags: int = 0):
     B, D, V = _shapes(hidden, W)
     if logits is None:
         logits = torch.empty((B, V), dtype=torch.float32, device=hidden.device)
-    st = lib().flash_lm_head_logits(_ptr(hidden), _ptr(W), B, D, V, _ptr(logits), _stream_ptr(stream),
-                                    int(flags))
+    st = lib().flash_lm_head_logits(_ptr(hidden), _ptr(W), B, D, V, _f32(logits, B * V, "logits"),
+                                    _stream_ptr(stream), int(flags))
     _check(st, "flash_lm_head_logits")
     return logits
 
@@ -419,9 +467,9 @@ def flash_gumbel_argmax_logits(logits, temperature, seed: int = 0, row_seeds=Non
                                stream=None):
     B, V = logits.shape
     out_idx, out_val = _outputs(B, logits.device, out_idx, out_val)
-    workspace, ws_bytes = _workspace(B, V, logits.device, workspace)
-    st = lib().flash_gumbel_argmax_logits(_ptr(logits), B, V, _ptr(temperature), int(seed),
-                                          _ptr(row_seeds), int(row_offset), int(vocab_offset),
+    workspace, ws_bytes = _workspace(B, V, logits.device, workspace, stream)
+    st = lib().flash_gumbel_argmax_logits(_f32(logits, B * V, "logits"), B, V, _f32(temperature, B, "temperature"),
+                                          int(seed), _seeds(row_seeds, B), int(row_offset), int(vocab_offset),
                                           _ptr(out_idx), _ptr(out_val), _ptr(workspace), ws_bytes,
                                           _stream_ptr(stream))
     _check(st, "flash_gumbel_argmax_logits")
@@ -436,36 +484,10 @@ def flash_sample_noise(seed: int, row: int, v0: int, n: int, device="cuda", stre
     return g
 
 
-def flash_sample_gumbel_transform(words, stream=None):
+def flash_sample_gumbel_transform(words, stream=None, flags: int = 0):
     import torch
     g = torch.empty(words.numel(), dtype=torch.float32, device=words.device)
-    st = lib().flash_sample_gumbel_transform(_ptr(words), words.numel(), _ptr(g), _stream_ptr(stream))
+    st = lib().flash_sample_gumbel_transform(_ptr(words, (torch.int32, torch.uint32), None, "words"), words.numel(),
+                                             _ptr(g), _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_gumbel_transform")
     return g
-
-
-def flash_sample_stream_probe(src, dst=None, sink=None, stream=None):
-    nbytes = src.numel() * src.element_size()
-    st = lib().flash_sample_stream_probe(_ptr(dst), _ptr(src), nbytes, _ptr(sink), _stream_ptr(stream))
-    _check(st, "flash_sample_stream_probe")
-
-
-# ----------------------------------------------------------------------------- byte model
-
-def io_model_bytes(B: int, D: int, V: int, fused: bool = True) -> int:
-    """Algorithmic HBM bytes of one call (the paper's IO cost model, Section "IO Cost Model and
-    Predicted Speedup", in bytes: bf16 W and H, fp32 logits, 8-byte candidates and outputs).
-    fused:    2 V D + 2 B D + 2 * 8 B T + 8 B
-    unfused:  2 V D + 2 B D + 2 * 4 B V + 2 * 8 B TC + 8 B      (TC = ceil(V / 1024))"""
-    T = (V + FS_VOCAB_TILE - 1) // FS_VOCAB_TILE
-    base = 2 * V * D + 2 * B * D + 8 * B
-    if fused:
-        return base + 2 * 8 * B * T
-    TC = (V + 1023) // 1024
-    return base + 2 * 4 * B * V + 2 * 8 * B * TC
-
-
-def io_model_speedup_elements(B: int, D: int, V: int) -> float:
-    """M_baseline / M_fused of the paper's IO cost model, in element counts as printed there:
-    (VD + DB + 2VB + B) / (VD + DB + B)."""
-    return (V * D + D * B + 2 * V * B + B) / (V * D + D * B + B)

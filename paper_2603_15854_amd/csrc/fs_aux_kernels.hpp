@@ -144,10 +144,10 @@ noise_kernel(uint64_t seed, uint32_t row_word, int32_t v0, int n, float* __restr
 }
 
 __global__ void __launch_bounds__(256)
-gumbel_transform_kernel(const uint32_t* __restrict__ words, int n, float* __restrict__ g_out)
+gumbel_transform_kernel(const uint32_t* __restrict__ words, int n, float* __restrict__ g_out, uint32_t flags)
 {
     const int k = blockIdx.x * 256 + threadIdx.x;
-    if (k < n) g_out[k] = gumbel_from_word(words[k]);
+    if (k < n) g_out[k] = (flags & kEpiExactLog) ? gumbel_from_word_exact(words[k]) : gumbel_from_word(words[k]);
 }
 
 // Decode tap: the FP8 E4M3 -> bf16 conversion of the FP8-weight kernels on caller-given codes

@@ -35,7 +35,12 @@ struct Stage1Params {
     float* lse_sum;           // [B, T] sum of exp(z - max) per (row, tile)
     // FP8 weights (kernels instantiated for one-byte W elements only): W points at E4M3 codes
     const float* w_scale = nullptr;   // [V] fp32 per-row scale of the logits, or nullptr (= 1)
+    // epilogue mode bits (FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG of the C ABI)
+    uint32_t epi_flags = 0;
 };
+
+constexpr uint32_t kEpiGreedy = 0x1u;     // no noise: the candidate is the arg max of the transformed logits
+constexpr uint32_t kEpiExactLog = 0x2u;   // Gumbel transform with the library logarithms instead of v_log_f32
 
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies
@@ -62,42 +67,60 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // 32-bit word -> Gumbel(0,1) variate in fp32 (Alg. 1: u in (0,1), g = -log(-log u)).
 //   x = min(fma(float(r), 2^-32, 2^-33), 1 - 2^-24) is 1 - u; it is strictly inside (0,1) and
 //   is fine-grained near 0, i.e. near u -> 1, the upper Gumbel tail that decides winners.
-//   e = -log(1 - x): five-term Maclaurin series below 2^-5 (relative truncation error < 1e-8),
-//   hardware log2 otherwise (1 - x is then exact or within half an ulp of 1/2..1).
-//   g = -log(e) by hardware log2.
+// Two evaluations of the logarithms (appendix "Numerically Stable and Fast Gumbel Generation":
+// an exact-math and a fast-math mode):
+//   fast (default)  e = -log(1 - x): five-term Maclaurin series below 2^-5 (relative truncation
+//                   error < 1e-8), hardware log2 otherwise (1 - x is then exact or within half an
+//                   ulp of 1/2..1); g = -log(e) by hardware log2 (v_log_f32, about 1 ulp)
+//   exact           e = -log1p(-x), g = -log(e) with the device library's log1pf / logf
+__device__ __forceinline__ float uniform_x_from_word(uint32_t r)
+{
+    return fminf(fmaf((float)r, 0x1p-32f, 0x1p-33f), 1.0f - 0x1p-24f);
+}
 __device__ __forceinline__ float gumbel_from_word(uint32_t r)
 {
     constexpr float kLn2 = 0.6931471805599453f;
-    const float x = fminf(fmaf((float)r, 0x1p-32f, 0x1p-33f), 1.0f - 0x1p-24f);
+    const float x = uniform_x_from_word(r);
     const float series =
         x * fmaf(x, fmaf(x, fmaf(x, fmaf(x, 0.2f, 0.25f), 1.0f / 3.0f), 0.5f), 1.0f);
     const float vialog = -kLn2 * __builtin_amdgcn_logf(1.0f - x);
     const float e = x < 0x1p-5f ? series : vialog;
     return -kLn2 * __builtin_amdgcn_logf(e);
 }
+__device__ __forceinline__ float gumbel_from_word_exact(uint32_t r)
+{
+    return -logf(-log1pf(-uniform_x_from_word(r)));
+}
 
 // Gumbel noise for four consecutive vocabulary ids vid0 .. vid0+3 of one row.  One Philox block
 // serves the four ids of an aligned group (counter word 0 is id >> 2, output word is id & 3);
 // a misaligned start (vocabulary shard offset not a multiple of 4) straddles two blocks.
-__device__ __forceinline__ void gumbel4(uint64_t seed, uint32_t row, uint32_t vid0, float g[4])
+__device__ __forceinline__ void gumbel4(uint64_t seed, uint32_t row, uint32_t vid0, float g[4], bool exact_log = false)
 {
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     uint32_t w[4];
     philox4x32_10(vid0 >> 2, row, 0u, 0u, k0, k1, w);
     const uint32_t sh = vid0 & 3u;
-    if (sh == 0u) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) g[j] = gumbel_from_word(w[j]);
-    } else {
+    if (sh != 0u) {   // the four ids straddle two blocks: words sh..3 of this one, 0..sh-1 of the next
         uint32_t w2[4];
         philox4x32_10((vid0 >> 2) + 1u, row, 0u, 0u, k0, k1, w2);
+        uint32_t m[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t q = sh + (uint32_t)j;  // 1..6
             const uint32_t lo = q == 1u ? w[1] : q == 2u ? w[2] : w[3];
             const uint32_t hi = q == 4u ? w2[0] : q == 5u ? w2[1] : w2[2];
-            g[j] = gumbel_from_word(q < 4u ? lo : hi);
+            m[j] = q < 4u ? lo : hi;
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = m[j];
+    }
+    if (exact_log) {    // uniform over the launch
+#pragma unroll
+        for (int j = 0; j < 4; ++j) g[j] = gumbel_from_word_exact(w[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) g[j] = gumbel_from_word(w[j]);
     }
 }
 
@@ -186,8 +209,9 @@ __device__ __forceinline__ void epilogue_quad(const Stage1Params& p, const RowEp
                                               int v0, int V, float& best, int& best_id,
                                               float& lmax, float& lsum)
 {
-    float gn[4];
-    gumbel4(r.seed, r.row_word, (uint32_t)(p.vocab_offset + v0), gn);
+    float gn[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!(p.epi_flags & kEpiGreedy))   // uniform over the launch
+        gumbel4(r.seed, r.row_word, (uint32_t)(p.vocab_offset + v0), gn, (p.epi_flags & kEpiExactLog) != 0u);
     if constexpr (!FULL) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

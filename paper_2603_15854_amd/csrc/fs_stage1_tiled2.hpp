@@ -21,9 +21,22 @@
 #include <type_traits>
 
 #include "fs_common.hpp"
-#include "fs_stage1_tiled.hpp"   // tile_off
 
 namespace fs {
+
+// Byte offset of 16-byte chunk c (0..7) of row r inside an LDS tile of 128-byte rows.
+// Rows are laid out in blocks of 16 (2 KB): rows r and r + 8 of a block share a 256-byte line
+// (row r & 7 picks the line, (r >> 3) & 1 the 128-byte half) and the chunk index is XORed with
+// r & 7.  An MFMA operand read (16 lanes = the 16 rows of a block, one chunk) then touches the 16
+// distinct 16-byte bank groups as  lane -> group 8 (r >> 3) + (c ^ (r & 7)).  Measured on gfx950
+// (ds_read_b128 at two waves per SIMD): this form runs at the rate of a linear read, while the
+// layout r * 128 + ((c ^ (r & 7) ^ (r >> 3 & 1)) << 4) -- also 16 distinct groups per 16 lanes --
+// takes 25 % longer per instruction and counts four bank-conflict cycles per read in
+// SQ_LDS_BANK_CONFLICT.  Row-contiguous ds_write_b128 parking showed no sensitivity to either.
+__device__ __forceinline__ int tile_off(int r, int c)
+{
+    return ((r >> 4) << 11) + ((r & 7) << 8) + (((r >> 3) & 1) << 7) + ((c ^ (r & 7)) << 4);
+}
 
 // VT: vocabulary rows per workgroup (128, 256 or 512 = one, two or four candidate tiles); BT: batch rows;
 // WM x WN waves (4 or 8); GS: K steps per W prefetch group; OCC: waves per SIMD asked for.
@@ -138,9 +151,8 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const bool k_ragged = KRAG && (D & (KS - 1)) != 0;
     auto fetch_w = [&](uint4 (&wr)[NWL], int k0) {
         const bool over = k0 >= D;                          // uniform
-        int k = k0 + wld_chunk * WEPC;
-        k = k < D - WEPC ? k : D - WEPC;
-        k = over ? wld_chunk * WEPC : k;
+        int k = over ? wld_chunk * WEPC : k0 + wld_chunk * WEPC;
+        k = k < D - WEPC ? k : D - WEPC;     // also when the fixed line is wider than a short row
 #pragma unroll
         for (int i = 0; i < NWL; ++i) {
             int row = tile_row0 + wld_row + WRPP * i;
@@ -159,9 +171,8 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         const bool over = k0 >= D;
 #pragma unroll
         for (int hh = 0; hh < HH; ++hh) {
-            int k = k0 + hh * 64 + ld_chunk * 8;
+            int k = over ? ld_chunk * 8 : k0 + hh * 64 + ld_chunk * 8;
             k = k < D - 8 ? k : D - 8;
-            k = over ? ld_chunk * 8 : k;
 #pragma unroll
             for (int i = 0; i < Cfg::kHLoads; ++i) {
                 int r = b0 + (Cfg::kHPartial ? (ld_row & (BT - 1)) : ld_row + RPP * i);

@@ -6,28 +6,33 @@ import re
 
 import pytest
 
+import fs_io_model as iom
 import paper_2603_15854_amd as fs
+from paper_2603_15854_amd import measure as fsm
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "flash_sample.h")
+MEASURE_HEADER = os.path.join(ROOT, "include", "flash_sample_measure.h")
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 FAKE = 0x7F0000001000  # an aligned, never dereferenced address: the checks under test return first
 
 
-def _declared_symbols():
-    text = open(HEADER).read()
+def _declared_symbols(header):
+    text = open(header).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(flash_[a-z0-9_]+|fs_status_string)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     L = fs.lib()
-    declared = _declared_symbols()
-    assert declared, "no declarations found in the header"
-    for name in declared:
-        assert hasattr(L, name), name
-    assert sorted(fs.EXPORTS) == declared        # the binding covers the same set
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["flash_sample.h", "flash_sample_measure.h"]
+    for header, exports in ((HEADER, fs.EXPORTS), (MEASURE_HEADER, fs.MEASURE_EXPORTS)):
+        declared = _declared_symbols(header)
+        assert declared, "no declarations found in the header"
+        for name in declared:
+            assert hasattr(L, name), name
+        assert sorted(exports) == declared        # the binding covers the same set
 
 
 def test_tile_and_workspace_arithmetic():
@@ -46,7 +51,7 @@ def test_tile_and_workspace_arithmetic():
 
 def test_status_strings():
     seen = set()
-    for code in range(0, 7):
+    for code in range(0, 8):
         s = fs.fs_status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -93,9 +98,13 @@ def test_bad_arguments_are_rejected_before_any_device_work():
     assert L.flash_gumbel_argmax_logits(FAKE, 1, 0, FAKE, 0, None, 0, 0, FAKE, FAKE, FAKE, 1 << 20, None) == fs.FS_ERR_SHAPE
     assert L.flash_sample_noise(0, 0, 0, -1, FAKE, None) == fs.FS_ERR_SHAPE
     assert L.flash_sample_noise(0, 0, 0, 0, None, None) == fs.FS_OK
-    assert L.flash_sample_gumbel_transform(None, 4, FAKE, None) == fs.FS_ERR_NULL
-    assert L.flash_sample_stream_probe(None, FAKE, 24, None, None) == fs.FS_ERR_SHAPE
-    assert L.flash_sample_stream_probe(None, None, 32, None, None) == fs.FS_ERR_NULL
+    assert L.flash_sample_gumbel_transform(None, 4, FAKE, None, 0) == fs.FS_ERR_NULL
+    assert L.flash_sample_gumbel_transform(FAKE, 4, FAKE, None, fs.FS_FLAG_GREEDY) == fs.FS_ERR_UNSUPPORTED
+    assert L.flash_measure_stream_probe(None, FAKE, 24, None, None) == fs.FS_ERR_SHAPE
+    assert L.flash_measure_stream_probe(None, None, 32, None, None) == fs.FS_ERR_NULL
+    # unknown flag bits and retired variant numbers
+    for bad in (0x4, 0x40, fs.FS_VARIANT(1), fs.FS_VARIANT(3), fs.FS_VARIANT(99), 1 << 20):
+        assert ex(flags=bad) == fs.FS_ERR_UNSUPPORTED, hex(bad)
 
     # FP8 weights
     def w8(B=4, D=256, out_idx=FAKE, ws=FAKE + 0x100000, flags=0):
@@ -133,7 +142,7 @@ def test_bad_arguments_are_rejected_before_any_device_work():
 def test_kernel_choice_by_shape():
     # the launcher's rule: split-K while the hidden slice of a wave fits its registers, else the
     # tile shape with the cheapest busiest CU, ceil(workgroups / CUs) * (rows + columns), finer on ties
-    kc = fs.flash_sample_kernel_choice
+    kc = fsm.flash_measure_kernel_choice
     assert [kc(B, 4096, 128256) for B in (1, 16)] == [0, 0]
     assert [kc(B, 4096, 128256) for B in (17, 32, 64, 128, 129, 256, 512)] == [6, 6, 7, 10, 9, 9, 9]
     assert kc(16, 8192, 128256) == 6 and kc(1, 7168, 129280) == 6          # wide hidden sizes: tiled
@@ -157,7 +166,7 @@ def test_io_model_matches_the_papers_predicted_overheads():
                 rows.append((int(D), int(V), int(B), float(pct)))
     assert len(rows) == 12
     for D, V, B, pct in rows:
-        model = (fs.io_model_speedup_elements(B, D, V) - 1.0) * 100.0
+        model = (iom.io_model_speedup_elements(B, D, V) - 1.0) * 100.0
         approx = 200.0 * B / D                                   # the printed column is 2B/D
         assert abs(approx - pct) <= 0.0051, (D, V, B, approx, pct)
         # the exact ratio 1 + 2/(D/B + D/V + 1/V) differs from it only by the D/V and 1/V terms
@@ -166,7 +175,7 @@ def test_io_model_matches_the_papers_predicted_overheads():
         assert 0 < approx - model < approx * 1.01 * B / V
     # byte form used by the benchmark: fp32 logits double the element-count overhead (4B/D)
     B, D, V = 16, 4096, 128256
-    fused, unfused = fs.io_model_bytes(B, D, V, True), fs.io_model_bytes(B, D, V, False)
+    fused, unfused = iom.io_model_bytes(B, D, V, True), iom.io_model_bytes(B, D, V, False)
     assert fused == 2 * V * D + 2 * B * D + 16 * B * 1002 + 8 * B
     assert abs((unfused - fused) / fused - 4 * B / D) < 2e-3
 

@@ -150,19 +150,13 @@ def test_full_transform_at_llama_shape(fs, orc):
         allowed = rng.random((B, w.V)) < 0.7
         words = orc.pack_allowed(allowed)
         gi, gv, gl = run_full(fs, H, Wb, tau, seed=1, bias=bias, words=words, Wd=Wd)
-        rows = sorted({0, 1, 15, B - 1, B // 2})
-        ref = orc.sample_full(np.ascontiguousarray(H[rows]), Wb, np.ascontiguousarray(tau[rows]), seed=1,
-                              row_ids=np.array(rows, dtype=np.int64), bias=bias,
-                              allowed_words=np.ascontiguousarray(words[rows]))
-        v = judge(orc, H, Wb, tau, gi, gv, ref, seed=1, row_ids=np.array(rows, dtype=np.int64), rows=rows,
-                  bias=bias, allowed_words=words)
-        assert v.ok, (B, str(v), v.failures[:3])
-        for k, b in enumerate(rows):
-            assert abs(gl[b] - ref["lse"][k]) <= lse_tol(tau[b], ref["lse"][k])
-        for b in range(B):     # every row: allowed pick and value = oracle score of the pick
+        ref = orc.sample_full(H, Wb, tau, seed=1, bias=bias, allowed_words=words)
+        v = judge(orc, H, Wb, tau, gi, gv, ref, seed=1, bias=bias, allowed_words=words)   # every row
+        print(f"[parity] full transform C2 B={B} all rows: {v}", flush=True)
+        assert v.rows == B and v.ok, (B, str(v), v.failures[:3])
+        for b in range(B):
             assert allowed[b, gi[b]]
-            s = orc.score_at_full(H, Wb, b, int(gi[b]), float(tau[b]), 1, b, int(gi[b]), bias=bias, allowed_row=words[b])
-            assert abs(gv[b] - s) <= 2e-3 / min(float(tau[b]), 1.0) + 1e-3 * (1 + abs(s))
+            assert abs(gl[b] - ref["lse"][b]) <= lse_tol(tau[b], ref["lse"][b])
 
 
 def test_full_entry_rejects_bad_arguments(fs):
@@ -170,9 +164,15 @@ def test_full_entry_rejects_bad_arguments(fs):
     W = torch.zeros((300, 256), dtype=torch.bfloat16, device="cuda")
     tau = torch.ones(4, device="cuda")
     short = torch.zeros((4, 5), dtype=torch.int32, device="cuda")     # needs ceil(300/32) = 10 words per row
-    with pytest.raises(fs.FlashSampleError) as e:
+    with pytest.raises(ValueError):                 # the binding sees the short rows first
         fs.flash_sample_full(H, W, tau, allowed=short)
-    assert e.value.status == fs.FS_ERR_SHAPE
+    ws = torch.empty(fs.flash_sample_full_workspace_bytes(4, 300), dtype=torch.uint8, device="cuda")
+    oi = torch.empty(4, dtype=torch.int32, device="cuda")
+    ov = torch.empty(4, dtype=torch.float32, device="cuda")
+    st = fs.lib().flash_sample_full(H.data_ptr(), W.data_ptr(), 4, 256, 300, tau.data_ptr(), 0, None, 0, 0, None,
+                                    short.data_ptr(), 5, oi.data_ptr(), ov.data_ptr(), None, ws.data_ptr(),
+                                    ws.numel(), None, 0)
+    assert st == fs.FS_ERR_SHAPE                    # and so does the library itself
     with pytest.raises(fs.FlashSampleError) as e:
         fs.flash_sample_full(H, W, tau, flags=fs.FS_VARIANT(3))
     assert e.value.status == fs.FS_ERR_UNSUPPORTED

@@ -45,7 +45,7 @@ def run_fused(fs, Hd, Wd, tau, seed=0, row_seeds=None, flags=0, **kw):
     return idx.cpu().numpy(), val.cpu().numpy()
 
 
-SMALL_VARIANTS = [0, 1, 2, 3, 4, 5, 6, 7]   # auto, split-K A/B, tiled, split-K C/D/E, tiled2
+SMALL_VARIANTS = [0, 2, 7]   # automatic choice, split-K (B <= 16, D <= 4096), tiled
 
 
 # ----------------------------------------------------------------------------- noise
@@ -142,8 +142,8 @@ SHAPES = [
 @pytest.mark.parametrize("variant", SMALL_VARIANTS)
 def test_small_batch_shapes_all_variants(fs, orc, shape, variant):
     B, D, V = shape
-    if variant in (1, 2, 4, 5, 6) and D > 8192:
-        pytest.skip("split-K variants cover D <= 8192")
+    if variant == 2 and D > 4096:
+        pytest.skip("the split-K kernel covers D <= 4096")
     _small_case(fs, orc, B, D, V, variant, data_seed=50 + B + V)
 
 
@@ -151,8 +151,8 @@ def test_small_batch_shapes_all_variants(fs, orc, shape, variant):
                                    (256, 512, 384), (300, 256, 1000), (5, 8200, 300), (2, 16384, 257)])
 def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
     B, D, V = shape
-    for variant in (0, 3, 7):
-        _small_case(fs, orc, B, D, V, variant, data_seed=70 + B)
+    for variant, tune in ((0, 0), (7, 0), (7, 4), (7, 5)):
+        _small_case(fs, orc, B, D, V, variant, data_seed=70 + B, tune=tune)
 
 
 @pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
@@ -168,15 +168,10 @@ def test_split_k_variants_refuse_what_they_cannot_run(fs):
     H = torch.zeros((17, 256), dtype=torch.bfloat16, device="cuda")
     W = torch.zeros((256, 256), dtype=torch.bfloat16, device="cuda")
     tau = torch.ones(17, device="cuda")
-    with pytest.raises(fs.FlashSampleError) as e:
-        fs.flash_sample_ex(H, W, tau, flags=fs.FS_VARIANT(1))
-    assert e.value.status == fs.FS_ERR_UNSUPPORTED
-    with pytest.raises(fs.FlashSampleError) as e:
-        fs.flash_sample_ex(H, W, tau, flags=fs.FS_VARIANT(99))
-    assert e.value.status == fs.FS_ERR_UNSUPPORTED
-    with pytest.raises(fs.FlashSampleError) as e:
-        fs.flash_sample_ex(H, W, tau, flags=1)
-    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+    for bad in (fs.FS_VARIANT(fs.FS_VARIANT_SPLITK), fs.FS_VARIANT(99), 0x40):   # B > 16; unknown variant; unknown bit
+        with pytest.raises(fs.FlashSampleError) as e:
+            fs.flash_sample_ex(H, W, tau, flags=bad)
+        assert e.value.status == fs.FS_ERR_UNSUPPORTED, hex(bad)
 
 
 def test_row_seeds_offsets_and_shards(fs, orc):
@@ -185,7 +180,7 @@ def test_row_seeds_offsets_and_shards(fs, orc):
     Hd, Wd = to_device_bf16(H), to_device_bf16(W)
     tau = np.full(B, 0.9, dtype=np.float32)
     seeds = np.array([0, 1, 2, (9 << 32) + 1, 2**63 + 5, 77], dtype=np.uint64)
-    for variant in (0, 3):
+    for variant in (0, 7):
         flags = fs.FS_VARIANT(variant)
         # per-row seeds and a row offset
         _small_case(fs, orc, B, D, V, variant, data_seed=90, tau=tau, row_seeds=seeds, row_offset=1000)
@@ -242,7 +237,7 @@ def test_rows_without_a_finite_score(fs, orc):
     tau = np.ones(B, dtype=np.float32)
     ref = orc.sample(H, W, tau, seed=3)
     assert ref["idx"][1] == -1
-    for variant in (0, 3):
+    for variant in (0, 7):
         gi, gv = run_fused(fs, to_device_bf16(H), to_device_bf16(W), tau, seed=3, flags=fs.FS_VARIANT(variant))
         assert gi[1] == -1 and gv[1] == -np.inf
         for b in (0, 2, 3):
@@ -255,7 +250,7 @@ def test_logits_tap_and_unfused_path_small(fs, orc):
         Hd, Wd = to_device_bf16(H), to_device_bf16(W)
         tau = np.linspace(0.5, 1.5, B).astype(np.float32)
         Y = orc.logits(H, W)
-        for variant in (0, 3):
+        for variant in (0, 7):
             lg = fs.flash_lm_head_logits(Hd, Wd, flags=fs.FS_VARIANT(variant))
             torch.cuda.synchronize()
             assert np.max(np.abs(lg.cpu().numpy().astype(np.float64) - Y)) <= 2e-3   # per-logit budget
@@ -323,42 +318,43 @@ def test_gpu_samples_follow_softmax_chi_square(fs, orc):
 
 # ----------------------------------------------------------------------------- full-size configs
 
-def _subset_rows(B, k=12):
-    """Rows spread over the batch, including both ends and 16-row block edges."""
-    if B <= k:
-        return list(range(B))
-    picks = {0, 1, 15, 16, 17, B - 1, B - 2, B // 2, B // 2 + 1}
-    rng = np.random.default_rng(B)
-    while len(picks) < k:
-        picks.add(int(rng.integers(0, B)))
-    return sorted(p for p in picks if p < B)
+_ORACLE_CACHE = {}
 
 
-def _full_config(fs, orc, name, B, flags=0, use_row_seeds=None, tau=None, subset=12):
+def oracle_rows(orc, name, B, use_row_seeds, tau=None):
+    """Oracle draw of rows 0..B-1 of a full-size config.  Row b of a config is the same for every
+    batch size (hidden state, temperature, seed and row word depend on b only), so the oracle runs
+    once per config at its largest batch and smaller batches are prefixes of that result."""
+    w = wl.WORKLOADS[name]
+    Wb, _ = weights(name)
+    if tau is not None:     # a one-off temperature set: no sharing between batch sizes
+        H = wl.make_hidden(w, B)
+        seeds = wl.make_row_seeds(w, B) if use_row_seeds else None
+        return orc.sample(H, Wb, tau, seed=w.seed, row_seeds=seeds)
+    key = (name, bool(use_row_seeds))
+    if key not in _ORACLE_CACHE or len(_ORACLE_CACHE[key]["idx"]) < B:
+        Bmax = max(max(w.batch_sizes), B)
+        H = wl.make_hidden(w, Bmax)
+        seeds = wl.make_row_seeds(w, Bmax) if use_row_seeds else None
+        _ORACLE_CACHE[key] = orc.sample(H, Wb, wl.make_temperature(w, Bmax), seed=w.seed, row_seeds=seeds)
+    ref = _ORACLE_CACHE[key]
+    return {k: (v[:B] if isinstance(v, np.ndarray) else v) for k, v in ref.items()}
+
+
+def _full_config(fs, orc, name, B, flags=0, use_row_seeds=None, tau=None):
+    """One full-size call judged on EVERY row: index equal to the oracle's, or a near-tie under the
+    acceptance rule; reported value equal to the oracle's score of the reported index."""
     w = wl.WORKLOADS[name]
     Wb, Wd = weights(name)
     H = wl.make_hidden(w, B)
+    use_row_seeds = w.per_row_seeds if use_row_seeds is None else (use_row_seeds and w.per_row_seeds)
+    row_seeds = wl.make_row_seeds(w, B) if use_row_seeds else None
+    ref = oracle_rows(orc, name, B, use_row_seeds, tau=tau)
     tau = wl.make_temperature(w, B) if tau is None else tau
-    row_seeds = wl.make_row_seeds(w, B) if (use_row_seeds is None or use_row_seeds) else None
-    if use_row_seeds is False:
-        row_seeds = None
     gi, gv = run_fused(fs, to_device_bf16(H), Wd, tau, seed=w.seed, row_seeds=row_seeds, flags=flags)
-    # (1) every row: the reported value is the oracle's score of the reported index
-    for b in range(B):
-        seed_b = int(row_seeds[b]) if row_seeds is not None else w.seed
-        assert 0 <= gi[b] < w.V
-        s = orc.score_at(H, Wb, b, int(gi[b]), float(tau[b]), seed_b, b, int(gi[b]))
-        assert abs(gv[b] - s) <= 2e-3 / min(float(tau[b]), 1.0) + 1e-3 * (1 + abs(s)), (name, B, b)
-    # (2) a spread of rows (all of them for small B): full argmax equality under the acceptance rule
-    rows = _subset_rows(B, subset)
-    ref = orc.sample(np.ascontiguousarray(H[rows]), Wb, np.ascontiguousarray(tau[rows]), seed=w.seed,
-                     row_seeds=None if row_seeds is None else np.ascontiguousarray(row_seeds[rows]),
-                     row_ids=np.array(rows, dtype=np.int64))
-    # judge() indexes H/gpu arrays by global row b and ref by position
-    v = judge(orc, H, Wb, tau, gi, gv, ref, seed=w.seed, row_seeds=row_seeds,
-              row_ids=np.array(rows, dtype=np.int64), rows=rows)
-    print(f"[parity] {name} B={B} flags={flags:#x}: {v}", flush=True)
-    assert v.ok, (name, B, str(v), v.failures[:3])
+    v = judge(orc, H, Wb, tau, gi, gv, ref, seed=w.seed, row_seeds=row_seeds)
+    print(f"[parity] {name} B={B} flags={flags:#x} all rows: {v}", flush=True)
+    assert v.rows == B and v.ok, (name, B, str(v), v.failures[:3])
     return gi, gv, v
 
 
@@ -366,7 +362,7 @@ def _full_config(fs, orc, name, B, flags=0, use_row_seeds=None, tau=None, subset
 def test_config_c2_llama_shape(fs, orc, B):
     gi, gv, _ = _full_config(fs, orc, "C2", B)                       # per-row seeds, all rows
     _full_config(fs, orc, "C2", B, use_row_seeds=False)             # single seed entry
-    ti, tv, _ = _full_config(fs, orc, "C2", B, flags=fs.FS_VARIANT(3))   # tiled kernel, same draws
+    ti, tv, _ = _full_config(fs, orc, "C2", B, flags=fs.FS_VARIANT(7))   # tiled kernel, same draws
     assert np.array_equal(gi, ti)
     assert np.allclose(gv, tv, rtol=0, atol=1e-4)
 
@@ -377,7 +373,8 @@ def test_config_c3_qwen_shape(fs, orc, B):
 
 
 def test_config_c4_compute_leaning_peaky(fs, orc):
-    _, _, v = _full_config(fs, orc, "C4", 256, subset=16)
+    _, _, v = _full_config(fs, orc, "C4", 256)
+    print(f"[parity] C4 near-tie rows: {v.near_ties} of {v.rows}", flush=True)
     # the unfused path draws the same tokens on this near-tie-heavy config
     w = wl.WORKLOADS["C4"]
     Wb, Wd = weights("C4")
@@ -392,6 +389,25 @@ def test_config_c4_compute_leaning_peaky(fs, orc):
 @pytest.mark.parametrize("B", [1, 8, 64, 256, 512])
 def test_config_c5_wide_hidden(fs, orc, B):
     _full_config(fs, orc, "C5", B)
+
+
+@pytest.mark.parametrize("name,B,variant", [("C4", 256, 0), ("C4", 16, 0), ("C4", 128, 0),
+                                            ("C5", 512, 0), ("C5", 64, 0), ("C5", 8, 0)])
+def test_per_logit_deviation_at_wide_hidden_sizes(fs, orc, name, B, variant):
+    # the logits-store tap (same main loop as the fused kernel) against the fp64 logits, whole rows
+    # of a spread of batch rows, at D = 8192 and D = 7168 (every tile-shape class): <= 2e-3 absolute
+    w = wl.WORKLOADS[name]
+    Wb, Wd = weights(name)
+    H = wl.make_hidden(w, B)
+    lg = fs.flash_lm_head_logits(to_device_bf16(H), Wd, flags=fs.FS_VARIANT(variant))
+    torch.cuda.synchronize()
+    rows = sorted({0, 1, 15, 16, 17, B // 2, B - 2, B - 1} & set(range(B)))
+    Y = orc.logits(np.ascontiguousarray(H[rows]), Wb)
+    got = lg[rows].cpu().numpy().astype(np.float64)
+    dev = np.abs(got - Y)
+    print(f"[logits] {name} B={B} variant={variant}: rows={rows} max|y_gpu-y_oracle|={dev.max():.3g} "
+          f"max|y|={np.abs(Y).max():.3g}", flush=True)
+    assert dev.max() <= 2e-3
 
 
 def test_config_c5_temperature_to_zero_is_argmax(fs, orc):

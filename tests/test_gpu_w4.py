@@ -66,20 +66,20 @@ def test_w4_matches_oracle(fs, orc, shape):
     assert np.max(np.abs(lg.cpu().numpy() - Y)) <= 2e-3
 
 
-@pytest.mark.parametrize("variant", [1, 2, 4, 9, 10])
-def test_w4_every_kernel_form(fs, orc, variant):
-    shapes = [(10, 1024, 700), (16, 4096, 300)] if variant < 8 else [(10, 2048, 700), (16, 8192, 300)]
-    for B, D, V in shapes:
-        print(f"w4 variant {variant} B={B} D={D} V={V}", flush=True)
+@pytest.mark.parametrize("wgs", [0, 1, 2])
+def test_w4_every_kernel_form(fs, orc, wgs):
+    # 16 K steps per wave (D <= 4096) and 32 (D % 1024 == 0, up to 8192); workgroups per CU automatic or forced
+    for B, D, V in [(10, 1024, 700), (16, 4096, 300), (10, 6144, 700), (16, 8192, 300), (3, 512, 2000)]:
+        print(f"w4 wgs/CU {wgs} B={B} D={D} V={V}", flush=True)
         H, W = wl.make_small(D=D, V=V, B=B, data_seed=970 + B)
         codes, scales = wl.quantize_mxfp4(W)
         tau = np.linspace(0.7, 1.5, B).astype(np.float32)
         ref = orc.sample_w4(H, codes, scales, tau, seed=9)
         gi, gv = fs.flash_sample_w4(to_device_bf16(H), dev(codes, np.uint8), dev(scales, np.uint8),
-                                    dev(tau, np.float32), seed=9, flags=fs.FS_VARIANT(variant))
+                                    dev(tau, np.float32), seed=9, flags=fs.FS_TUNE_WGS_PER_CU(wgs))
         torch.cuda.synchronize()
         v = judge(orc, H, codes, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, seed=9, w4_scales=scales)
-        assert v.ok, (variant, B, D, V, str(v), v.failures[:3])
+        assert v.ok, (wgs, B, D, V, str(v), v.failures[:3])
 
 
 def test_w4_at_llama_shape(fs, orc):

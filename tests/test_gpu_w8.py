@@ -86,21 +86,25 @@ def test_w8_at_llama_shape(fs, orc):
     assert v.ok, (str(v), v.failures[:3])
 
 
-@pytest.mark.parametrize("variant", [1, 4, 5, 6, 7, 8, 9, 10, 14, 15, 16, 17, 18, 19, 20])
-def test_w8_every_kernel_choice(fs, orc, variant):
-    # 1: four-wave split-K; 4..10: the tiled shapes 3..9 (256x128, 128x128, 128x64, 512x32, 512x64, 256x32,
-    # 256x256) with the codes kept in LDS where that fits; 14..20: the same shapes widening the codes at park time
-    for B, D, V in [(10, 528, 1100), (16, 2048, 700)] if variant == 1 else [(20, 528, 1100), (70, 256, 1500), (150, 1072, 700), (33, 48, 513)]:
-        print(f"w8 variant {variant} B={B} D={D} V={V}", flush=True)
+@pytest.mark.parametrize("tune", [-1, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+def test_w8_every_kernel_choice(fs, orc, tune):
+    # -1: the split-K kernel forced; 1..10: the tile shapes of the tiled kernel (codes kept in LDS when
+    # D % 128 == 0, widened at park time on the two-per-CU shapes otherwise)
+    shapes = [(10, 528, 1100), (16, 2048, 700), (7, 8192, 300)] if tune < 0 else \
+        [(20, 528, 1100), (70, 256, 1500), (150, 1152, 700), (33, 48, 513), (40, 192, 600)]
+    for B, D, V in shapes:
+        print(f"w8 tune {tune} B={B} D={D} V={V}", flush=True)
         H, W = wl.make_small(D=D, V=V, B=B, data_seed=850 + B)
         codes, scale = wl.quantize_e4m3(W)
         tau = np.linspace(0.7, 1.5, B).astype(np.float32)
         ref = orc.sample_w8(H, codes, scale, tau, seed=9)
+        flags = fs.FS_VARIANT(fs.FS_VARIANT_SPLITK) if tune < 0 else \
+            fs.FS_VARIANT(fs.FS_VARIANT_TILED2) | fs.FS_TUNE_TILE_SHAPE(tune)
         gi, gv = fs.flash_sample_w8(to_device_bf16(H), dev(codes, np.uint8), dev(scale, np.float32),
-                                    dev(tau, np.float32), seed=9, flags=fs.FS_VARIANT(variant))
+                                    dev(tau, np.float32), seed=9, flags=flags)
         torch.cuda.synchronize()
         v = judge(orc, H, codes, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, seed=9, w8_scale=scale)
-        assert v.ok, (variant, B, D, V, str(v), v.failures[:3])
+        assert v.ok, (tune, B, D, V, str(v), v.failures[:3])
 
 
 def test_w8_shapes_outside_the_kernel_are_refused(fs):
