@@ -63,7 +63,8 @@ typedef enum {
     FS_ERR_WORKSPACE = 4,   /* workspace missing or smaller than flash_sample_workspace_bytes */
     FS_ERR_HIP = 5,         /* a HIP runtime call failed (launch, allocation) */
     FS_ERR_UNSUPPORTED = 6, /* unknown flag or a kernel variant that cannot run this shape */
-    FS_ERR_DEVICE = 7       /* current device ordinal >= 64 (the size of the per-device tables) */
+    FS_ERR_DEVICE = 7,      /* current device ordinal >= 64 (the size of the per-device tables) */
+    FS_ERR_SCRATCH_LIMIT = 8 /* flash_sample_static: 8 B T bytes exceed FS_STATIC_SCRATCH_BYTES */
 } fs_status;
 
 /* flags for the *_ex entry points */
@@ -129,6 +130,27 @@ fs_status flash_sample_ex(const void* hidden, const void* W, int B, int D, int V
                           int64_t row_offset, int32_t vocab_offset,
                           int32_t* out_idx, float* out_val,
                           void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
+ * flash_sample_ex for callers that cannot allocate and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The candidate buffer of
+ * Alg. 1 lives in a device array built into the library (FS_STATIC_SCRATCH_BYTES per device, held
+ * until the process ends); the call allocates nothing and calls no allocating routine.
+ *   - needs flash_sample_workspace_bytes(B, V) <= FS_STATIC_SCRATCH_BYTES (e.g. B = 512 at
+ *     V = 129280), else FS_ERR_SCRATCH_LIMIT and nothing is launched;
+ *   - the first call on a device looks up the array's address (hipGetSymbolAddress) and does the
+ *     kernels' one-time set-up: make it outside any capture;
+ *   - every call on a device uses that device's one array: calls that overlap in time on one device
+ *     (different streams, or threads) race on it -- keep them on one stream, or use
+ *     flash_sample_ex with separate workspaces.  Nothing in the array has to be cleared between
+ *     calls: stage 1 writes every entry stage 2 reads.
+ * All other arguments, results and error codes as in flash_sample_ex.
+ */
+#define FS_STATIC_SCRATCH_BYTES (8u << 20)
+fs_status flash_sample_static(const void* hidden, const void* W, int B, int D, int V,
+                              const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                              int64_t row_offset, int32_t vocab_offset,
+                              int32_t* out_idx, float* out_val, void* stream, uint32_t flags);
 
 /*
  * The same draw with the whole deterministic transform of the paper's notation ("additive bias,

@@ -5,7 +5,7 @@ PyTorch is used for device memory and streams, nothing else.  There is no CPU fa
 library is missing or a call fails, an exception is raised.
 
 Functions mirror the C names (``EXPORTS`` lists every symbol of the header): ``flash_sample``,
-``flash_sample_ex``, ``flash_sample_full``, ``flash_sample_grouped``,
+``flash_sample_ex``, ``flash_sample_static``, ``flash_sample_full``, ``flash_sample_grouped``,
 ``flash_group_choose``, ``flash_sample_w8``, ``flash_sample_w4``, the stages ``flash_sample_stage1`` /
 ``flash_sample_stage2``, the comparison path ``flash_sample_unfused`` / ``flash_lm_head_logits`` /
 ``flash_gumbel_argmax_logits`` and the debug taps.  The measurement aids of
@@ -25,14 +25,16 @@ LIB_PATH = os.path.join(_HERE, "libflashsample.so")
 
 FS_OK = 0
 FS_ERR_NULL, FS_ERR_SHAPE, FS_ERR_ALIGN, FS_ERR_WORKSPACE, FS_ERR_HIP, FS_ERR_UNSUPPORTED = 1, 2, 3, 4, 5, 6
-FS_ERR_DEVICE = 7
+FS_ERR_DEVICE, FS_ERR_SCRATCH_LIMIT = 7, 8
 FS_VOCAB_TILE = 128
 FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG = 0, 1, 2
 FS_VARIANT_AUTO, FS_VARIANT_SPLITK, FS_VARIANT_TILED2 = 0, 2, 7
+FS_STATIC_SCRATCH_BYTES = 8 << 20
 
 # every symbol include/flash_sample.h declares
 EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
+    "flash_sample_static",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
     "flash_sample_w8", "flash_sample_e4m3_decode", "flash_sample_w4", "flash_sample_mxfp4_decode",
@@ -85,6 +87,8 @@ def lib():
     L.flash_sample.restype = i32
     L.flash_sample_ex.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, sz, vp, u32]
     L.flash_sample_ex.restype = i32
+    L.flash_sample_static.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, vp, u32]
+    L.flash_sample_static.restype = i32
     L.flash_sample_full_workspace_bytes.argtypes = [i32, i32]
     L.flash_sample_full_workspace_bytes.restype = sz
     L.flash_sample_full.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
@@ -247,6 +251,19 @@ def flash_sample_ex(hidden, W, temperature, seed: int = 0, row_seeds=None, row_o
                                _seeds(row_seeds, B), int(row_offset), int(vocab_offset), _ptr(out_idx),
                                _ptr(out_val), _ptr(workspace), ws_bytes, _stream_ptr(stream), int(flags))
     _check(st, "flash_sample_ex")
+    return out_idx, out_val
+
+
+def flash_sample_static(hidden, W, temperature, out_idx, out_val, seed: int = 0, row_seeds=None,
+                        row_offset: int = 0, vocab_offset: int = 0, stream=None, flags: int = 0):
+    """flash_sample_ex on the library's built-in scratch: no allocation anywhere, so the caller
+    passes the outputs too.  Calls that overlap on one device race on the scratch."""
+    B, D, V = _shapes(hidden, W)
+    st = lib().flash_sample_static(_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"),
+                                   int(seed), _seeds(row_seeds, B), int(row_offset), int(vocab_offset),
+                                   _i32(out_idx, B, "out_idx"), _f32(out_val, B, "out_val"),
+                                   _stream_ptr(stream), int(flags))
+    _check(st, "flash_sample_static")
     return out_idx, out_val
 
 

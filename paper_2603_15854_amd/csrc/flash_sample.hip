@@ -171,7 +171,30 @@ Stage1Params make_params(const void* hidden, const void* W, int B, int D, int V,
 
 }  // namespace
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of flash_sample_static: the candidate buffer of Alg. 1 in a file-scope device array, for
+// callers that cannot allocate.  In host code the array's name is only a stand-in; its device
+// address is looked up once per device (each device holds its own copy) and used from then on.
+static __device__ __align__(256) unsigned char scratch[FS_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (first call on a device: one symbol lookup).
+fs_status static_scratch(void** out)
+{
+    int dev = 0;
+    const fs_status ds = current_device(&dev, nullptr);
+    if (ds != FS_OK) return ds;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FS_ERR_HIP;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return FS_OK;
+}
 
 // workspace cache of the plain entry point, one per device; g_ws_mu is held across the launch so
 // that a concurrent call cannot free the buffer between another thread's lookup and its launch
@@ -202,6 +225,8 @@ const char* fs_status_string(fs_status s)
     case FS_ERR_HIP: return "a HIP runtime call failed";
     case FS_ERR_UNSUPPORTED: return "unknown flag, or the requested kernel variant cannot run this shape";
     case FS_ERR_DEVICE: return "the current device ordinal is beyond the library's per-device tables (64 devices)";
+    case FS_ERR_SCRATCH_LIMIT: return "the problem needs more than the built-in scratch of flash_sample_static "
+                                      "(8 B T bytes > FS_STATIC_SCRATCH_BYTES): use flash_sample_ex with a workspace";
     }
     return "unknown status";
 }
@@ -281,6 +306,23 @@ fs_status flash_sample(const void* hidden, const void* W, int B, int D, int V,
     }
     return flash_sample_ex(hidden, W, B, D, V, temperature, seed, nullptr, 0, 0, out_idx, out_val,
                            c.ws, need, nullptr, FS_FLAG_NONE);
+}
+
+fs_status flash_sample_static(const void* hidden, const void* W, int B, int D, int V,
+                              const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                              int64_t row_offset, int32_t vocab_offset,
+                              int32_t* out_idx, float* out_val, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK || B == 0) return s;
+    if (workspace_bytes(B, V) > (size_t)FS_STATIC_SCRATCH_BYTES) return FS_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    s = static_scratch(&ptr);
+    if (s != FS_OK) return s;
+    // every (row, tile) entry of the candidate buffer is written by stage 1 before stage 2 reads
+    // it, so nothing in the scratch has to start at zero
+    return flash_sample_ex(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset,
+                           out_idx, out_val, ptr, (size_t)FS_STATIC_SCRATCH_BYTES, stream, flags);
 }
 
 size_t flash_sample_full_workspace_bytes(int B, int V) { return 2 * workspace_bytes(B, V); }

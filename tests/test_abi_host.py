@@ -51,7 +51,7 @@ def test_tile_and_workspace_arithmetic():
 
 def test_status_strings():
     seen = set()
-    for code in range(0, 8):
+    for code in range(0, 9):
         s = fs.fs_status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -105,6 +105,19 @@ def test_bad_arguments_are_rejected_before_any_device_work():
     # unknown flag bits and retired variant numbers
     for bad in (0x4, 0x40, fs.FS_VARIANT(1), fs.FS_VARIANT(3), fs.FS_VARIANT(99), 1 << 20):
         assert ex(flags=bad) == fs.FS_ERR_UNSUPPORTED, hex(bad)
+
+    # the entry point on the built-in scratch: same checks, plus its size limit (before any device work)
+    def static(B=4, V=4096, hidden=FAKE, out_idx=FAKE, D=256):
+        return L.flash_sample_static(hidden, FAKE, B, D, V, FAKE, 0, None, 0, 0, out_idx, FAKE, None, 0)
+
+    assert static(B=0) == fs.FS_OK
+    assert static(hidden=None) == fs.FS_ERR_NULL and static(D=252) == fs.FS_ERR_SHAPE
+    assert fs.flash_sample_workspace_bytes(512, 129280) <= fs.FS_STATIC_SCRATCH_BYTES
+    Bmax = fs.FS_STATIC_SCRATCH_BYTES // (8 * 1002)
+    assert fs.flash_sample_workspace_bytes(Bmax + 1, 128256) > fs.FS_STATIC_SCRATCH_BYTES
+    assert static(B=Bmax + 1, V=128256) == fs.FS_ERR_SCRATCH_LIMIT
+    assert static(B=4, V=2**31 - 2) == fs.FS_ERR_SCRATCH_LIMIT
+    assert "scratch" in fs.fs_status_string(fs.FS_ERR_SCRATCH_LIMIT)
 
     # FP8 weights
     def w8(B=4, D=256, out_idx=FAKE, ws=FAKE + 0x100000, flags=0):
