@@ -1,22 +1,34 @@
 #!/usr/bin/env python3
 """Benchmark of the fused LM-head + Gumbel-max sampling call on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--no-sweep] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--quick] [--no-cpu]
 
 One "step" is one whole call of the hot path (stage 1 + stage 2) on one batch of synthetic
 input of the Llama-3-8B-shaped LM head (D=4096, V=128256, bf16; workload C2).  The headline
-line is quoted at B=16, the largest batch of the bandwidth-bound decode regime; the same JSON
-line carries a sweep over B = 1..256 with the unfused comparison path beside it.
+line is quoted at B=16, the largest batch of the bandwidth-bound decode regime.  The same JSON
+line carries, unless --quick is given:
+  sweep           the C2 shape at B = 1..256, fused and unfused, % of HBM peak and % of MFMA peak
+  configs         workloads C3 (B=32/64/128), C4 (B=16/64/256; the shape of the paper's absolute
+                  kernel times) and C5 (B=1/8/64/256/512), fused and unfused
+  epilogue_share  stage 1 with the noise switched off (FS_FLAG_GREEDY) against the sampling form
+  top_k           the fused top-k / top-p draw against "logits-store GEMM + top-k kernel"
+  fp8_weights, mxfp4_weights   the same call on lower-precision weights
+  cpu_baseline    the CPU oracle on the host cores (bounded sample)
 
-Timing: W warm-up calls, then exactly K calls bracketed by events on the stream the kernels are
-launched on (torch's current stream, which is passed to the library), with a device
-synchronisation on both sides.  Inputs are resident in HBM before the timed region.
+Timing.  Headline: W warm-up calls, then exactly K calls bracketed by events on the stream the
+kernels are launched on (torch's current stream, which is passed to the library), with a device
+synchronisation on both sides; `ms_per_step` is that bracket divided by K.  Every figure also gets
+the distribution of the time per call: 25 warm-ups, then `--repeats` repeats of `--calls` calls
+with an event after every `--group` calls; reported are the median over all samples and the
+smallest and largest per-repeat median.  Inputs are resident in HBM before any timed region.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -24,9 +36,32 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
-MEASURED_TRAFFIC_C2_B16 = int((514427.6 * 2.0 + 1009.6) * 1024)   # bytes per stage-1 launch (rocprofv3)
+TRAFFIC_PROFILE = "profiles/stage1_splitk_C2_B16_hbm_traffic_pmc.txt"
+# sampling share of the fused kernel's time printed in the paper (table "sampling % of kernel
+# time"; another machine, another kernel: context only)
+PAPER_SAMPLING_SHARE_PCT = {1: 2.3, 16: 2.3, 64: 6.0, 256: 6.2}
+# the paper's only absolute kernel times (appendix table of tensor-parallel runtimes, TP=1 column,
+# D=8192, V=128256, an 8 TB/s-class NVIDIA GPU): (fused, Gumbel-max on stored logits) in us
+PAPER_ABS_US = {16: (333.8, 385.0), 64: (344.1, 439.2), 256: (676.8, 669.7)}
+
+
+def profiled_traffic():
+    """HBM bytes per stage-1 launch at C2/B=16 as counted by rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    in a separate run (counters perturb timing); read from the committed summary, never a constant
+    in this file.  (None, reason) when the summary is missing or has no such line."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    try:
+        text = open(path).read()
+    except OSError:
+        return None, f"{TRAFFIC_PROFILE} missing"
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*(\d+)", text, flags=re.M)
+    c = re.search(r"^measured_at_commit\s*=\s*(\S+)", text, flags=re.M)
+    if not m:
+        return None, f"{TRAFFIC_PROFILE} has no traffic_bytes_per_launch line"
+    return int(m.group(1)), f"{TRAFFIC_PROFILE} (rocprofv3 --pmc, separate run; kernels as of commit " \
+                            f"{c.group(1) if c else 'unknown'}), not this run"
 
 
 def main() -> int:
@@ -34,16 +69,21 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--calls", type=int, default=100, help="calls per repeat of the per-call distribution")
+    ap.add_argument("--repeats", type=int, default=10, help="repeats of the per-call distribution")
+    ap.add_argument("--group", type=int, default=5,
+                    help="back-to-back calls per timing sample of the distribution (an event costs about 2.5 us "
+                         "on the stream; with one event per call that overhead would sit in every sample)")
     ap.add_argument("--spinup-ms", type=float, default=100.0,
                     help="untimed busy period before each measurement (clock ramp after idle); 0 = off")
     ap.add_argument("--batch", type=int, default=16, help="batch size of the headline line")
     ap.add_argument("--workload", default="C2")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the B = 1..256 sweep")
+    ap.add_argument("--quick", "--no-sweep", dest="quick", action="store_true",
+                    help="headline and roofline only (what the profiler runs use)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time of the CPU-oracle leg")
-    ap.add_argument("--no-paper-shape", action="store_true",
-                    help="skip the D=8192, V=128256 legs that sit beside the paper's absolute kernel times")
     ap.add_argument("--variant", type=int, default=0, help="stage-1 kernel variant (0 = automatic)")
+    ap.add_argument("--tile-shape", type=int, default=0, help="tile shape of the tiled kernel (0 = automatic)")
     ap.add_argument("--calibrate", type=int, default=0,
                     help="also launch N plain read and N plain copy kernels over a W-sized buffer "
                          "(known traffic, to scale the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -59,88 +99,144 @@ def main() -> int:
     import fs_io_model as iom
     import fs_workloads as wl
     import paper_2603_15854_amd as fs
-    from paper_2603_15854_amd import measure as fsm
     from fs_workloads import to_device_bf16
+    from paper_2603_15854_amd import measure as fsm
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     fs.lib()
     torch.cuda.set_device(0)
-    w = wl.WORKLOADS[args.workload]
-    D, V = w.D, w.V
-    T = fs.flash_sample_num_tiles(V)
-    flags = fs.FS_VARIANT(args.variant)
-
-    Wb = wl.make_weights(w)
-    Wd = to_device_bf16(Wb)
+    flags = fs.FS_VARIANT(args.variant) | fs.FS_TUNE_TILE_SHAPE(args.tile_shape)
     stream = torch.cuda.current_stream()
 
-    def setup(B):
-        H = wl.make_hidden(w, B)
-        s = dict(
-            B=B, H=H, Hd=to_device_bf16(H),
-            tau_h=wl.make_temperature(w, B),
-            seeds_h=wl.make_row_seeds(w, B),
-        )
-        s["tau"] = torch.from_numpy(s["tau_h"]).cuda()
-        s["seeds"] = None if s["seeds_h"] is None else torch.from_numpy(s["seeds_h"].view(np.int64)).cuda()
-        s["ws"] = torch.empty(max(256, fs.flash_sample_workspace_bytes(B, V)), dtype=torch.uint8, device="cuda")
-        s["oi"] = torch.empty(B, dtype=torch.int32, device="cuda")
-        s["ov"] = torch.empty(B, dtype=torch.float32, device="cuda")
-        s["cv"] = torch.empty((B, T), dtype=torch.float32, device="cuda")
-        s["ci"] = torch.empty((B, T), dtype=torch.int32, device="cuda")
-        return s
+    class Leg:
+        """Device-resident inputs and outputs of one (workload, B)."""
 
-    def fused(s):
-        fs.flash_sample_ex(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"], out_idx=s["oi"],
-                           out_val=s["ov"], workspace=s["ws"], stream=stream, flags=flags)
+        def __init__(self, w, Wd, B, want_logits=False):
+            self.w, self.Wd, self.B = w, Wd, B
+            self.T = fs.flash_sample_num_tiles(w.V)
+            self.H = wl.make_hidden(w, B)
+            self.Hd = to_device_bf16(self.H)
+            self.tau_h = wl.make_temperature(w, B)
+            self.seeds_h = wl.make_row_seeds(w, B)
+            self.tau = torch.from_numpy(self.tau_h).cuda()
+            self.seeds = None if self.seeds_h is None else torch.from_numpy(self.seeds_h.view(np.int64)).cuda()
+            self.ws = torch.empty(max(256, fs.flash_sample_full_workspace_bytes(B, w.V)), dtype=torch.uint8, device="cuda")
+            self.oi = torch.empty(B, dtype=torch.int32, device="cuda")
+            self.ov = torch.empty(B, dtype=torch.float32, device="cuda")
+            self.cv = torch.empty((B, self.T), dtype=torch.float32, device="cuda")
+            self.ci = torch.empty((B, self.T), dtype=torch.int32, device="cuda")
+            self.lg = torch.empty((B, w.V), dtype=torch.float32, device="cuda") if want_logits else None
 
-    def stage1(s):
-        fs.flash_sample_stage1(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"],
-                               cand_val=s["cv"], cand_idx=s["ci"], stream=stream, flags=flags)
+        def fused(self):
+            fs.flash_sample_ex(self.Hd, self.Wd, self.tau, seed=self.w.seed, row_seeds=self.seeds, out_idx=self.oi,
+                               out_val=self.ov, workspace=self.ws, stream=stream, flags=flags)
 
-    def unfused(s):
-        fs.flash_sample_unfused(s["Hd"], Wd, s["tau"], seed=w.seed, row_seeds=s["seeds"], logits=s["lg"],
-                                out_idx=s["oi"], out_val=s["ov"], workspace=s["ws"], stream=stream)
+        def stage1(self, extra_flags=0):
+            fs.flash_sample_stage1(self.Hd, self.Wd, self.tau, seed=self.w.seed, row_seeds=self.seeds,
+                                   cand_val=self.cv, cand_idx=self.ci, stream=stream, flags=flags | extra_flags)
 
-    def spin_up(fn, s):
-        """Keep the GPU busy with the call about to be measured for args.spinup_ms: after the host-side
-        set-up the device sits in an idle clock state, and the first ~10 ms of work run 10-15 % slow
+        def stage1_greedy(self):
+            self.stage1(fs.FS_FLAG_GREEDY)
+
+        def unfused(self):
+            fs.flash_sample_unfused(self.Hd, self.Wd, self.tau, seed=self.w.seed, row_seeds=self.seeds,
+                                    logits=self.lg, out_idx=self.oi, out_val=self.ov, workspace=self.ws,
+                                    stream=stream, flags=flags)
+
+    def spin_up(fn):
+        """Keep the GPU busy with the call about to be measured for args.spinup_ms: after host-side
+        set-up the device sits in an idle clock state and whatever is timed first runs 10-15 % slow
         (measured: the same kernel timed first after set-up vs. after other kernels).  Untimed."""
         if args.spinup_ms <= 0:
             return
         t_end = time.perf_counter() + args.spinup_ms * 1e-3
         while time.perf_counter() < t_end:
             for _ in range(8):
-                fn(s)
+                fn()
             torch.cuda.synchronize()
 
-    def timed(fn, s, steps, warmup):
-        """Average milliseconds per call over exactly `steps` calls."""
-        spin_up(fn, s)
+    def bracket_ms(fn, steps, warmup):
+        """Milliseconds per call from ONE bracket around exactly `steps` calls."""
+        spin_up(fn)
         for _ in range(warmup):
-            fn(s)
+            fn()
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(steps):
-            fn(s)
+            fn()
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / steps
 
+    def per_call_us(fn, calls=None, repeats=None, warmup=25):
+        """Distribution of the time per call: 25 warm-ups, then `repeats` repeats of `calls` calls with
+        an event after every `--group` calls (one sample = the mean of that many back-to-back calls):
+        median over all samples, smallest / largest per-repeat median, mean."""
+        calls = args.calls if calls is None else calls
+        repeats = args.repeats if repeats is None else repeats
+        group = max(1, min(args.group, calls))
+        nsamp = calls // group
+        spin_up(fn)
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(nsamp + 1)]
+        all_us, medians = [], []
+        for _ in range(repeats):
+            ev[0].record(stream)
+            for i in range(nsamp):
+                for _ in range(group):
+                    fn()
+                ev[i + 1].record(stream)
+            torch.cuda.synchronize()
+            us = [ev[i].elapsed_time(ev[i + 1]) * 1e3 / group for i in range(nsamp)]
+            all_us += us
+            medians.append(statistics.median(us))
+        return {"median_us": round(statistics.median(all_us), 2), "min_us": round(min(medians), 2),
+                "max_us": round(max(medians), 2), "mean_us": round(statistics.fmean(all_us), 2),
+                "calls": nsamp * group, "repeats": repeats, "calls_per_sample": group}
+
+    def rates(B, D, V, us, w_bytes_per_row=None):
+        by = iom.io_model_bytes(B, D, V, fused=True, w_bytes_per_row=w_bytes_per_row)
+        fl = 2.0 * B * D * V
+        return {"hbm_gbs": round(by / us / 1e3, 1), "pct_hbm_peak": round(100.0 * by / us / 1e3 / HBM_PEAK_GBS, 2),
+                "tflops": round(fl / us / 1e6, 1), "pct_mfma_peak": round(100.0 * fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 2),
+                "tokens_per_s": round(B / us * 1e6, 1)}
+
+    def fused_vs_unfused(leg):
+        """One row of a sweep: fused and unfused per-call distributions and the derived rates."""
+        f = per_call_us(leg.fused)
+        u = per_call_us(leg.unfused)
+        w = leg.w
+        row = {"B": leg.B, "fused_us": f["median_us"], "fused_min_us": f["min_us"], "fused_max_us": f["max_us"],
+               "unfused_us": u["median_us"], "unfused_min_us": u["min_us"], "unfused_max_us": u["max_us"],
+               "fused_over_unfused_speedup": round(u["median_us"] / f["median_us"], 4)}
+        row.update(rates(leg.B, w.D, w.V, f["median_us"]))
+        return row
+
     # ------------------------------------------------------------------ headline: whole call at B
+    w = wl.WORKLOADS[args.workload]
+    D, V = w.D, w.V
+    Wb = wl.make_weights(w)
+    Wd = to_device_bf16(Wb)
     B = args.batch
-    s = setup(B)
-    ms = timed(fused, s, args.steps, args.warmup)
+    head = Leg(w, Wd, B)
+    ms = bracket_ms(head.fused, args.steps, args.warmup)
+    dist = per_call_us(head.fused)
     bytes_fused = iom.io_model_bytes(B, D, V, fused=True)
     gbs = bytes_fused / (ms * 1e-3) / 1e9
 
-    # dominant kernel (stage 1) alone, same stream, same launch configuration
-    ms1 = timed(stage1, s, args.steps, args.warmup)
-    bytes_stage1 = 2 * V * D + 2 * B * D + 8 * B * T      # W once + H once + candidates written
+    # dominant kernel (stage 1) alone, same stream, same launch configuration, timed live
+    ms1 = bracket_ms(head.stage1, args.steps, args.warmup)
+    dist1 = per_call_us(head.stage1)
+    bytes_stage1 = iom.stage1_bytes(B, D, V)      # W once + H once + candidates written
+    traffic, traffic_source = (None, "no profile for this configuration")
+    if w.name == "C2" and B == 16 and args.variant == 0:
+        traffic, traffic_source = profiled_traffic()
     roofline = {
         "kernel": "stage1 (fused matmul + Gumbel-max epilogue)",
         "bound": "hbm",
@@ -149,11 +245,10 @@ def main() -> int:
         "unit": "GB/s",
         "frac": round(bytes_stage1 / (ms1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "us_per_launch": round(ms1 * 1e3, 2),
+        "us_per_launch_median": dist1["median_us"],
         "algorithmic_bytes_per_launch": bytes_stage1,
-        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE (x 2.0 KiB per count) + WRITE_SIZE
-        # (x 1.0 KiB per count), both scaled by a plain copy kernel of known size; measured for
-        # this launch configuration only (profiles/stage1_splitk_C2_B16_hbm_traffic_pmc.txt)
-        "traffic": MEASURED_TRAFFIC_C2_B16 if (w.name == "C2" and B == 16 and args.variant == 0) else None,
+        "traffic": traffic,
+        "traffic_source": traffic_source,
     }
 
     out = {
@@ -167,6 +262,7 @@ def main() -> int:
         "spinup_ms": args.spinup_ms,
         "ms_per_step": round(ms, 5),
         "us_per_call": round(ms * 1e3, 2),
+        "us_per_call_distribution": dist,
         "tokens_per_s": round(B / (ms * 1e-3), 1),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "higher_is_better": True,
@@ -177,6 +273,9 @@ def main() -> int:
         "config": {"workload": f"{w.name}: Llama-3-8B-shaped LM head, D={D}, V={V}, B={B}, bf16 W~N(0,1/D), "
                                "hidden~N(0,1), tau=1, per-row seeds",
                    "batch": B, "D": D, "V": V, "vocab_tile": fs.FS_VOCAB_TILE},
+        "timing_protocol": f"value / ms_per_step: one bracket around exactly {args.steps} calls after {args.warmup} "
+                           f"warm-ups; distributions: 25 warm-ups, {args.repeats} repeats x {args.calls} calls, an event "
+                           f"after every {args.group} calls, median over all samples, min / max of the per-repeat medians",
         "roofline": roofline,
     }
 
@@ -191,121 +290,92 @@ def main() -> int:
         out["calibration"] = {"probe_bytes": int(Wd.numel() * 2), "launches_each": args.calibrate}
         del dst
 
-    # ------------------------------------------------------------------ sweep B = 1..256
-    if not args.no_sweep:
+    if not args.quick:
+        # -------------------------------------------------------------- sweep B = 1..256 at the headline shape
         sweep = []
-        steps = max(20, args.steps // 2)
         for Bs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
-            ss = setup(Bs)
-            ss["lg"] = torch.empty((Bs, V), dtype=torch.float32, device="cuda")
-            f_ms = timed(fused, ss, steps, 10)
-            u_ms = timed(unfused, ss, steps, 10)
-            bf = iom.io_model_bytes(Bs, D, V, fused=True)
-            sweep.append({
-                "B": Bs,
-                "fused_us": round(f_ms * 1e3, 2),
-                "unfused_us": round(u_ms * 1e3, 2),
-                "fused_over_unfused_speedup": round(u_ms / f_ms, 4),
-                "tokens_per_s": round(Bs / (f_ms * 1e-3), 1),
-                "hbm_gbs": round(bf / (f_ms * 1e-3) / 1e9, 1),
-                "pct_hbm_peak": round(100.0 * bf / (f_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
-                "tflops": round(2.0 * Bs * D * V / (f_ms * 1e-3) / 1e12, 1),
-                "pct_mfma_peak": round(100.0 * 2.0 * Bs * D * V / (f_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
-            })
-            del ss
+            sweep.append(fused_vs_unfused(Leg(w, Wd, Bs, want_logits=True)))
         out["sweep"] = sweep
 
-    # ------------------------------------------------------------------ FP8 weights (same shape)
-    # The same call on E4M3 weight codes with per-row scales (a "next" row of the build, not the
-    # headline): the byte count of W halves, which is what the bandwidth-bound regime is made of.
-    if not args.no_sweep:
+        # -------------------------------------------------------------- sampling epilogue share of stage 1
+        share = []
+        for Bs in (1, 16, 64, 256):
+            leg = Leg(w, Wd, Bs)
+            on = per_call_us(leg.stage1)
+            off = per_call_us(leg.stage1_greedy)
+            share.append({"B": Bs, "stage1_sampling_us": on["median_us"], "stage1_noise_off_us": off["median_us"],
+                          "noise_share_pct": round(100.0 * (on["median_us"] - off["median_us"]) / on["median_us"], 2),
+                          "paper_sampling_share_pct": PAPER_SAMPLING_SHARE_PCT[Bs]})
+        out["epilogue_share"] = {
+            "what": "stage 1 with the noise switched off (FS_FLAG_GREEDY: no Philox, no logarithms; the 1/tau "
+                    "scaling, the per-tile arg max and the candidate store stay) against the sampling kernel; "
+                    "the paper's column is its sampling share of the fused kernel on its own GPU (context)",
+            "rows": share}
+
+        # -------------------------------------------------------------- FP8 / MXFP4 weights (same shape)
         codes, wscale = wl.quantize_e4m3(Wb)
         W8d = torch.from_numpy(codes).cuda()
         scd = torch.from_numpy(wscale).cuda()
         rows8 = []
         for Bq in (1, 16, 64):
-            q = setup(Bq)
-
-            def fused8(q):
-                fs.flash_sample_w8(q["Hd"], W8d, scd, q["tau"], seed=w.seed, row_seeds=q["seeds"],
-                                   out_idx=q["oi"], out_val=q["ov"], workspace=q["ws"], stream=stream)
-
-            ms8 = timed(fused8, q, 50, 10)
-            by8 = V * D + 2 * Bq * D + 16 * Bq * T + 8 * Bq
-            rows8.append({"B": Bq, "fused_us": round(ms8 * 1e3, 2), "hbm_gbs": round(by8 / (ms8 * 1e-3) / 1e9, 1),
-                          "pct_hbm_peak": round(100.0 * by8 / (ms8 * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)})
-            del q
-        out["fp8_weights"] = {"format": "OCP E4M3 codes + fp32 scale per vocabulary row, hidden bf16",
-                              "rows": rows8}
+            q = Leg(w, Wd, Bq)
+            d8 = per_call_us(lambda: fs.flash_sample_w8(q.Hd, W8d, scd, q.tau, seed=w.seed, row_seeds=q.seeds,
+                                                        out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
+            r = {"B": Bq, "fused_us": d8["median_us"], "fused_min_us": d8["min_us"], "fused_max_us": d8["max_us"]}
+            r.update(rates(Bq, D, V, d8["median_us"], w_bytes_per_row=D + 4))
+            rows8.append(r)
+        out["fp8_weights"] = {"format": "OCP E4M3 codes + fp32 scale per vocabulary row, hidden bf16", "rows": rows8}
         del W8d, scd, codes
-
-        # and on MXFP4 codes (E2M1, one E8M0 scale per 32 elements): the decode regime only
         c4, s4 = wl.quantize_mxfp4(Wb)
         W4d = torch.from_numpy(c4).cuda()
         S4d = torch.from_numpy(s4).cuda()
         rows4 = []
         for Bq in (1, 16):
-            q = setup(Bq)
-
-            def fused4b(q):
-                fs.flash_sample_w4(q["Hd"], W4d, S4d, q["tau"], seed=w.seed, row_seeds=q["seeds"],
-                                   out_idx=q["oi"], out_val=q["ov"], workspace=q["ws"], stream=stream)
-
-            ms4 = timed(fused4b, q, 50, 10)
-            by4 = V * (D // 2 + D // 32) + 2 * Bq * D + 16 * Bq * T + 8 * Bq
-            rows4.append({"B": Bq, "fused_us": round(ms4 * 1e3, 2), "hbm_gbs": round(by4 / (ms4 * 1e-3) / 1e9, 1),
-                          "pct_hbm_peak": round(100.0 * by4 / (ms4 * 1e-3) / 1e9 / HBM_PEAK_GBS, 2)})
-            del q
+            q = Leg(w, Wd, Bq)
+            d4 = per_call_us(lambda: fs.flash_sample_w4(q.Hd, W4d, S4d, q.tau, seed=w.seed, row_seeds=q.seeds,
+                                                        out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
+            r = {"B": Bq, "fused_us": d4["median_us"], "fused_min_us": d4["min_us"], "fused_max_us": d4["max_us"]}
+            r.update(rates(Bq, D, V, d4["median_us"], w_bytes_per_row=D // 2 + D // 32))
+            rows4.append(r)
         out["mxfp4_weights"] = {"format": "OCP MXFP4: E2M1 codes, one E8M0 scale per 32 elements, hidden bf16",
                                 "rows": rows4}
         del W4d, S4d, c4, s4
 
-    # ------------------------------------------------------------------ the paper's absolute-time shape
-    # The paper prints absolute kernel times only for D=8192, V=128256 (appendix table of
-    # tensor-parallel runtimes, TP=1 column; an 8 TB/s-class NVIDIA GPU, Triton kernel).  Same shape
-    # here, as context beside those figures: another machine's numbers, not a target.
-    if not args.no_sweep and not args.no_paper_shape:
-        w4 = wl.WORKLOADS["C4"]
-        W4 = to_device_bf16(wl.make_weights(w4))
-        paper_us = {16: (333.8, 385.0), 64: (344.1, 439.2), 256: (676.8, 669.7)}
-        rows = []
-        for Bq in (16, 64, 256):
-            q = dict(Hd=to_device_bf16(wl.make_hidden(w4, Bq)),
-                     tau=torch.from_numpy(wl.make_temperature(w4, Bq)).cuda(),
-                     ws=torch.empty(max(256, fs.flash_sample_workspace_bytes(Bq, w4.V)), dtype=torch.uint8, device="cuda"),
-                     oi=torch.empty(Bq, dtype=torch.int32, device="cuda"),
-                     ov=torch.empty(Bq, dtype=torch.float32, device="cuda"),
-                     lg=torch.empty((Bq, w4.V), dtype=torch.float32, device="cuda"))
-
-            def fused4(q):
-                fs.flash_sample_ex(q["Hd"], W4, q["tau"], seed=w4.seed, out_idx=q["oi"], out_val=q["ov"],
-                                   workspace=q["ws"], stream=stream)
-
-            def unfused4(q):
-                fs.flash_sample_unfused(q["Hd"], W4, q["tau"], seed=w4.seed, logits=q["lg"], out_idx=q["oi"],
-                                        out_val=q["ov"], workspace=q["ws"], stream=stream)
-
-            f_ms = timed(fused4, q, 50, 10)
-            u_ms = timed(unfused4, q, 50, 10)
-            rows.append({"B": Bq, "fused_us": round(f_ms * 1e3, 2), "unfused_us": round(u_ms * 1e3, 2),
-                         "paper_fused_us": paper_us[Bq][0], "paper_gumbel_on_stored_logits_us": paper_us[Bq][1]})
-            del q
-        out["paper_shape"] = {
-            "D": w4.D, "V": w4.V, "rows": rows,
-            "paper_numbers": "appendix table of tensor-parallel runtimes, TP=1 column: the paper's fused "
-                             "kernel and its FlashInfer Gumbel-max baseline on an 8 TB/s-class NVIDIA GPU; "
-                             "context only (other hardware, other software)",
-        }
-        del W4
+        # -------------------------------------------------------------- the other workloads
+        # C3 (Qwen-style vocabulary), C4 (D=8192: the shape of the paper's only absolute kernel
+        # times, which sit beside these rows as context: another machine, another kernel) and C5
+        # (wide hidden sweep); one weight matrix on the device at a time.
+        out["configs"] = {}
+        keep_head = (head.oi.clone(), head.H, head.tau_h, head.seeds_h)
+        del Wd, head
+        torch.cuda.empty_cache()
+        for name, batches in (("C3", (32, 64, 128)), ("C4", (16, 64, 256)), ("C5", (1, 8, 64, 256, 512))):
+            wk = wl.WORKLOADS[name]
+            Wk = to_device_bf16(wl.make_weights(wk))
+            rows = []
+            for Bq in batches:
+                row = fused_vs_unfused(Leg(wk, Wk, Bq, want_logits=True))
+                if name == "C4":
+                    row["paper_fused_us"], row["paper_gumbel_on_stored_logits_us"] = PAPER_ABS_US[Bq]
+                rows.append(row)
+            out["configs"][name] = {"D": wk.D, "V": wk.V, "note": wk.note, "rows": rows}
+            del Wk
+            torch.cuda.empty_cache()
+        out["configs"]["C4"]["paper_numbers"] = (
+            "appendix table of tensor-parallel runtimes, TP=1 column: the paper's fused kernel and its FlashInfer "
+            "Gumbel-max baseline on an 8 TB/s-class NVIDIA GPU; context only (other hardware, other software)")
+        head_oi, head_H, head_tau, head_seeds = keep_head
+    else:
+        head_oi, head_H, head_tau, head_seeds = head.oi, head.H, head.tau_h, head.seeds_h
 
     # ------------------------------------------------------------------ CPU oracle baseline
     if not args.no_cpu:
         import oracle
         oracle.lib()
         Bc = min(B, 16)
-        Hc = np.ascontiguousarray(s["H"][:Bc])
-        tc = np.ascontiguousarray(s["tau_h"][:Bc])
-        sc = None if s["seeds_h"] is None else np.ascontiguousarray(s["seeds_h"][:Bc])
+        Hc = np.ascontiguousarray(head_H[:Bc])
+        tc = np.ascontiguousarray(head_tau[:Bc])
+        sc = None if head_seeds is None else np.ascontiguousarray(head_seeds[:Bc])
         calls, t0 = 0, time.perf_counter()
         while True:   # whole calls for about ten seconds of CPU work
             ref = oracle.sample(Hc, Wb, tc, seed=w.seed, row_seeds=sc)
@@ -324,7 +394,7 @@ def main() -> int:
             "sample": f"mean of {calls} whole calls of the workload (B={Bc} rows, all V={V} logits per row), "
                       f"fp64 oracle, {dt * calls:.1f} s of wall time",
         }
-        same = int((ref["idx"] == s["oi"][:Bc].cpu().numpy()).sum())
+        same = int((ref["idx"] == head_oi[:Bc].cpu().numpy()).sum())
         out["cpu_baseline"]["rows_equal_to_gpu"] = f"{same}/{Bc}"
 
     print(json.dumps(out))
