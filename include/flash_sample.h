@@ -91,8 +91,9 @@ typedef enum {
 /* bits 16..19: tuning aid.  FS_VARIANT_SPLITK: workgroups per compute unit (0 = automatic).
  * FS_VARIANT_TILED2: tile shape (vocabulary rows x batch rows, waves), 0 = automatic,
  * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4),
- * 6 = 512x32 (8), 7 = 512x64 (8), 8 = 256x32 (4), 9 = 256x256 (8), 10 = 512x128 (8).  A hidden size
- * that is not a multiple of 64 always runs on shapes 8, 5 or 4 (by batch size). */
+ * 6 = 512x32 (8), 7 = 512x64 (8), 8 = 256x32 (4), 10 = 512x128 (8), 12 = 256x256 (4 waves, tiles loaded
+ * from global memory straight into LDS).  A hidden size that is not a multiple of 64 always runs on
+ * shapes 8, 5 or 4 (by batch size). */
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 #define FS_TUNE_TILE_SHAPE(n) FS_TUNE_WGS_PER_CU(n)
 
@@ -242,7 +243,7 @@ fs_status flash_group_choose(const float* group_log_mass, const int32_t* group_s
  *   logits        NULL, or fp32 [B, V]: also store y (for tests and the comparison path)
  *   workspace     at least flash_sample_workspace_bytes(B, V) bytes, 256-byte aligned
  *   flags         FS_FLAG_NONE, FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG; or, as a tuning aid, FS_VARIANT_SPLITK
- *                 (B <= 16, D <= 8192) / FS_VARIANT_TILED2 with FS_TUNE_TILE_SHAPE (shapes 9 and 10
+ *                 (B <= 16, D <= 8192) / FS_VARIANT_TILED2 with FS_TUNE_TILE_SHAPE (shapes 10 and 12
  *                 run as shape 3; D % 128 != 0 always runs on shapes 8, 5 or 4)
  * NaN codes (S.1111.111) propagate to NaN logits, which never win.
  */

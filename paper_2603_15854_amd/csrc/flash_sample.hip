@@ -51,15 +51,16 @@ fs_status current_device(int* dev_out, int* cus_out)
 //   B = 32   V = 128256: s6 161, s8 160, s1 165-173 | 152064: s8 187, s6 230 | 201088: s6 257, s8 277
 //   B = 64   V = 50304: s2 74, s5 81, s7 108 | 100352: s7 132, s2 147, s5 150 | 152064: s5 190, s2 212, s7 247
 //   B = 128  V = 50304: s3 84, s4 99, s10 136 | 100352: s10 149, s3 172, s4 187 | 128256: s10 182, s3 195-203, s4 217
-//   B = 256  V = 32000: s3 84, s4 96, s9 124 | 128256: s9 301, s3 376 | 201088: s9 515, s4 570, s3 573
-// and at D = 8192, V = 128256, B <= 16: s6 307, s8 315, s1 317; B = 256: s9 562 against 699 for s3.
+//   B = 256  V = 32000: s3 84, s4 96 | 128256: s12 259, s3 346 | D = 8192: s12 488, s3 648
+// (s12 is the 256 x 256 kernel with direct global -> LDS loads; the 256 x 256 shape of the tiled
+// kernel it replaced ran at 301 and 566) and at D = 8192, V = 128256, B <= 16: s6 307, s8 315, s1 317.
 int pick_tile_shape(int B, int V, int cus)
 {
     struct TileShape { int id, vt, bt; };
     static constexpr TileShape b32[] = {{1, 128, 32}, {8, 256, 32}, {6, 512, 32}};
     static constexpr TileShape b64[] = {{5, 128, 64}, {2, 256, 64}, {7, 512, 64}};
     static constexpr TileShape b128[] = {{4, 128, 128}, {3, 256, 128}, {10, 512, 128}};
-    static constexpr TileShape big[] = {{4, 128, 128}, {3, 256, 128}, {9, 256, 256}};
+    static constexpr TileShape big[] = {{4, 128, 128}, {3, 256, 128}, {12, 256, 256}};
     const TileShape* cand = B <= 32 ? b32 : B <= 64 ? b64 : B <= 128 ? b128 : big;
     int best = cand[0].id;
     long long best_cost = -1;

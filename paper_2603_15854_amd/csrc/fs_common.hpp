@@ -251,6 +251,24 @@ __device__ __forceinline__ void epilogue_quad(const Stage1Params& p, const RowEp
     }
 }
 
+// The plain epilogue (1/tau scaling, default log mode) for a quad that needs no checks: vid0 % 4 == 0
+// and all four ids valid.  Same arithmetic as epilogue_quad<false>, without a branch, so that a
+// caller can run several independent quads side by side (the ten Philox rounds are one long
+// dependent chain, and a wave that is alone on its SIMD has nothing else to overlap it with).
+__device__ __forceinline__ void epilogue_quad_fast(uint64_t seed, uint32_t row_word, float inv_tau, const f32x4 y,
+                                                   int vid0, float& best, int& best_id)
+{
+    uint32_t w[4];
+    philox4x32_10((uint32_t)vid0 >> 2, row_word, 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const float s = fmaf(y[j], inv_tau, gumbel_from_word(w[j]));
+        const bool take = s > best;
+        best = take ? s : best;
+        best_id = take ? vid0 + j : best_id;
+    }
+}
+
 __device__ __forceinline__ uint4 ld_global_16B(const uint16_t* p)
 {
     return *reinterpret_cast<const uint4*>(p);

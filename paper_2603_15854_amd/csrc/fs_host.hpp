@@ -65,6 +65,7 @@ int pick_tile_shape(int B, int V, int cus);
 fs_status launch_stage1_splitk(const Stage1Params& p, bool full, int wgs_per_cu, hipStream_t st);
 fs_status launch_stage1_tiled(const Stage1Params& p, int shape, hipStream_t st);
 fs_status launch_stage1_tiled_full(const Stage1Params& p, int shape, hipStream_t st);
+fs_status launch_stage1_dma(const Stage1Params& p, bool full, hipStream_t st);
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
 fs_status launch_mxfp4_decode(const uint32_t* codes, const uint8_t* scales, int n8, float* out, hipStream_t st);

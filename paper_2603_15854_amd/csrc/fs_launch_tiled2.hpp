@@ -41,8 +41,9 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //   2: 256 x 64   8 waves, one per CU                 6: 512 x 32   8 waves, one per CU
 //   3: 256 x 128  8 waves, one per CU                 7: 512 x 64   8 waves, one per CU
 //   4: 128 x 128  4 waves, two per CU                 8: 256 x 32   4 waves, two per CU
-//   9: 256 x 256  8 waves, one per CU (accumulators take 128 VGPRs)
 //  10: 512 x 128  8 waves, one per CU, one register set of prefetch (128 accumulator VGPRs, 160 KB of LDS)
+//  12: 256 x 256  4 waves, the kernel with direct global -> LDS loads of fs_stage1_dma.hpp (another
+//      translation unit); 9 was the 256 x 256 shape of this kernel, which 12 replaced
 using Shape1 = Tiled2Cfg<32, 4, 1, 4>;
 using Shape2 = Tiled2Cfg<64, 4, 2, 2, 2, 256>;
 using Shape3 = Tiled2Cfg<128, 4, 2, 1, 2, 256>;
@@ -51,7 +52,6 @@ using Shape5 = Tiled2Cfg<64, 2, 2, 2, 2>;
 using Shape6 = Tiled2Cfg<32, 8, 1, 1, 1, 512>;
 using Shape7 = Tiled2Cfg<64, 4, 2, 1, 1, 512>;
 using Shape8 = Tiled2Cfg<32, 4, 1, 1, 2, 256>;
-using Shape9 = Tiled2Cfg<256, 4, 2, 1, 2, 256, 2>;
 using Shape10 = Tiled2Cfg<128, 4, 2, 1, 2, 512, 1>;
 
 // A hidden size that is not a multiple of the K step runs on the three two-per-CU shapes, built
@@ -64,7 +64,7 @@ fs_status launch_tiled2_ragged(const Stage1Params& p, hipStream_t st)
     return launch_tiled2<Shape4, FULL, WB, false, true>(p, st);
 }
 
-// bf16 weights.  `shape` = 0 picks by pick_tile_shape; 1..10 forces one shape (tuning aid and
+// bf16 weights.  `shape` = 0 picks by pick_tile_shape; 1..8, 10, 12 force one shape (tuning aid and
 // tiling-invariance tests; honoured for whole-K-step hidden sizes only).
 template <bool FULL>
 fs_status launch_tiled2_bf16(const Stage1Params& p, int shape, hipStream_t st)
@@ -85,8 +85,8 @@ fs_status launch_tiled2_bf16(const Stage1Params& p, int shape, hipStream_t st)
     case 6: return launch_tiled2<Shape6, FULL>(p, st);
     case 7: return launch_tiled2<Shape7, FULL>(p, st);
     case 8: return launch_tiled2<Shape8, FULL>(p, st);
-    case 9: return launch_tiled2<Shape9, FULL, 2, false, false, true>(p, st);
     case 10: return launch_tiled2<Shape10, FULL>(p, st);
+    case 12: return launch_stage1_dma(p, FULL, st);
     default: break;
     }
     return FS_ERR_UNSUPPORTED;

@@ -42,8 +42,8 @@ fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStre
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512, 1>, false, 1, true>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, false, 1, true>(p, st);
     case 3:
-    case 9:    // 256 x 256 and 512 x 128 do not fit LDS with two hidden sub-tiles per step:
-    case 10:   // both run as 256 x 128 (B = 256: 299 us, no slower than a 256 x 256 park-time form)
+    case 10:   // 512 x 128 and 256 x 256 do not fit LDS with two hidden sub-tiles per step:
+    case 12:   // both run as 256 x 128
         return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true, false, true>(p, st);
     default: break;
     }

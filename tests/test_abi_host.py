@@ -157,13 +157,13 @@ def test_kernel_choice_by_shape():
     # tile shape with the cheapest busiest CU, ceil(workgroups / CUs) * (rows + columns), finer on ties
     kc = fsm.flash_measure_kernel_choice
     assert [kc(B, 4096, 128256) for B in (1, 16)] == [0, 0]
-    assert [kc(B, 4096, 128256) for B in (17, 32, 64, 128, 129, 256, 512)] == [6, 6, 7, 10, 9, 9, 9]
+    assert [kc(B, 4096, 128256) for B in (17, 32, 64, 128, 129, 256, 512)] == [6, 6, 7, 10, 12, 12, 12]
     assert kc(16, 8192, 128256) == 6 and kc(1, 7168, 129280) == 6          # wide hidden sizes: tiled
     # the choices measured fastest on the machine (D = 4096, 256 CUs)
     assert [kc(32, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [1, 8, 6, 1, 6]
     assert [kc(64, 4096, V) for V in (32000, 50304, 100352, 152064)] == [5, 2, 7, 5]
     assert [kc(128, 4096, V) for V in (32000, 50304, 100352, 152064, 201088, 256000)] == [4, 3, 10, 4, 10, 10]
-    assert [kc(256, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [3, 9, 9, 9, 9]
+    assert [kc(256, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [3, 12, 12, 12, 12]
     assert [kc(B, 520, 128256) for B in (20, 64, 200)] == [8, 5, 4]        # D % 64 != 0
     assert kc(4, 4096, 1000) == 0 and kc(40, 4096, 1000) == 5              # a handful of tiles: fine shapes
     assert kc(0, 4096, 10) == -1 and kc(4, 4100, 10) == -1 and kc(4, 4096, 10, 0) == -1

@@ -155,11 +155,12 @@ def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
         _small_case(fs, orc, B, D, V, variant, data_seed=70 + B, tune=tune)
 
 
-@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12])
 def test_every_tile_shape_of_the_tiled_kernel(fs, orc, tile_shape):
     # the shapes the launcher can pick (128/256/512 vocabulary rows x 32/64/128 batch rows), each on
     # ragged V, B smaller and larger than its batch tile, and a K tail (D % 64 != 0)
-    for B, D, V in [(20, 520, 1100), (70, 256, 3000), (150, 1032, 700), (33, 64, 513), (300, 128, 600)]:
+    for B, D, V in [(20, 520, 1100), (70, 256, 3000), (150, 1032, 700), (33, 64, 513), (300, 128, 600), (257, 1024, 1300),
+                    (128, 4096, 700)]:
         print(f"tile shape {tile_shape} B={B} D={D} V={V}", flush=True)
         _small_case(fs, orc, B, D, V, 7, data_seed=140 + B, tune=tile_shape)
 

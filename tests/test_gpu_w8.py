@@ -86,9 +86,9 @@ def test_w8_at_llama_shape(fs, orc):
     assert v.ok, (str(v), v.failures[:3])
 
 
-@pytest.mark.parametrize("tune", [-1, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("tune", [-1, 1, 2, 3, 4, 5, 6, 7, 8, 10, 12])
 def test_w8_every_kernel_choice(fs, orc, tune):
-    # -1: the split-K kernel forced; 1..10: the tile shapes of the tiled kernel (codes kept in LDS when
+    # -1: the split-K kernel forced; others: the tile shapes of the tiled kernel (codes kept in LDS when
     # D % 128 == 0, widened at park time on the two-per-CU shapes otherwise)
     shapes = [(10, 528, 1100), (16, 2048, 700), (7, 8192, 300)] if tune < 0 else \
         [(20, 528, 1100), (70, 256, 1500), (150, 1152, 700), (33, 48, 513), (40, 192, 600)]
