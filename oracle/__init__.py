@@ -143,6 +143,14 @@ def lib():
     L.fso_grouped_draw_counts.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int64,
                                           C.c_int64, _i64p]
     L.fso_grouped_draw_counts.restype = None
+    L.fso_topk_row.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int64, _f64p, _i64p, C.POINTER(C.c_double)]
+    L.fso_topk_row.restype = C.c_int
+    L.fso_top_p_cut.argtypes = [_f64p, C.c_int64, C.c_double, C.POINTER(C.c_double)]
+    L.fso_top_p_cut.restype = C.c_int64
+    L.fso_sample_topk.argtypes = [_u16p, _u16p, C.c_int64, C.c_int64, C.c_int64, _f32p, C.c_uint64, C.c_void_p,
+                                  C.c_int64, C.c_int64, C.c_int64, C.c_double, C.c_int, _i32p, _f32p, _f64p, _i64p,
+                                  _i64p, _f64p, _f64p, _f64p, _f64p]
+    L.fso_sample_topk.restype = C.c_int
     _lib = L
     return L
 
@@ -498,3 +506,52 @@ def grouped_draw_counts(z, g: int, mode: int, seed: int, ndraws: int, row0: int 
 
 def num_threads() -> int:
     return int(lib().fso_num_threads())
+
+
+# ----------------------------------------------------------------------------- truncated supports
+
+TOPK_TRUNCATE, TOPK_GUMBEL = 0, 1
+
+
+def topk_row(key, k: int, vocab_offset: int = 0):
+    """The k largest keys of a row by a full sort -> (keys [k], ids [k], (k+1)-th key)."""
+    key = np.ascontiguousarray(key, dtype=np.float64)
+    ok = np.empty(k, dtype=np.float64)
+    oi = np.empty(k, dtype=np.int64)
+    nxt = C.c_double()
+    if lib().fso_topk_row(key, key.size, k, vocab_offset, ok, oi, C.byref(nxt)) != 0:
+        raise MemoryError("oracle: out of memory")
+    return ok, oi, nxt.value
+
+
+def top_p_cut(z_sorted, top_p: float):
+    """Nucleus rule on candidates in descending order -> (number kept, mass of the kept prefix without its last)."""
+    z = np.ascontiguousarray(z_sorted, dtype=np.float64)
+    mb = C.c_double()
+    n = lib().fso_top_p_cut(z, z.size, float(top_p), C.byref(mb))
+    return int(n), mb.value
+
+
+def sample_topk(H, W, tau, k: int, top_p: float = 1.0, mode: int = TOPK_TRUNCATE, seed: int = 0, row_seeds=None,
+                row_offset: int = 0, vocab_offset: int = 0):
+    """Top-k / nucleus draw (mode TOPK_TRUNCATE) or Gumbel-top-k (mode TOPK_GUMBEL).  Returns
+    dict(idx, val, top_key [B,k], top_id [B,k], n_kept, kth1, mass_before, top1, top2, threads)."""
+    B, D = H.shape
+    V = W.shape[0]
+    tau = np.ascontiguousarray(tau, dtype=np.float32)
+    rs, rs_p = _opt_ptr(row_seeds, np.uint64)
+    out_idx = np.empty(B, dtype=np.int32)
+    out_val = np.empty(B, dtype=np.float32)
+    top_key = np.empty((B, k), dtype=np.float64)
+    top_id = np.empty((B, k), dtype=np.int64)
+    n_kept = np.empty(B, dtype=np.int64)
+    kth1 = np.empty(B, dtype=np.float64)
+    mass_before = np.empty(B, dtype=np.float64)
+    top1 = np.empty(B, dtype=np.float64)
+    top2 = np.empty(B, dtype=np.float64)
+    nt = lib().fso_sample_topk(H, W, B, D, V, tau, seed, rs_p, row_offset, vocab_offset, k, float(top_p), int(mode),
+                               out_idx, out_val, top_key, top_id, n_kept, kth1, mass_before, top1, top2)
+    if nt < 0:
+        raise MemoryError("oracle: out of memory")
+    return dict(idx=out_idx, val=out_val, top_key=top_key, top_id=top_id, n_kept=n_kept, kth1=kth1,
+                mass_before=mass_before, top1=top1, top2=top2, threads=nt)

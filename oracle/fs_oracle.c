@@ -33,7 +33,8 @@
  * log sum_i exp(z_i) are the second group of functions (fso_transform_row and below); the
  * grouped variants (parallel and online Group-Gumbel-Max) are the third (fso_group_word and below);
  * FP8 (E4M3) weights with per-row scales are the fourth (fso_e4m3_to_double and below), MXFP4
- * weights the fifth (fso_e2m1_to_double and below).
+ * weights the fifth (fso_e2m1_to_double and below); truncated supports (top-k, nucleus on the k
+ * candidates, Gumbel-top-k) the sixth (fso_topk_row and below).
  *
  * NaN scores never win (the strict > comparison is false for NaN); a row with no
  * score > -inf returns idx = -1, val = -inf.
@@ -694,6 +695,168 @@ double fso_score_at_w4(const uint16_t* H, const uint8_t* W4, const uint8_t* S, i
 }
 
 /* ------------------------------------------------------------------ helpers for the pins */
+
+/* ------------------------------------------------------------------ truncated supports */
+
+/*
+ * Section "Top-k, Nucleus Sampling, and Masking".  Two uses of "the k largest of a row":
+ *   truncation     the support is cut to the k ids with the largest transformed logits z_i, and
+ *                  the draw is a Gumbel-max over that support (which is the masked draw of the same
+ *                  section with every other id set to -inf, hence exact on the restricted support);
+ *                  optionally the nucleus rule is applied on those k candidates first;
+ *   Gumbel-top-k   the k ids with the largest PERTURBED scores s_i = z_i + g_i, in descending
+ *                  order: a draw of k ids without replacement (the trick the section cites); its
+ *                  first element is the plain Gumbel-max sample.
+ * Order used everywhere: larger key first; equal keys: lower id first.  NaN keys count as -inf
+ * (they never win).  The paper fixes none of these details.
+ */
+typedef struct { double key; int64_t id; } fso_pair;
+
+static int fso_pair_cmp(const void* a, const void* b)
+{
+    const fso_pair* x = (const fso_pair*)a;
+    const fso_pair* y = (const fso_pair*)b;
+    if (x->key > y->key) return -1;
+    if (x->key < y->key) return 1;
+    return x->id < y->id ? -1 : (x->id > y->id ? 1 : 0);
+}
+
+/* The k largest keys of key[0..V) by a full sort: out_key/out_id [k] in descending order (lower id
+ * first on ties), ids reported as vocab_offset + i; slots past V are (-inf, -1).  If kth1 is not
+ * NULL it receives the (k+1)-th largest key (-inf if there is none): the runner-up of the cut. */
+int fso_topk_row(const double* key, int64_t V, int64_t k, int64_t vocab_offset, double* out_key,
+                 int64_t* out_id, double* kth1)
+{
+    fso_pair* p = (fso_pair*)malloc(sizeof(fso_pair) * (size_t)V);
+    if (!p) return -1;
+    for (int64_t i = 0; i < V; ++i) {
+        p[i].key = isnan(key[i]) ? -INFINITY : key[i];
+        p[i].id = vocab_offset + i;
+    }
+    qsort(p, (size_t)V, sizeof(fso_pair), fso_pair_cmp);
+    for (int64_t j = 0; j < k; ++j) {
+        out_key[j] = j < V ? p[j].key : -INFINITY;
+        out_id[j] = j < V ? p[j].id : -1;
+    }
+    if (kth1) *kth1 = k < V ? p[k].key : -INFINITY;
+    free(p);
+    return 0;
+}
+
+/*
+ * Nucleus rule on k candidates given in descending order of z: q_j = exp(z_j) / sum_{l<k} exp(z_l)
+ * (the softmax over the candidates only, as the section applies top-p after top-k); keep the
+ * shortest prefix whose mass reaches top_p, at least one candidate.  Candidates with z = -inf
+ * (padding) carry no mass.  Returns the number kept; *mass_before (if not NULL) receives the
+ * cumulative mass of the kept prefix WITHOUT its last element (how close the cut was to moving).
+ * top_p >= 1 keeps every candidate that has mass.
+ */
+int64_t fso_top_p_cut(const double* z_sorted, int64_t k, double top_p, double* mass_before)
+{
+    if (mass_before) *mass_before = 0.0;
+    if (k <= 0 || !(z_sorted[0] > -INFINITY)) return 0;
+    double zmax = z_sorted[0], sum = 0.0;
+    int64_t live = 0;
+    for (int64_t j = 0; j < k; ++j)
+        if (z_sorted[j] > -INFINITY) { sum += exp(z_sorted[j] - zmax); ++live; }
+    if (top_p >= 1.0) {
+        if (mass_before) *mass_before = live > 0 ? (sum - exp(z_sorted[live - 1] - zmax)) / sum : 0.0;
+        return live;
+    }
+    double cum = 0.0;
+    for (int64_t j = 0; j < live; ++j) {
+        if (mass_before) *mass_before = cum / sum;
+        cum += exp(z_sorted[j] - zmax);
+        if (cum / sum >= top_p) return j + 1;
+    }
+    return live;
+}
+
+/*
+ * One row.  mode 0 (truncation): z_i = y_i / tau; S = top-k of z; nucleus cut on S; the sample is
+ * argmax_{i in kept} (z_i + g_i) with the per-(row, id) noise of the main path, lowest id on ties.
+ * mode 1 (Gumbel-top-k): S = top-k of s_i = z_i + g_i; the sample is its first element.
+ * Outputs: top_key/top_id [k] (z or s, sorted), *n_kept, *best_id / *best_val (perturbed score),
+ * *kth1 = the (k+1)-th key, *mass_before as in fso_top_p_cut, *second_val = runner-up perturbed
+ * score among the kept candidates (mode 0) or the second key (mode 1).
+ */
+int fso_sample_topk_row(const double* y, int64_t V, double tau, uint64_t seed, int64_t row,
+                        int64_t vocab_offset, int64_t k, double top_p, int mode, double* top_key,
+                        int64_t* top_id, int64_t* n_kept, int64_t* best_id, double* best_val,
+                        double* kth1, double* mass_before, double* second_val)
+{
+    double* key = (double*)malloc(sizeof(double) * (size_t)V);
+    if (!key) return -1;
+    for (int64_t i = 0; i < V; ++i) {
+        key[i] = y[i] / tau;
+        if (mode == 1) key[i] += fso_gumbel(seed, row, vocab_offset + i);
+    }
+    int rc = fso_topk_row(key, V, k, vocab_offset, top_key, top_id, kth1);
+    free(key);
+    if (rc != 0) return rc;
+    if (mode == 1) {
+        int64_t live = 0;
+        for (int64_t j = 0; j < k; ++j) if (top_id[j] >= 0 && top_key[j] > -INFINITY) ++live;
+        *n_kept = live;
+        *best_id = live > 0 ? top_id[0] : -1;
+        *best_val = live > 0 ? top_key[0] : -INFINITY;
+        if (second_val) *second_val = live > 1 ? top_key[1] : -INFINITY;
+        if (mass_before) *mass_before = 0.0;
+        return 0;
+    }
+    *n_kept = fso_top_p_cut(top_key, k, top_p, mass_before);
+    double m = -INFINITY, m2 = -INFINITY;
+    int64_t im = -1;
+    /* Gumbel-max over the kept candidates in ascending id order with a strict >: lowest id on ties */
+    fso_pair* q = (fso_pair*)malloc(sizeof(fso_pair) * (size_t)(*n_kept > 0 ? *n_kept : 1));
+    if (!q) return -1;
+    for (int64_t j = 0; j < *n_kept; ++j) { q[j].key = -(double)top_id[j]; q[j].id = j; }   /* by id, ascending */
+    qsort(q, (size_t)*n_kept, sizeof(fso_pair), fso_pair_cmp);
+    for (int64_t t = 0; t < *n_kept; ++t) {
+        const int64_t j = q[t].id;
+        const double s = top_key[j] + fso_gumbel(seed, row, top_id[j]);
+        if (s > m) { m2 = m; m = s; im = top_id[j]; }
+        else if (s > m2) m2 = s;
+    }
+    free(q);
+    *best_id = im;
+    *best_val = m;
+    if (second_val) *second_val = m2;
+    return 0;
+}
+
+/* Batch form.  Arrays: top_key/top_id [B, k]; n_kept, kth1, mass_before, top1, top2 [B]. */
+int fso_sample_topk(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D, int64_t V,
+                    const float* tau, uint64_t seed, const uint64_t* row_seeds, int64_t row_offset,
+                    int64_t vocab_offset, int64_t k, double top_p, int mode, int32_t* out_idx,
+                    float* out_val, double* top_key, int64_t* top_id, int64_t* n_kept, double* kth1,
+                    double* mass_before, double* top1_val, double* top2_val)
+{
+    if (B <= 0 || V <= 0 || k <= 0) return 0;
+    double* Y = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+    if (!Y) return -1;
+    int nthreads = fso_logits(H, W, B, D, V, Y);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t b = 0; b < B; ++b) {
+        int64_t bid;
+        double bval, second;
+        int rc = fso_sample_topk_row(Y + b * V, V, (double)tau[b], row_seed(seed, row_seeds, b), row_offset + b,
+                                     vocab_offset, k, top_p, mode, top_key + b * k, top_id + b * k, n_kept + b,
+                                     &bid, &bval, kth1 + b, mass_before + b, &second);
+        if (rc != 0) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        out_idx[b] = (int32_t)bid;
+        if (out_val) out_val[b] = (float)bval;
+        if (top1_val) top1_val[b] = bval;
+        if (top2_val) top2_val[b] = second;
+    }
+    free(Y);
+    return failed ? -1 : nthreads;
+}
 
 /* counts[i] += number of draws that picked i, over draws k = 0..ndraws-1.
  * by_row != 0: draw k uses (seed, row = row0 + k); else (seed + k, row = row0). */
