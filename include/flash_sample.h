@@ -181,6 +181,48 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
                             void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
 /*
+ * Truncated supports (Section "Top-k, Nucleus Sampling, and Masking": each tile computes its top-k
+ * candidates locally, a second stage reduces them to a global top-k, and the nucleus rule is applied
+ * on the k candidates; the paper gives the scheme and leaves the implementation open).  With
+ * z_{b,i} = y_{b,i} / temperature_b and the per-id noise g of the main path:
+ *   FS_TOPK_TRUNCATE  S_b = the k ids with the largest z (ties: lower id first).  If top_p < 1 the
+ *                     candidates, in that order, get q_j = softmax over S_b, and only the shortest
+ *                     prefix whose mass reaches top_p is kept (at least one).  The draw is
+ *                     i*_b = argmax over the kept ids of z + g: an exact sample of the softmax
+ *                     restricted to them (it is the masked draw of flash_sample_full with every other
+ *                     id forbidden).  out_val = the winning perturbed score.
+ *   FS_TOPK_GUMBEL    the k ids with the largest perturbed scores z + g, in descending order: a draw of
+ *                     k ids without replacement (the Gumbel-top-k trick); out_idx / out_val are its
+ *                     first element, which is exactly flash_sample_ex's sample.  top_p must be 1.
+ *   k          1 .. FS_TOPK_MAX_K;  top_p in (0, 1]
+ *   topk_val   NULL, or fp32 [B, k]: the keys of the k candidates in order (z, or z + g)
+ *   topk_idx   NULL, or int32 [B, k]: their global ids; slots past V are (-inf, -1)
+ *   n_kept     NULL, or int32 [B]: candidates kept by the nucleus rule (those with a key > -inf)
+ *   workspace  at least flash_sample_topk_workspace_bytes(B, V, k) bytes, 256-byte aligned
+ *   flags      FS_FLAG_NONE or FS_FLAG_EXACT_LOG
+ * NaN logits count as -inf.  flash_sample_topk is the fused form: stage 1 writes k (at most 128)
+ * sorted candidates per row and 128-id tile instead of one, and the [B, V] logits never reach device
+ * memory; it needs D % 64 == 0 (FS_ERR_UNSUPPORTED otherwise).  flash_sample_topk_unfused is the
+ * comparison form for any D: the logits-store GEMM writes `logits` (fp32 [B, V], overwritten with
+ * the keys), and the same reduction runs over the stored row.  Same results up to fp32 rounding.
+ */
+#define FS_TOPK_TRUNCATE 0
+#define FS_TOPK_GUMBEL 1
+#define FS_TOPK_MAX_K 64
+size_t flash_sample_topk_workspace_bytes(int B, int V, int k);
+fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int V,
+                            const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                            int64_t row_offset, int32_t vocab_offset, int k, float top_p, int mode,
+                            int32_t* out_idx, float* out_val, float* topk_val, int32_t* topk_idx, int32_t* n_kept,
+                            void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+fs_status flash_sample_topk_unfused(const void* hidden, const void* W, int B, int D, int V,
+                                    const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                                    int64_t row_offset, int32_t vocab_offset, int k, float top_p, int mode,
+                                    float* logits, int32_t* out_idx, float* out_val, float* topk_val,
+                                    int32_t* topk_idx, int32_t* n_kept,
+                                    void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
+
+/*
  * Grouped variants (Section "Group-Gumbel-Max: Hierarchical Exact Sampling"; appendix algorithms
  * "FlashSampling (parallel)" and "FlashSampling (sequential/online)").  The vocabulary is cut
  * into groups of 128 * group_tiles consecutive ids (the last group may be shorter).  Stage 1 is

@@ -36,6 +36,7 @@ EXPORTS = (
     "flash_sample_num_tiles", "flash_sample_workspace_bytes", "flash_sample", "flash_sample_ex",
     "flash_sample_static",
     "flash_sample_full", "flash_sample_full_workspace_bytes",
+    "flash_sample_topk", "flash_sample_topk_unfused", "flash_sample_topk_workspace_bytes",
     "flash_sample_grouped", "flash_sample_num_groups", "flash_group_choose",
     "flash_sample_w8", "flash_sample_e4m3_decode", "flash_sample_w4", "flash_sample_mxfp4_decode",
     "flash_sample_stage1", "flash_sample_stage2", "flash_sample_unfused", "flash_lm_head_logits",
@@ -94,6 +95,14 @@ def lib():
     L.flash_sample_full.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
                                     vp, vp, vp, vp, sz, vp, u32]
     L.flash_sample_full.restype = i32
+    L.flash_sample_topk_workspace_bytes.argtypes = [i32, i32, i32]
+    L.flash_sample_topk_workspace_bytes.restype = sz
+    L.flash_sample_topk.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, i32, C.c_float, i32,
+                                    vp, vp, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_topk.restype = i32
+    L.flash_sample_topk_unfused.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, i32, C.c_float, i32,
+                                            vp, vp, vp, vp, vp, vp, vp, sz, vp, u32]
+    L.flash_sample_topk_unfused.restype = i32
     L.flash_sample_num_groups.argtypes = [i32, i32]
     L.flash_sample_num_groups.restype = i32
     L.flash_sample_grouped.argtypes = [vp, vp, i32, i32, i32, vp, u64, vp, i64, C.c_int32, vp, vp, i64,
@@ -369,6 +378,39 @@ def flash_sample_e4m3_decode(codes, out=None, stream=None):
 
 
 FS_GROUPED_PARALLEL, FS_GROUPED_ONLINE = 0, 1
+FS_TOPK_TRUNCATE, FS_TOPK_GUMBEL = 0, 1
+FS_TOPK_MAX_K = 64
+
+
+def flash_sample_topk_workspace_bytes(B: int, V: int, k: int) -> int:
+    return int(lib().flash_sample_topk_workspace_bytes(int(B), int(V), int(k)))
+
+
+def flash_sample_topk(hidden, W, temperature, k: int, top_p: float = 1.0, mode: int = FS_TOPK_TRUNCATE, seed: int = 0,
+                      row_seeds=None, row_offset: int = 0, vocab_offset: int = 0, fused: bool = True, logits=None,
+                      out_idx=None, out_val=None, workspace=None, stream=None, flags: int = 0):
+    """Top-k / nucleus draw (FS_TOPK_TRUNCATE) or Gumbel-top-k (FS_TOPK_GUMBEL).  fused=False runs the
+    comparison form over stored logits.  Returns (out_idx, out_val, topk_val [B,k], topk_idx [B,k], n_kept [B])."""
+    import torch
+    B, D, V = _shapes(hidden, W)
+    out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
+    tv = torch.empty((B, k), dtype=torch.float32, device=hidden.device)
+    ti = torch.empty((B, k), dtype=torch.int32, device=hidden.device)
+    nk = torch.empty(B, dtype=torch.int32, device=hidden.device)
+    workspace, ws_bytes = _scratch(flash_sample_topk_workspace_bytes(B, V, k), hidden.device, workspace, stream)
+    common = (_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed), _seeds(row_seeds, B),
+              int(row_offset), int(vocab_offset), int(k), float(top_p), int(mode))
+    tail = (_ptr(out_idx), _ptr(out_val), _ptr(tv), _ptr(ti), _ptr(nk), _ptr(workspace), ws_bytes, _stream_ptr(stream),
+            int(flags))
+    if fused:
+        st = lib().flash_sample_topk(*common, *tail)
+        _check(st, "flash_sample_topk")
+    else:
+        if logits is None:
+            logits = torch.empty((B, V), dtype=torch.float32, device=hidden.device)
+        st = lib().flash_sample_topk_unfused(*common, _f32(logits, B * V, "logits"), *tail)
+        _check(st, "flash_sample_topk_unfused")
+    return out_idx, out_val, tv, ti, nk
 
 
 def flash_sample_num_groups(V: int, group_tiles: int) -> int:

@@ -595,6 +595,117 @@ fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_o
                   static_cast<hipStream_t>(stream), words, n, g_out, flags);
 }
 
+// ---- truncated supports
+
+namespace {
+
+struct TopkWs {
+    float* pair_val; int32_t* pair_idx;     // [B, T * kt]   per-tile candidates (fused path only)
+    float* tmp_val; int32_t* tmp_idx;       // [B, chunks * k]
+    float* fin_val; int32_t* fin_idx;       // [B, k]
+    size_t bytes;
+};
+
+// n_cand: candidates per row of the first selection pass (T * kt fused, V unfused)
+TopkWs carve_topk(void* ws, int B, int V, int k, bool fused)
+{
+    const int kt = k < kVocabTile ? k : kVocabTile;
+    const size_t pairs = fused ? align_up((size_t)B * (size_t)num_tiles(V) * (size_t)kt * 4, 256) : 0;
+    const int n_cand = fused ? num_tiles(V) * kt : V;
+    const size_t tmp = align_up((size_t)B * (size_t)topk_chunks(B, n_cand) * (size_t)k * 4, 256);
+    const size_t fin = align_up((size_t)B * (size_t)k * 4, 256);
+    unsigned char* q = static_cast<unsigned char*>(ws);
+    TopkWs w;
+    w.pair_val = reinterpret_cast<float*>(q); q += pairs;
+    w.pair_idx = reinterpret_cast<int32_t*>(q); q += pairs;
+    w.tmp_val = reinterpret_cast<float*>(q); q += tmp;
+    w.tmp_idx = reinterpret_cast<int32_t*>(q); q += tmp;
+    w.fin_val = reinterpret_cast<float*>(q); q += fin;
+    w.fin_idx = reinterpret_cast<int32_t*>(q); q += fin;
+    w.bytes = 2 * (pairs + tmp + fin);
+    return w;
+}
+
+fs_status check_topk(int B, int k, float top_p, int mode, uint32_t flags, const void* temperature, const void* out_idx,
+                     const void* out_val, const void* topk_val, const void* topk_idx, const void* n_kept,
+                     const void* row_seeds)
+{
+    if (k < 1 || k > FS_TOPK_MAX_K) return FS_ERR_SHAPE;
+    if (mode != FS_TOPK_TRUNCATE && mode != FS_TOPK_GUMBEL) return FS_ERR_SHAPE;
+    if (!(top_p > 0.0f) || top_p > 1.0f) return FS_ERR_SHAPE;                 // also rejects NaN
+    if (mode == FS_TOPK_GUMBEL && top_p != 1.0f) return FS_ERR_SHAPE;         // the candidates are the draw: nothing to cut
+    if (flags & ~(uint32_t)FS_FLAG_EXACT_LOG) return FS_ERR_UNSUPPORTED;
+    if (B == 0) return FS_OK;
+    if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
+    if (!aligned(temperature, 4) || !aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(topk_val, 4) ||
+        !aligned(topk_idx, 4) || !aligned(n_kept, 4) || !aligned(row_seeds, 8))
+        return FS_ERR_ALIGN;
+    return FS_OK;
+}
+
+}  // namespace
+
+size_t flash_sample_topk_workspace_bytes(int B, int V, int k)
+{
+    if (B <= 0 || V <= 0 || k < 1 || k > FS_TOPK_MAX_K) return 0;
+    const size_t fused = carve_topk(nullptr, B, V, k, true).bytes, unfused = carve_topk(nullptr, B, V, k, false).bytes;
+    return fused > unfused ? fused : unfused;
+}
+
+fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int V,
+                            const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                            int64_t row_offset, int32_t vocab_offset, int k, float top_p, int mode,
+                            int32_t* out_idx, float* out_val, float* topk_val, int32_t* topk_idx, int32_t* n_kept,
+                            void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK) return s;
+    s = check_topk(B, k, top_p, mode, flags, temperature, out_idx, out_val, topk_val, topk_idx, n_kept, row_seeds);
+    if (s != FS_OK || B == 0) return s;
+    if (D % 64 != 0) return FS_ERR_UNSUPPORTED;      // the per-tile top-k epilogue exists for whole K steps only
+    const TopkWs ws = carve_topk(workspace, B, V, k, true);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < ws.bytes) return FS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int kt = k < kVocabTile ? k : kVocabTile;
+    Stage1Params p = make_params(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset, flags);
+    p.topk_val = ws.pair_val; p.topk_idx = ws.pair_idx; p.topk_k = kt; p.topk_mode = mode;
+    s = launch_stage1_topk(p, st);
+    if (s != FS_OK) return s;
+    const int n_cand = p.T * kt;
+    s = launch_topk_reduce(ws.pair_val, ws.pair_idx, B, n_cand, (int64_t)n_cand, 0, k, ws.tmp_val, ws.tmp_idx,
+                           ws.fin_val, ws.fin_idx, st);
+    if (s != FS_OK) return s;
+    return launch_topk_finish(ws.fin_val, ws.fin_idx, B, k, top_p, mode, seed, row_seeds, row_offset, epi_bits(flags),
+                              out_idx, out_val, topk_val, topk_idx, n_kept, st);
+}
+
+fs_status flash_sample_topk_unfused(const void* hidden, const void* W, int B, int D, int V,
+                                    const float* temperature, uint64_t seed, const uint64_t* row_seeds,
+                                    int64_t row_offset, int32_t vocab_offset, int k, float top_p, int mode,
+                                    float* logits, int32_t* out_idx, float* out_val, float* topk_val,
+                                    int32_t* topk_idx, int32_t* n_kept,
+                                    void* workspace, size_t workspace_bytes_given, void* stream, uint32_t flags)
+{
+    fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
+    if (s != FS_OK) return s;
+    s = check_topk(B, k, top_p, mode, flags, temperature, out_idx, out_val, topk_val, topk_idx, n_kept, row_seeds);
+    if (s != FS_OK || B == 0) return s;
+    if (!logits) return FS_ERR_NULL;
+    if (!aligned(logits, 16)) return FS_ERR_ALIGN;
+    if (B > 65535) return FS_ERR_SHAPE;
+    const TopkWs ws = carve_topk(workspace, B, V, k, false);
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < ws.bytes) return FS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = flash_lm_head_logits(hidden, W, B, D, V, logits, stream, FS_FLAG_NONE);
+    if (s != FS_OK) return s;
+    s = launch_keys_from_logits(logits, B, V, temperature, seed, row_seeds, row_offset, vocab_offset, mode, epi_bits(flags), st);
+    if (s != FS_OK) return s;
+    s = launch_topk_reduce(logits, nullptr, B, V, (int64_t)V, vocab_offset, k, ws.tmp_val, ws.tmp_idx, ws.fin_val, ws.fin_idx, st);
+    if (s != FS_OK) return s;
+    return launch_topk_finish(ws.fin_val, ws.fin_idx, B, k, top_p, mode, seed, row_seeds, row_offset, epi_bits(flags),
+                              out_idx, out_val, topk_val, topk_idx, n_kept, st);
+}
+
 // ---- include/flash_sample_measure.h
 
 int flash_measure_kernel_choice(int B, int D, int V, int compute_units)

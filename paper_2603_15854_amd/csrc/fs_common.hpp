@@ -37,6 +37,12 @@ struct Stage1Params {
     const float* w_scale = nullptr;   // [V] fp32 per-row scale of the logits, or nullptr (= 1)
     // epilogue mode bits (FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG of the C ABI)
     uint32_t epi_flags = 0;
+    // per-tile top-k candidates (kernels instantiated with TOPK = true only): the topk_k best
+    // (key, id) pairs of every (row, 128-id tile), sorted, at [(b T + t) topk_k + j]
+    float* topk_val = nullptr;
+    int32_t* topk_idx = nullptr;
+    int topk_k = 0;
+    int topk_mode = 0;                // 0: key = y / tau; 1: key = y / tau + Gumbel noise
 };
 
 constexpr uint32_t kEpiGreedy = 0x1u;     // no noise: the candidate is the arg max of the transformed logits

@@ -68,6 +68,16 @@ fs_status launch_stage1_tiled_full(const Stage1Params& p, int shape, hipStream_t
 fs_status launch_stage1_dma(const Stage1Params& p, bool full, hipStream_t st);
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
+// truncated supports (fs_topk.hip)
+fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st);
+int topk_chunks(int B, int N);
+fs_status launch_keys_from_logits(float* logits, int B, int V, const float* tau, uint64_t seed, const uint64_t* row_seeds,
+                                  int64_t row_offset, int32_t vocab_offset, int mode, uint32_t epi_flags, hipStream_t st);
+fs_status launch_topk_reduce(const float* vals, const int32_t* ids, int B, int N, int64_t row_stride, int32_t id_base,
+                             int k, float* tmp_val, int32_t* tmp_idx, float* fin_val, int32_t* fin_idx, hipStream_t st);
+fs_status launch_topk_finish(const float* fin_val, const int32_t* fin_idx, int B, int k, float top_p, int mode, uint64_t seed,
+                             const uint64_t* row_seeds, int64_t row_offset, uint32_t epi_flags, int32_t* out_idx,
+                             float* out_val, float* topk_val, int32_t* topk_idx, int32_t* n_kept, hipStream_t st);
 fs_status launch_mxfp4_decode(const uint32_t* codes, const uint8_t* scales, int n8, float* out, hipStream_t st);
 
 }  // namespace fs

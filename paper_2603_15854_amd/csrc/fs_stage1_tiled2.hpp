@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "fs_common.hpp"
+#include "fs_topk_common.hpp"   // wave_sort128_desc
 
 namespace fs {
 
@@ -82,10 +83,15 @@ struct Tiled2Cfg {
 // KRAG: D need not be a multiple of the K step (the chunks of the last step that lie past D are
 // zeroed when parked).  The zeroing selects cost registers and time in the main loop (256 x 128:
 // 202 -> 158 VGPRs and -5 % time without them), so whole-step hidden sizes get KRAG = false.
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true>
+// TOPK: instead of one candidate per (row, 128-id tile) the epilogue writes the tile's p.topk_k best
+// (key, id) pairs, sorted (Section "Top-k, Nucleus Sampling, and Masking": "each tile computes top-k
+// candidates locally").  The keys of the workgroup tile are staged in LDS as [BT][VT + 4] floats and
+// every (row, candidate tile) unit is sorted by one wave (wave_sort128_desc).
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, bool TOPK = false>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
+    static_assert(!TOPK || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
     static_assert(!WCODES || WB == 1, "codes in LDS only for one-byte W elements");
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
     constexpr int KS = WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
@@ -277,6 +283,52 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     int base = 0;
     for (; base + 2 * GS <= nk; base += 2 * GS) body(base, std::false_type{});
     if (base < nk) body(base, std::true_type{});
+
+    if constexpr (TOPK) {
+        // the last K step ended with a barrier: the tile buffers are free
+        constexpr int KSTRIDE = VT + 4;                   // floats per batch row of the key array
+        float* keys = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const int bl = wn * (16 * CB) + j * 16 + n;
+            const int b = b0 + bl;
+            const int bc = b < B ? b : B - 1;
+            const float inv_tau = 1.0f / p.tau[bc];
+            const uint64_t sd = p.row_seeds ? p.row_seeds[bc] : p.seed;
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int vl = wm * (16 * RB) + i * 16 + 4 * g;
+                float gn[4] = {0.f, 0.f, 0.f, 0.f};
+                if (p.topk_mode == kTopkGumbel)
+                    gumbel4(sd, (uint32_t)(uint64_t)(p.row_offset + bc), (uint32_t)(p.vocab_offset + tile_row0 + vl), gn,
+                            (p.epi_flags & kEpiExactLog) != 0u);
+                f32x4 kq;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) kq[q] = key_sanitize(fmaf(acc[i][j][q], inv_tau, gn[q]));
+                *reinterpret_cast<f32x4*>(keys + bl * KSTRIDE + vl) = kq;
+            }
+        }
+        __syncthreads();
+        const int kt = p.topk_k;
+        for (int u = wave; u < BT * Cfg::kCandTiles; u += Cfg::kWaves) {     // unit = (batch row, candidate tile)
+            const int bl = u % BT, ct = u / BT;
+            const int b = b0 + bl;
+            const int ctile = tile * Cfg::kCandTiles + ct;
+            if (b >= B || ctile >= T) continue;                              // wave-uniform
+            const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
+            float v0 = e0 < V ? keys[bl * KSTRIDE + ct * kVocabTile + lane] : -__builtin_inff();
+            float v1 = e1 < V ? keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane] : -__builtin_inff();
+            int i0 = e0 < V ? p.vocab_offset + e0 : -1;
+            int i1 = e1 < V ? p.vocab_offset + e1 : -1;
+            wave_sort128_desc(v0, i0, v1, i1, lane);
+            if (lane < kt) {
+                const size_t o = ((size_t)b * T + ctile) * (size_t)kt + lane;
+                p.topk_val[o] = v0;
+                p.topk_idx[o] = i0;
+            }
+        }
+        return;
+    }
 
     // epilogue: acc[i][j][q] = logit of vocabulary row tile_row0 + wm*16*RB + 16 i + 4 g + q,
     // batch row b0 + wn*16*CB + 16 j + n

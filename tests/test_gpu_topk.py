@@ -1,0 +1,215 @@
+"""GPU parity of the truncated-support path (flash_sample_topk, fused and over stored logits) against
+the oracle's fso_sample_topk on the same seeded inputs.
+
+What is unique is compared exactly: the sorted candidate ids and the drawn id.  Where fp32 and fp64 may
+order two keys differently the rule of the main path applies: two keys closer than
+1e-3 (1 + |key|) may swap, a candidate may differ from the oracle's only if its own oracle key is that
+close to the key it displaced, the nucleus cut may move only if a prefix mass is within 2e-3 of top_p,
+and such rows are counted and capped."""
+import numpy as np
+import pytest
+
+import fs_workloads as wl
+from tests.parity import to_device_bf16, to_device_seeds
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+TRUNC, GUMBEL = 0, 1
+
+
+@pytest.fixture(scope="module")
+def fs():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2603_15854_amd as fs
+    fs.lib()
+    return fs
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def run(fs, H, W, tau, k, p, mode, fused, Wd=None, **kw):
+    rs = kw.pop("row_seeds", None)
+    oi, ov, tv, ti, nk = fs.flash_sample_topk(to_device_bf16(H), to_device_bf16(W) if Wd is None else Wd, dev(tau, np.float32),
+                                              k, top_p=p, mode=mode, fused=fused, row_seeds=to_device_seeds(rs), **kw)
+    torch.cuda.synchronize()
+    return oi.cpu().numpy(), ov.cpu().numpy(), tv.cpu().numpy().astype(np.float64), ti.cpu().numpy(), nk.cpu().numpy()
+
+
+def judge_topk(orc, H, W, tau, k, p, mode, ref, got, *, seed=0, row_seeds=None, row_offset=0, vocab_offset=0):
+    """Returns (exact rows, rows that needed a near-tie allowance); raises on a failure."""
+    gi, gv, tv, ti, nk = got
+    B, V = H.shape[0], W.shape[0]
+    exact = near = 0
+    for b in range(B):
+        t = float(tau[b])
+        sd = int(row_seeds[b]) if row_seeds is not None else seed
+        row = row_offset + b
+
+        def okey(i):          # the oracle's key of a global id
+            y = orc.logit(H, W, b, i - vocab_offset) / t
+            return y + orc.gumbel(sd, row, i) if mode == GUMBEL else y
+
+        rk, ri = ref["top_key"][b], ref["top_id"][b]
+        m = min(k, V)
+        used_tie = False
+        assert np.all(ti[b, m:] == -1) and np.all(tv[b, m:] == -np.inf), (b, "padding")
+        for j in range(m):
+            tol = 1e-3 * (1.0 + abs(rk[j]))
+            vtol = 2e-3 / min(t, 1.0) + tol
+            assert abs(tv[b, j] - rk[j]) <= vtol, (b, j, "key value", tv[b, j], rk[j])
+            if ti[b, j] != ri[j]:
+                assert vocab_offset <= ti[b, j] < vocab_offset + V, (b, j, "id range", ti[b, j])
+                assert abs(okey(int(ti[b, j])) - rk[j]) < tol, (b, j, "candidate is not a near-tie", ti[b, j], ri[j])
+                used_tie = True
+        assert len(set(ti[b, :m].tolist())) == m, (b, "duplicate candidate")
+        if mode == GUMBEL:
+            assert nk[b] == m
+            assert gi[b] == ti[b, 0] and abs(gv[b] - tv[b, 0]) <= 1e-6 * (1 + abs(gv[b])), (b, "first element")
+        else:
+            q = np.exp(rk[:m] - rk[0])
+            cum = np.cumsum(q) / q.sum()
+
+            def cut(pp):
+                return m if pp >= 1.0 else (int(np.argmax(cum >= pp)) + 1 if np.any(cum >= pp) else m)
+
+            lo, hi = cut(max(p - 2e-3, 1e-9)), cut(min(p + 2e-3, 1.0)) if p < 1.0 else m
+            assert lo <= nk[b] <= hi, (b, "kept", nk[b], ref["n_kept"][b], lo, hi)
+            if nk[b] != ref["n_kept"][b]:
+                used_tie = True
+            kept = set(ti[b, :nk[b]].tolist())
+            assert int(gi[b]) in kept, (b, "drawn id outside the kept candidates")
+            s = orc.logit(H, W, b, int(gi[b]) - vocab_offset) / t + orc.gumbel(sd, row, int(gi[b]))
+            assert abs(gv[b] - s) <= 2e-3 / min(t, 1.0) + 1e-3 * (1 + abs(s)), (b, "value", gv[b], s)
+            if kept == set(ri[:ref["n_kept"][b]].tolist()) and gi[b] != ref["idx"][b]:
+                tol = 1e-3 * (1.0 + abs(ref["top1"][b]))
+                assert ref["top1"][b] - ref["top2"][b] < tol and ref["top1"][b] - s < tol, (b, "wrong draw", gi[b], ref["idx"][b])
+                used_tie = True
+        if used_tie:
+            near += 1
+        else:
+            assert gi[b] == ref["idx"][b], (b, gi[b], ref["idx"][b])
+            exact += 1
+    return exact, near
+
+
+CASES = [
+    # (B, D, V, k, top_p): ragged last tile, V < k, one tile, several batch tiles, every tile shape class
+    (5, 512, 1189, 8, 1.0), (5, 512, 1189, 50, 0.9), (16, 1024, 128 * 9 + 1, 64, 0.5), (1, 256, 4096, 1, 1.0),
+    (3, 64, 40, 64, 0.95), (2, 64, 127, 33, 0.8), (40, 1024, 1300, 20, 0.9), (64, 512, 700, 64, 1.0),
+    (100, 256, 640, 16, 0.7), (130, 2048, 515, 50, 0.9), (300, 256, 1000, 7, 0.6),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("mode", [TRUNC, GUMBEL])
+@pytest.mark.parametrize("fused", [True, False])
+def test_topk_matches_oracle(fs, orc, case, mode, fused):
+    B, D, V, k, p = case
+    p = 1.0 if mode == GUMBEL else p
+    print(f"topk case={case} mode={mode} fused={fused}", flush=True)
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=500 + B + V, w_row_scale=2.0)
+    tau = np.linspace(0.6, 1.5, B).astype(np.float32)
+    seeds = np.arange(B, dtype=np.uint64) * np.uint64(7) + np.uint64(3)
+    ref = orc.sample_topk(H, W, tau, k, top_p=p, mode=mode, row_seeds=seeds, row_offset=5, vocab_offset=256)
+    got = run(fs, H, W, tau, k, p, mode, fused, row_seeds=seeds, row_offset=5, vocab_offset=256)
+    exact, near = judge_topk(orc, H, W, tau, k, p, mode, ref, got, row_seeds=seeds, row_offset=5, vocab_offset=256)
+    assert near <= max(2, B // 10), (exact, near)
+
+
+def test_fused_and_unfused_agree_and_gumbel_first_is_the_plain_sample(fs, orc):
+    B, D, V, k = 8, 1024, 20000, 32
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=560)
+    tau = np.full(B, 0.9, dtype=np.float32)
+    f = run(fs, H, W, tau, k, 1.0, GUMBEL, True, seed=4)
+    u = run(fs, H, W, tau, k, 1.0, GUMBEL, False, seed=4)
+    assert (f[3] != u[3]).sum() <= 2                         # same ids up to fp32 summation order
+    # first element = the plain sampler's draw, bit for bit when the same kernel and tile shape form the logits
+    pi, pv = fs.flash_sample_ex(to_device_bf16(H), to_device_bf16(W), dev(tau, np.float32), seed=4,
+                                flags=fs.FS_VARIANT(fs.FS_VARIANT_TILED2) | fs.FS_TUNE_TILE_SHAPE(6))
+    torch.cuda.synchronize()
+    assert np.array_equal(pi.cpu().numpy(), f[0]) and np.array_equal(pv.cpu().numpy(), f[1])
+    # k = 1 truncation is greedy decoding: the arg max of the logits
+    t = run(fs, H, W, tau, 1, 1.0, TRUNC, True, seed=4)
+    g, _ = fs.flash_sample_ex(to_device_bf16(H), to_device_bf16(W), dev(tau, np.float32), seed=4, flags=fs.FS_FLAG_GREEDY)
+    torch.cuda.synchronize()
+    assert np.array_equal(t[0], g.cpu().numpy())
+
+
+def test_adversarial_orders_and_ties_in_the_selection(fs, orc):
+    # identical rows of W give exactly equal logits (ties by id); ascending logits defeat the threshold filter
+    B, D, V, k = 3, 64, 6000, 40
+    H, _ = wl.make_small(D=D, V=8, B=B, data_seed=570)
+    base = wl.make_small(D=D, V=50, B=1, data_seed=571)[1]
+    W = np.ascontiguousarray(base[np.arange(V) % 50])                       # 120 copies of 50 rows: massive ties
+    tau = np.ones(B, dtype=np.float32)
+    for fused in (True, False):
+        ref = orc.sample_topk(H, W, tau, k, top_p=0.9, mode=TRUNC, seed=2)
+        got = run(fs, H, W, tau, k, 0.9, TRUNC, fused, seed=2)
+        assert np.array_equal(got[3], ref["top_id"]), fused               # exact ties: lowest ids, exactly
+        assert np.array_equal(got[0], ref["idx"])
+    # logits that grow with the id: every block of the row passes the running threshold
+    Hs = np.zeros((1, D), dtype=np.uint16); Hs[0, 0] = 0x3F80                # hidden = e_0
+    Ws = np.zeros((V, D), dtype=np.uint16)
+    Ws[:, 0] = wl.f32_to_bf16_bits(np.linspace(-4.0, 4.0, V).astype(np.float32))
+    ref = orc.sample_topk(Hs, Ws, np.ones(1, np.float32), 64, mode=TRUNC, seed=1)
+    got = run(fs, Hs, Ws, np.ones(1, np.float32), 64, 1.0, TRUNC, False, seed=1)
+    assert np.array_equal(got[3], ref["top_id"]) and got[0][0] == ref["idx"][0]
+
+
+def test_topk_at_llama_shape_every_row(fs, orc):
+    w = wl.WORKLOADS["C2"]
+    Wb = wl.make_weights(w)
+    Wd = to_device_bf16(Wb)
+    B, k, p = 16, 50, 0.9
+    H = wl.make_hidden(w, B)
+    tau = np.linspace(0.7, 1.3, B).astype(np.float32)
+    seeds = wl.make_row_seeds(w, B)
+    for mode, pp in ((TRUNC, p), (GUMBEL, 1.0)):
+        ref = orc.sample_topk(H, Wb, tau, k, top_p=pp, mode=mode, row_seeds=seeds)
+        for fused in (True, False):
+            got = run(fs, H, Wb, tau, k, pp, mode, fused, Wd=Wd, row_seeds=seeds)
+            exact, near = judge_topk(orc, H, Wb, tau, k, pp, mode, ref, got, row_seeds=seeds)
+            print(f"[parity] top-k C2 B={B} k={k} p={pp} mode={mode} fused={fused}: exact={exact} near_tie={near}", flush=True)
+            assert near <= 2
+
+
+def test_truncated_draw_follows_the_renormalised_softmax_on_the_gpu(fs, orc):
+    from scipy import stats
+    D, V, k, p, tau, n = 64, 512, 8, 0.8, 0.9, 40_000
+    H1, W = wl.make_small(D=D, V=V, B=1, data_seed=95, w_row_scale=2.0)
+    z = orc.logits(H1, W)[0] / float(np.float32(tau))
+    order = np.lexsort((np.arange(V), -z))[:k]
+    q = np.exp(z[order] - z[order].max()); q /= q.sum()
+    nkeep = int(np.argmax(np.cumsum(q) >= p)) + 1
+    target = np.zeros(V); target[order[:nkeep]] = q[:nkeep] / q[:nkeep].sum()
+    got = run(fs, np.repeat(H1, n, axis=0), W, np.full(n, tau, np.float32), k, p, TRUNC, True, seed=31)
+    counts = np.bincount(got[0], minlength=V)
+    assert counts[target == 0].sum() == 0
+    keep = target > 0
+    chi2 = ((counts[keep] - target[keep] * n) ** 2 / (target[keep] * n)).sum()
+    assert chi2 < stats.chi2.ppf(0.999, keep.sum() - 1), chi2
+
+
+def test_topk_rejects_bad_arguments(fs):
+    H = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((300, 256), dtype=torch.bfloat16, device="cuda")
+    tau = torch.ones(4, device="cuda")
+    for kw, status in ((dict(k=0), fs.FS_ERR_SHAPE), (dict(k=65), fs.FS_ERR_SHAPE), (dict(k=8, top_p=0.0), fs.FS_ERR_SHAPE),
+                       (dict(k=8, top_p=1.5), fs.FS_ERR_SHAPE), (dict(k=8, top_p=0.9, mode=GUMBEL), fs.FS_ERR_SHAPE),
+                       (dict(k=8, mode=2), fs.FS_ERR_SHAPE), (dict(k=8, flags=fs.FS_FLAG_GREEDY), fs.FS_ERR_UNSUPPORTED)):
+        if kw.get("k", 1) < 1:
+            continue      # the binding cannot size its outputs for k = 0; the C side is covered by the host test
+        with pytest.raises(fs.FlashSampleError) as e:
+            fs.flash_sample_topk(H, W, tau, **kw)
+        assert e.value.status == status, kw
+    H2 = torch.zeros((4, 40), dtype=torch.bfloat16, device="cuda")
+    W2 = torch.zeros((300, 40), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fs.FlashSampleError) as e:           # fused form: whole K steps only
+        fs.flash_sample_topk(H2, W2, tau, 8)
+    assert e.value.status == fs.FS_ERR_UNSUPPORTED
+    fs.flash_sample_topk(H2, W2, tau, 8, fused=False)       # the form over stored logits takes any D
+    torch.cuda.synchronize()
