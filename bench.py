@@ -312,6 +312,36 @@ def main() -> int:
                     "the paper's column is its sampling share of the fused kernel on its own GPU (context)",
             "rows": share}
 
+        # -------------------------------------------------------------- top-k / top-p: fused against stored logits
+        rows_k = []
+        for Bs, kk in ((16, 50), (64, 50), (256, 50), (64, 8), (64, 64)):
+            leg = Leg(w, Wd, Bs, want_logits=True)
+            wsk = torch.empty(fs.flash_sample_topk_workspace_bytes(Bs, V, kk), dtype=torch.uint8, device="cuda")
+            tv = torch.empty((Bs, kk), dtype=torch.float32, device="cuda")
+            ti = torch.empty((Bs, kk), dtype=torch.int32, device="cuda")
+            nk = torch.empty(Bs, dtype=torch.int32, device="cuda")
+
+            def topk(fused, leg=leg, kk=kk, wsk=wsk, tv=tv, ti=ti, nk=nk):
+                fs.flash_sample_topk(leg.Hd, leg.Wd, leg.tau, kk, top_p=0.9, mode=fs.FS_TOPK_TRUNCATE, seed=w.seed,
+                                     row_seeds=leg.seeds, fused=fused, logits=leg.lg, out_idx=leg.oi, out_val=leg.ov,
+                                     topk_val=tv, topk_idx=ti, n_kept=nk, workspace=wsk, stream=stream)
+
+            plain = per_call_us(leg.fused)
+            f = per_call_us(lambda: topk(True))
+            u = per_call_us(lambda: topk(False))
+            rows_k.append({"B": Bs, "k": kk, "top_p": 0.9, "plain_sample_us": plain["median_us"],
+                           "fused_topk_us": f["median_us"], "fused_topk_min_us": f["min_us"], "fused_topk_max_us": f["max_us"],
+                           "stored_logits_topk_us": u["median_us"], "stored_logits_topk_min_us": u["min_us"],
+                           "stored_logits_topk_max_us": u["max_us"],
+                           "fused_over_stored_speedup": round(u["median_us"] / f["median_us"], 4),
+                           "fused_topk_over_plain": round(f["median_us"] / plain["median_us"], 4)})
+            del leg, wsk
+        out["top_k"] = {
+            "what": "top-k truncation + nucleus on the k candidates + Gumbel-max over the kept ids: the fused form "
+                    "(per-tile top-k in the stage-1 epilogue, no logits in HBM) against the form over stored logits "
+                    "(logits-store GEMM, then keys, selection and draw kernels); plain_sample is the untruncated draw",
+            "rows": rows_k}
+
         # -------------------------------------------------------------- FP8 / MXFP4 weights (same shape)
         codes, wscale = wl.quantize_e4m3(Wb)
         W8d = torch.from_numpy(codes).cuda()

@@ -388,20 +388,22 @@ def flash_sample_topk_workspace_bytes(B: int, V: int, k: int) -> int:
 
 def flash_sample_topk(hidden, W, temperature, k: int, top_p: float = 1.0, mode: int = FS_TOPK_TRUNCATE, seed: int = 0,
                       row_seeds=None, row_offset: int = 0, vocab_offset: int = 0, fused: bool = True, logits=None,
-                      out_idx=None, out_val=None, workspace=None, stream=None, flags: int = 0):
+                      out_idx=None, out_val=None, topk_val=None, topk_idx=None, n_kept=None, workspace=None, stream=None,
+                      flags: int = 0):
     """Top-k / nucleus draw (FS_TOPK_TRUNCATE) or Gumbel-top-k (FS_TOPK_GUMBEL).  fused=False runs the
     comparison form over stored logits.  Returns (out_idx, out_val, topk_val [B,k], topk_idx [B,k], n_kept [B])."""
     import torch
     B, D, V = _shapes(hidden, W)
     out_idx, out_val = _outputs(B, hidden.device, out_idx, out_val)
-    tv = torch.empty((B, k), dtype=torch.float32, device=hidden.device)
-    ti = torch.empty((B, k), dtype=torch.int32, device=hidden.device)
-    nk = torch.empty(B, dtype=torch.int32, device=hidden.device)
+    tv = torch.empty((B, k), dtype=torch.float32, device=hidden.device) if topk_val is None else topk_val
+    ti = torch.empty((B, k), dtype=torch.int32, device=hidden.device) if topk_idx is None else topk_idx
+    nk = torch.empty(B, dtype=torch.int32, device=hidden.device) if n_kept is None else n_kept
     workspace, ws_bytes = _scratch(flash_sample_topk_workspace_bytes(B, V, k), hidden.device, workspace, stream)
     common = (_ptr(hidden), _ptr(W), B, D, V, _f32(temperature, B, "temperature"), int(seed), _seeds(row_seeds, B),
               int(row_offset), int(vocab_offset), int(k), float(top_p), int(mode))
     tail = (_ptr(out_idx), _ptr(out_val), _ptr(tv), _ptr(ti), _ptr(nk), _ptr(workspace), ws_bytes, _stream_ptr(stream),
             int(flags))
+    tail = (tail[0], tail[1], _f32(tv, B * k, "topk_val"), _i32(ti, B * k, "topk_idx"), _i32(nk, B, "n_kept")) + tail[5:]
     if fused:
         st = lib().flash_sample_topk(*common, *tail)
         _check(st, "flash_sample_topk")

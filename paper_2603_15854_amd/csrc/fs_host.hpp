@@ -12,6 +12,7 @@
 
 #include "flash_sample.h"
 #include "fs_common.hpp"
+#include "fs_topk_common.hpp"
 
 namespace fs {
 
@@ -69,15 +70,19 @@ fs_status launch_stage1_dma(const Stage1Params& p, bool full, hipStream_t st);
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
 // truncated supports (fs_topk.hip)
-fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st);
-int topk_chunks(int B, int N);
-fs_status launch_keys_from_logits(float* logits, int B, int V, const float* tau, uint64_t seed, const uint64_t* row_seeds,
-                                  int64_t row_offset, int32_t vocab_offset, int mode, uint32_t epi_flags, hipStream_t st);
-fs_status launch_topk_reduce(const float* vals, const int32_t* ids, int B, int N, int64_t row_stride, int32_t id_base,
-                             int k, float* tmp_val, int32_t* tmp_idx, float* fin_val, int32_t* fin_idx, hipStream_t st);
-fs_status launch_topk_finish(const float* fin_val, const int32_t* fin_idx, int B, int k, float top_p, int mode, uint64_t seed,
-                             const uint64_t* row_seeds, int64_t row_offset, uint32_t epi_flags, int32_t* out_idx,
-                             float* out_val, float* topk_val, int32_t* topk_idx, int32_t* n_kept, hipStream_t st);
+fs_status launch_stage1_topk(const Stage1Params& p, int pass, hipStream_t st);
+struct TopkPlan {                 // selection levels for rows of N candidates (topk_plan)
+    static constexpr int kMaxLevels = 4;
+    int levels;
+    int chunks[kMaxLevels];       // chunks per row at each level; 1 at the last
+    int n[kMaxLevels];            // candidates per row at each level
+    size_t buf_words[2];          // 64-bit words of the two intermediate buffers
+};
+TopkPlan topk_plan(int B, int N, int k);
+// keys: how stored logits become keys (input = fp32 [B, N] logits), or null (input = packed candidates);
+// fix: the fused path's check for tiles that need all their candidates, or null
+fs_status launch_topk_reduce(const void* in, const TopkKeys* keys, int B, int N, int64_t row_stride, int32_t id_base, int k,
+                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkFix* fix, hipStream_t st);
 fs_status launch_mxfp4_decode(const uint32_t* codes, const uint8_t* scales, int n8, float* out, hipStream_t st);
 
 }  // namespace fs

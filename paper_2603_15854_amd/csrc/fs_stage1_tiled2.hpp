@@ -83,15 +83,18 @@ struct Tiled2Cfg {
 // KRAG: D need not be a multiple of the K step (the chunks of the last step that lie past D are
 // zeroed when parked).  The zeroing selects cost registers and time in the main loop (256 x 128:
 // 202 -> 158 VGPRs and -5 % time without them), so whole-step hidden sizes get KRAG = false.
-// TOPK: instead of one candidate per (row, 128-id tile) the epilogue writes the tile's p.topk_k best
-// (key, id) pairs, sorted (Section "Top-k, Nucleus Sampling, and Masking": "each tile computes top-k
-// candidates locally").  The keys of the workgroup tile are staged in LDS as [BT][VT + 4] floats and
-// every (row, candidate tile) unit is sorted by one wave (wave_sort128_desc).
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, bool TOPK = false>
+// TOPK (Section "Top-k, Nucleus Sampling, and Masking": per-tile candidates): instead of one
+// candidate per (row, 128-id tile) the epilogue writes several, sorted and packed.  The keys of the
+// workgroup tile are staged in LDS as [BT][VT + 4] floats and one wave handles a (row, candidate
+// tile) unit.  TOPK = 1: the p.topk_k <= 8 best of every unit (wave_top_m).  TOPK = 2: only the tiles
+// flagged in p.tile_flag run (the other workgroups leave at once); the units listed in p.fix_tiles
+// are sorted completely (wave_sort128_desc) and their p.topk_kfull best written.  Both passes use
+// the same tile shape and K order, so the keys of the second pass equal those of the first bit for bit.
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, int TOPK = 0>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
-    static_assert(!TOPK || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
+    static_assert(TOPK == 0 || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
     static_assert(!WCODES || WB == 1, "codes in LDS only for one-byte W elements");
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
     constexpr int KS = WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
@@ -127,6 +130,18 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int tile = group * 8 + (rem & 7);      // macro tile of VT vocabulary rows
     const int bt = rem >> 3;
     if (tile * VT >= V) return;                  // whole workgroup leaves: no barrier is skipped
+    if constexpr (TOPK == 2) {
+        bool any = false;
+        for (int ct = 0; ct < Cfg::kCandTiles; ++ct) {
+            const int ctile = tile * Cfg::kCandTiles + ct;
+            if (ctile < p.T && p.tile_flag[ctile] != 0) any = true;
+        }
+        if (!any) return;                        // uniform over the workgroup
+    }
+    if constexpr (TOPK == 1) {
+        if (bt == 0 && p.tile_flag && (int)threadIdx.x < Cfg::kCandTiles && tile * Cfg::kCandTiles + (int)threadIdx.x < p.T)
+            p.tile_flag[tile * Cfg::kCandTiles + (int)threadIdx.x] = 0;
+    }
     const int b0 = bt * BT;
     const int tile_row0 = tile * VT;
 
@@ -284,7 +299,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     for (; base + 2 * GS <= nk; base += 2 * GS) body(base, std::false_type{});
     if (base < nk) body(base, std::true_type{});
 
-    if constexpr (TOPK) {
+    if constexpr (TOPK != 0) {
         // the last K step ended with a barrier: the tile buffers are free
         constexpr int KSTRIDE = VT + 4;                   // floats per batch row of the key array
         float* keys = reinterpret_cast<float*>(smem);
@@ -309,22 +324,29 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             }
         }
         __syncthreads();
-        const int kt = p.topk_k;
         for (int u = wave; u < BT * Cfg::kCandTiles; u += Cfg::kWaves) {     // unit = (batch row, candidate tile)
             const int bl = u % BT, ct = u / BT;
             const int b = b0 + bl;
             const int ctile = tile * Cfg::kCandTiles + ct;
             if (b >= B || ctile >= T) continue;                              // wave-uniform
             const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-            float v0 = e0 < V ? keys[bl * KSTRIDE + ct * kVocabTile + lane] : -__builtin_inff();
-            float v1 = e1 < V ? keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane] : -__builtin_inff();
-            int i0 = e0 < V ? p.vocab_offset + e0 : -1;
-            int i1 = e1 < V ? p.vocab_offset + e1 : -1;
-            wave_sort128_desc(v0, i0, v1, i1, lane);
-            if (lane < kt) {
-                const size_t o = ((size_t)b * T + ctile) * (size_t)kt + lane;
-                p.topk_val[o] = v0;
-                p.topk_idx[o] = i0;
+            const float v0 = keys[bl * KSTRIDE + ct * kVocabTile + lane];
+            const float v1 = keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane];
+            if constexpr (TOPK == 1) {
+                const int kt = p.topk_k;
+                const uint64_t r = wave_top_m(v0, v1, e0 < V, e1 < V, p.vocab_offset + tile_row0 + ct * kVocabTile, kt, lane);
+                if (lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = r;
+            } else {
+                if (p.tile_flag[ctile] == 0) continue;
+                const int nf = p.n_fix[b];
+                for (int sl = 0; sl < nf; ++sl) {
+                    if (p.fix_tiles[b * kTopkFixMax + sl] != ctile) continue;
+                    uint64_t a0 = e0 < V ? topk_pack(v0, p.vocab_offset + e0) : kTopkPad;
+                    uint64_t a1 = e1 < V ? topk_pack(v1, p.vocab_offset + e1) : kTopkPad;
+                    wave_sort128_desc(a0, a1, lane);
+                    const int kf = p.topk_kfull;
+                    if (lane < kf) p.rowbuf[(size_t)b * p.rowbuf_stride + (size_t)kf * (1 + sl) + lane] = a0;
+                }
             }
         }
         return;

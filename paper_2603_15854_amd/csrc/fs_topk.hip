@@ -5,60 +5,81 @@
 
 namespace fs {
 
-// Stage 1 with the per-tile top-k epilogue.  Three tile shapes (by batch size), whole K steps only.
-fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st)
+// Stage 1 with the per-tile candidate epilogue, first (pass = 1) or second (pass = 2) pass.  Three
+// tile shapes (by batch size), whole K steps only; both passes of a call take the same shape.
+fs_status launch_stage1_topk(const Stage1Params& p, int pass, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
-    if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
-    if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
-    return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);                   // 256 x 128, batch tiles XCD-paired
-}
-
-// Chunks a row of N candidates is cut into for the first selection pass: enough workgroups to fill
-// the device at small B, never chunks shorter than 2048 elements, at most 64.
-int topk_chunks(int B, int N)
-{
-    int want = (512 + B - 1) / B;
-    const int cap = (N + 2047) / 2048;
-    want = want < cap ? want : cap;
-    want = want < 64 ? want : 64;
-    return want < 1 ? 1 : want;
-}
-
-fs_status launch_keys_from_logits(float* logits, int B, int V, const float* tau, uint64_t seed, const uint64_t* row_seeds,
-                                  int64_t row_offset, int32_t vocab_offset, int mode, uint32_t epi_flags, hipStream_t st)
-{
-    return launch(keys_from_logits_kernel, dim3((V + 1023) / 1024, B), dim3(256), 0, st, logits, V, tau, seed, row_seeds,
-                  row_offset, vocab_offset, mode, epi_flags);
-}
-
-// The k best of every row of [B, N] candidates ((vals, ids) pairs, or keys with id = id_base +
-// position when ids is null): chunks first, then the chunks' results.  tmp_* hold B * chunks * k
-// pairs, fin_* B * k.
-fs_status launch_topk_reduce(const float* vals, const int32_t* ids, int B, int N, int64_t row_stride, int32_t id_base,
-                             int k, float* tmp_val, int32_t* tmp_idx, float* fin_val, int32_t* fin_idx, hipStream_t st)
-{
-    const int chunks = topk_chunks(B, N);
-    const int chunk_len = (N + chunks - 1) / chunks;
-    fs_status s;
-    if (chunks == 1) {
-        if (ids) return launch(topk_select_kernel<true>, dim3(1, B), dim3(256), 0, st, vals, ids, row_stride, N, id_base, chunk_len, k, fin_val, fin_idx);
-        return launch(topk_select_kernel<false>, dim3(1, B), dim3(256), 0, st, vals, ids, row_stride, N, id_base, chunk_len, k, fin_val, fin_idx);
+    if (pass == 1) {
+        if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, 1>(p, st);   // 512 x 32
+        if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, 1>(p, st);   // 512 x 64
+        return launch_tiled2<Shape3, false, 2, false, false, true, 1>(p, st);                   // 256 x 128, batch tiles XCD-paired
     }
-    if (ids) s = launch(topk_select_kernel<true>, dim3(chunks, B), dim3(256), 0, st, vals, ids, row_stride, N, id_base, chunk_len, k, tmp_val, tmp_idx);
-    else s = launch(topk_select_kernel<false>, dim3(chunks, B), dim3(256), 0, st, vals, ids, row_stride, N, id_base, chunk_len, k, tmp_val, tmp_idx);
-    if (s != FS_OK) return s;
-    const int n2 = chunks * k;
-    return launch(topk_select_kernel<true>, dim3(1, B), dim3(256), 0, st, (const float*)tmp_val, (const int32_t*)tmp_idx,
-                  (int64_t)n2, n2, 0, n2, k, fin_val, fin_idx);
+    if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, 2>(p, st);
+    if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, 2>(p, st);
+    return launch_tiled2<Shape3, false, 2, false, false, true, 2>(p, st);
 }
 
-fs_status launch_topk_finish(const float* fin_val, const int32_t* fin_idx, int B, int k, float top_p, int mode, uint64_t seed,
-                             const uint64_t* row_seeds, int64_t row_offset, uint32_t epi_flags, int32_t* out_idx,
-                             float* out_val, float* topk_val, int32_t* topk_idx, int32_t* n_kept, hipStream_t st)
+// Selection levels for rows of N candidates: every level cuts a row into chunks of at most kSelChunk
+// candidates and leaves k per chunk; the last level has one chunk.  The first level uses more (shorter)
+// chunks than it must when B is small, to fill the device, as long as the next level still fits one
+// workgroup.
+TopkPlan topk_plan(int B, int N, int k)
 {
-    return launch(topk_finish_kernel, dim3(B), dim3(64), 0, st, fin_val, fin_idx, k, top_p, mode, seed, row_seeds,
-                  row_offset, epi_flags, out_idx, out_val, topk_val, topk_idx, n_kept);
+    TopkPlan pl = {};
+    int64_t n = N;
+    for (int lvl = 0; lvl < TopkPlan::kMaxLevels; ++lvl) {
+        int64_t c = (n + kSelChunk - 1) / kSelChunk;
+        if (c > 1 && lvl == 0) {
+            const int64_t one_more = kSelChunk / k;                  // chunks the next level takes in one workgroup
+            int64_t want = (512 + B - 1) / B;
+            const int64_t cap = (n + 1023) / 1024;
+            want = want < cap ? want : cap;
+            want = want < one_more ? want : one_more;
+            c = c > want ? c : want;
+        }
+        pl.chunks[lvl] = (int)c;
+        pl.n[lvl] = (int)n;
+        pl.levels = lvl + 1;
+        if (c == 1) break;
+        n = c * k;
+    }
+    // outputs of levels 0, 2 go to the first buffer, of level 1 to the second (the last level writes none)
+    pl.buf_words[0] = pl.levels > 1 ? (size_t)B * pl.chunks[0] * k : 0;
+    pl.buf_words[1] = pl.levels > 2 ? (size_t)B * pl.chunks[1] * k : 0;
+    return pl;
+}
+
+// The k best of every row of [B, N] candidates, then the nucleus rule and the draw.  buf0 / buf1:
+// topk_plan's buffers.
+fs_status launch_topk_reduce(const void* in, const TopkKeys* keys, int B, int N, int64_t row_stride, int32_t id_base, int k,
+                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkFix* fix, hipStream_t st)
+{
+    const TopkPlan pl = topk_plan(B, N, k);
+    if (pl.chunks[pl.levels - 1] != 1 || B > 65535) return FS_ERR_SHAPE;
+    const TopkKeys kp = keys ? *keys : TopkKeys{};
+    const TopkFix none = {};
+    const void* src = in;
+    for (int lvl = 0; lvl < pl.levels; ++lvl) {
+        const int c = pl.chunks[lvl], n = pl.n[lvl];
+        int chunk_len = (n + c - 1) / c;
+        chunk_len = (chunk_len + 3) & ~3;                  // chunks of key rows start at whole groups of four ids
+        const bool last = lvl == pl.levels - 1;
+        uint64_t* dst = last ? nullptr : (lvl & 1) ? buf1 : buf0;
+        const bool from_keys = keys && lvl == 0;
+        const int64_t stride = lvl == 0 ? row_stride : (int64_t)n;
+        const int32_t base = lvl == 0 ? id_base : 0;
+        const TopkFix fx = last && fix ? *fix : none;
+        fs_status s;
+        const dim3 grid(c, B), block(256);
+        if (from_keys && last) s = launch(topk_select_kernel<true, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
+        else if (from_keys) s = launch(topk_select_kernel<true, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
+        else if (last) s = launch(topk_select_kernel<false, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
+        else s = launch(topk_select_kernel<false, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
+        if (s != FS_OK) return s;
+        src = dst;
+    }
+    return FS_OK;
 }
 
 }  // namespace fs

@@ -1,20 +1,15 @@
-// Truncated supports (Section "Top-k, Nucleus Sampling, and Masking"): per-tile top-k candidates,
-// the reduction of candidates to a global top-k, the nucleus rule on the k candidates and the draw.
+// Truncated supports (Section "Top-k, Nucleus Sampling, and Masking"): the reduction of candidates to
+// a global top-k, the nucleus rule on the k candidates and the draw.
 //
-// Order used everywhere: larger key first; equal keys: lower id first; padding is (-inf, -1) and
-// sorts last (ids compare as unsigned, so -1 is the largest); NaN keys are turned into -inf when
-// a key is formed.  Two kinds of key, chosen by the caller:
+// Two kinds of key, chosen by the caller:
 //   truncation    key = z = y / tau: the k candidates are the support the draw is cut to;
 //   Gumbel-top-k  key = s = z + g:   the k candidates, in order, ARE the draw (k ids without
 //                 replacement); the first one is the plain Gumbel-max sample.
 //
 // Pieces:
-//   wave_sort128_desc    a wave sorts 128 (key, id) pairs held two per lane (bitonic network over
-//                        lanes by shuffles): the per-tile top-k of the fused stage-1 epilogue
-//   keys_from_logits     the unfused path: stored logits -> keys, in place
-//   topk_select_kernel   the k best of a chunk of a row, from pairs or from a key row; run once
-//                        over chunks (many workgroups per row) and once over the chunks' results
-//   topk_finish_kernel   nucleus rule on the k sorted candidates + Gumbel-max over the kept ones
+//   topk_select_kernel   the k best of a chunk of a row, from a key row or from packed candidates;
+//                        run over chunks (many workgroups per row), then over the chunks' results;
+//                        the last level also applies the nucleus rule and draws (topk_finish)
 #pragma once
 
 #include "fs_common.hpp"
@@ -45,118 +40,23 @@ keys_from_logits_kernel(float* __restrict__ logits, int V, const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// The k best pairs of one chunk of one row.  grid = (chunks, B).  Input: PAIRS ? (vals, ids)[b, 0..N)
-// : keys[b, 0..N) with id = id_base + position.  Output: out[(b * chunks + c) * k + j], j < k, sorted,
-// padded with (-inf, -1).
-//
-// The workgroup keeps the best k seen so far, sorted, at the head of an LDS buffer of 2048 pairs, and
-// the k-th of them as a threshold.  Elements are read 1024 at a time; those that come before the
-// threshold are appended behind the head; when the buffer could overflow (or at the end) the whole
-// buffer is sorted (bitonic, in LDS), the head is the new top k, and the threshold moves up.  After
-// the first few blocks hardly anything passes the threshold, so a row costs little more than reading
-// it; an adversarial (ascending) row sorts once per 1024 elements.  The result does not depend on
-// the order in which the appends land: the sort is a total order on (key, id).
-constexpr int kSelBuf = 2048;
-constexpr int kSelStep = 1024;
-
-__device__ __forceinline__ void lds_sort_desc(float* sv, int* si, int n, int tid)   // n: power of two <= kSelBuf
-{
-    for (int size = 2; size <= n; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int t = tid; t < (n >> 1); t += 256) {
-                const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
-                const int hi = lo | stride;
-                const bool up = (lo & size) == 0 || size == n;      // the last merge sorts the whole array descending
-                const float av = sv[lo], bv = sv[hi];
-                const int ai = si[lo], bi = si[hi];
-                const bool a_first = pair_before(av, ai, bv, bi);
-                if (a_first != up) { sv[lo] = bv; si[lo] = bi; sv[hi] = av; si[hi] = ai; }
-            }
-            __syncthreads();
-        }
-    }
-}
-
-template <bool PAIRS>
-__global__ void __launch_bounds__(256)
-topk_select_kernel(const float* __restrict__ vals, const int32_t* __restrict__ ids, int64_t row_stride, int N,
-                   int32_t id_base, int chunk_len, int k, float* __restrict__ out_val, int32_t* __restrict__ out_idx)
-{
-    __shared__ float sv[kSelBuf];
-    __shared__ int si[kSelBuf];
-    __shared__ int s_count;
-    const int tid = threadIdx.x;
-    const int b = blockIdx.y, c = blockIdx.x;
-    const float* rv = vals + (size_t)b * row_stride;
-    const int32_t* ri = PAIRS ? ids + (size_t)b * row_stride : nullptr;
-    const int begin = c * chunk_len;
-    int end = begin + chunk_len;
-    end = end < N ? end : N;
-
-    for (int t = tid; t < kSelBuf; t += 256) { sv[t] = -__builtin_inff(); si[t] = -1; }
-    if (tid == 0) s_count = 0;
-    __syncthreads();
-
-    auto flush = [&]() {      // sort head + pending, pad the rest again; all threads call it
-        const int used = k + s_count;
-        int n = 64;
-        while (n < used) n <<= 1;
-        lds_sort_desc(sv, si, n, tid);
-        for (int t = k + tid; t < n; t += 256) { sv[t] = -__builtin_inff(); si[t] = -1; }
-        if (tid == 0) s_count = 0;
-        __syncthreads();
-    };
-
-    for (int base = begin; base < end; base += kSelStep) {
-        if (k + s_count + kSelStep > kSelBuf) flush();      // s_count is uniform here (read after a barrier)
-        const float thr_v = sv[k - 1];
-        const int thr_i = si[k - 1];
-#pragma unroll
-        for (int u = 0; u < kSelStep / 256; ++u) {
-            const int pos = base + u * 256 + tid;
-            if (pos < end) {
-                const float v = key_sanitize(rv[pos]);
-                const int id = PAIRS ? ri[pos] : id_base + pos;
-                if (pair_before(v, id, thr_v, thr_i)) {
-                    const int slot = atomicAdd(&s_count, 1);
-                    sv[k + slot] = v;
-                    si[k + slot] = id;
-                }
-            }
-        }
-        __syncthreads();
-    }
-    flush();
-    const size_t o = ((size_t)b * gridDim.x + c) * (size_t)k;
-    for (int t = tid; t < k; t += 256) { out_val[o + t] = sv[t]; out_idx[o + t] = si[t]; }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Last step, one wave per row: the k sorted candidates (key, id) of the row ->
+// One wave, lane j holds the j-th candidate of row b (padding beyond k):
 //   truncation    nucleus rule on the softmax over the candidates (keep the shortest prefix whose
 //                 mass reaches top_p, at least one), then Gumbel-max over the kept ids with the
 //                 per-id noise of the main path (lowest id on exact ties);
 //   Gumbel-top-k  the first candidate.
 // Also copies the candidates to the caller's arrays (if given) and reports how many were kept.
-__global__ void __launch_bounds__(64)
-topk_finish_kernel(const float* __restrict__ cand_val, const int32_t* __restrict__ cand_idx, int k, float top_p, int mode,
-                   uint64_t seed, const uint64_t* __restrict__ row_seeds, int64_t row_offset, uint32_t epi_flags,
-                   int32_t* __restrict__ out_idx, float* __restrict__ out_val, float* __restrict__ topk_val,
-                   int32_t* __restrict__ topk_idx, int32_t* __restrict__ n_kept)
+__device__ __forceinline__ void topk_finish(const TopkFinish& f, int b, int k, int lane, float key, int32_t id)
 {
-    const int b = blockIdx.x, lane = threadIdx.x;
-    float key = -__builtin_inff();
-    int id = -1;
-    if (lane < k) { key = cand_val[(size_t)b * k + lane]; id = cand_idx[(size_t)b * k + lane]; }
     if (lane < k) {
-        if (topk_val) topk_val[(size_t)b * k + lane] = key;
-        if (topk_idx) topk_idx[(size_t)b * k + lane] = id;
+        if (f.topk_val) f.topk_val[(size_t)b * k + lane] = key;
+        if (f.topk_idx) f.topk_idx[(size_t)b * k + lane] = id;
     }
     const bool live = id >= 0 && key > -__builtin_inff();
     float best = -__builtin_inff();
     int best_id = -1;
     int kept_count;
-    if (mode == kTopkGumbel) {
+    if (f.mode == kTopkGumbel) {
         kept_count = (int)__builtin_popcountll(__ballot(live));
         if (lane == 0 && live) { best = key; best_id = id; }
     } else {
@@ -170,17 +70,15 @@ topk_finish_kernel(const float* __restrict__ cand_val, const int32_t* __restrict
         }
         const float total = __shfl(cum, kWave - 1, kWave);
         // kept: everything before it has not reached top_p yet (the first live candidate always is)
-        const bool kept = live && (top_p >= 1.0f || lane == 0 || (cum - e) < top_p * total);
+        const bool kept = live && (f.top_p >= 1.0f || lane == 0 || (cum - e) < f.top_p * total);
         kept_count = (int)__builtin_popcountll(__ballot(kept));
         if (kept) {
-            const uint64_t sd = row_seeds ? row_seeds[b] : seed;
-            const uint32_t w = [&]() {
-                uint32_t ww[4];
-                philox4x32_10((uint32_t)id >> 2, (uint32_t)(uint64_t)(row_offset + b), 0u, 0u, (uint32_t)sd, (uint32_t)(sd >> 32), ww);
-                const uint32_t q = (uint32_t)id & 3u;
-                return q == 0u ? ww[0] : q == 1u ? ww[1] : q == 2u ? ww[2] : ww[3];
-            }();
-            best = key + ((epi_flags & kEpiExactLog) ? gumbel_from_word_exact(w) : gumbel_from_word(w));
+            const uint64_t sd = f.row_seeds ? f.row_seeds[b] : f.seed;
+            uint32_t ww[4];
+            philox4x32_10((uint32_t)id >> 2, (uint32_t)(uint64_t)(f.row_offset + b), 0u, 0u, (uint32_t)sd, (uint32_t)(sd >> 32), ww);
+            const uint32_t q = (uint32_t)id & 3u;
+            const uint32_t w = q == 0u ? ww[0] : q == 1u ? ww[1] : q == 2u ? ww[2] : ww[3];
+            best = key + ((f.epi_flags & kEpiExactLog) ? gumbel_from_word_exact(w) : gumbel_from_word(w));
             best_id = id;
         }
     }
@@ -193,9 +91,186 @@ topk_finish_kernel(const float* __restrict__ cand_val, const int32_t* __restrict
         best_id = take ? oi : best_id;
     }
     if (lane == 0) {
-        out_idx[b] = best_id;
-        out_val[b] = best;
-        if (n_kept) n_kept[b] = kept_count;
+        f.out_idx[b] = best_id;
+        f.out_val[b] = best;
+        if (f.n_kept) f.n_kept[b] = kept_count;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------------------
+// The k best candidates of one chunk of one row.  grid = (chunks, B), 256 threads.
+//   KEYS   input is a row of stored fp32 logits, id = id_base + position, key formed on the fly;
+//          otherwise packed candidates
+//   FINAL  one chunk per row: nucleus rule and draw follow (topk_finish); otherwise the k words go
+//          to out[(b * chunks + c) * k + j], sorted, padded
+//
+// Every thread holds kSelE candidates of the chunk in registers.  The k-th largest of the 256
+// per-thread maxima is a lower bound of the chunk's k-th largest candidate (k threads hold one at
+// least as large), and only the threads that own those k maxima can hold anything at or above it:
+// at most k * kSelE candidates pass, whatever the data (typically little more than k).  They go to a
+// list in LDS, which one wave sorts in registers when it has at most 128 entries and the workgroup
+// sorts in LDS otherwise.  The result does not depend on the order in which the list is filled: the
+// order on words is total.  The k-th largest maximum: every wave sorts its 64 maxima, then each
+// thread ranks its own among the other three runs by binary search.
+constexpr int kSelE = 32;
+constexpr int kSelChunk = 256 * kSelE;          // candidates one workgroup can take
+constexpr int kSelList = kTopkMax * kSelE;      // bound of the list
+
+__device__ __forceinline__ void lds_sort_desc(uint64_t* s, int n, int tid)   // n: power of two
+{
+    for (int size = 2; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int t = tid; t < (n >> 1); t += 256) {
+                const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
+                const int hi = lo | stride;
+                const bool up = (lo & size) == 0 || size == n;      // the last merge sorts the whole array descending
+                const uint64_t a = s[lo], c = s[hi];
+                if ((a > c) != up) { s[lo] = c; s[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <bool KEYS, bool FINAL>
+__global__ void __launch_bounds__(256)
+topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32_t id_base, int chunk_len, int k,
+                   uint64_t* __restrict__ out, TopkKeys kp, TopkFinish fin, TopkFix fix)
+{
+    __shared__ uint64_t s_list[kSelList];
+    __shared__ uint64_t s_max[256];
+    __shared__ uint64_t s_thr;
+    __shared__ int s_count;
+    __shared__ int s_nfix;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y, c = blockIdx.x;
+    if (FINAL && fix.row_gate && fix.row_gate[b] == 0) return;       // uniform over the workgroup
+    const int begin = c * chunk_len;
+    int end = begin + chunk_len;
+    end = end < N ? end : N;
+
+    uint64_t it[kSelE];
+    uint64_t m = kTopkPad;
+    if constexpr (KEYS) {
+        // four consecutive ids per thread and load: one Philox block serves them
+        const float* row = static_cast<const float*>(in) + (size_t)b * row_stride;
+        const float inv_tau = 1.0f / kp.tau[b];
+        const uint64_t sd = kp.row_seeds ? kp.row_seeds[b] : kp.seed;
+        const bool vec = (((uint64_t)row_stride | (uint64_t)begin) & 3u) == 0u && ((uintptr_t)in & 15u) == 0u;
+#pragma unroll
+        for (int j = 0; j < kSelE / 4; ++j) {
+            const int p4 = begin + (j * 256 + tid) * 4;
+            float y[4] = {0.f, 0.f, 0.f, 0.f};
+            if (p4 + 3 < end && vec) {
+                const f32x4 q = *reinterpret_cast<const f32x4*>(row + p4);
+                y[0] = q[0]; y[1] = q[1]; y[2] = q[2]; y[3] = q[3];
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (p4 + q < end) y[q] = row[p4 + q];
+            }
+            float gn[4] = {0.f, 0.f, 0.f, 0.f};
+            if (kp.mode == kTopkGumbel && p4 < end)
+                gumbel4(sd, (uint32_t)(uint64_t)(kp.row_offset + b), (uint32_t)(id_base + p4), gn,
+                        (kp.epi_flags & kEpiExactLog) != 0u);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint64_t w = p4 + q < end ? topk_pack(fmaf(y[q], inv_tau, gn[q]), id_base + p4 + q) : kTopkPad;
+                it[4 * j + q] = w;
+                m = w > m ? w : m;
+            }
+        }
+    } else {
+        // candidate j of the thread: position 256 j + ((tid + 37 j) mod 256) of the chunk -- coalesced, and
+        // the rotation keeps a thread from collecting the same rank of many sorted runs
+        const uint64_t* words = static_cast<const uint64_t*>(in) + (size_t)b * row_stride;
+#pragma unroll
+        for (int j = 0; j < kSelE; ++j) {
+            const int pos = begin + j * 256 + ((tid + 37 * j) & 255);
+            it[j] = pos < end ? words[pos] : kTopkPad;
+            m = it[j] > m ? it[j] : m;
+        }
+    }
+    wave_sort64_desc(m, lane);
+    s_max[tid] = m;                              // four descending runs of 64
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    int rank = lane;                             // position of m among the 256 maxima (ties: lower wave first)
+    for (int w2 = 0; w2 < 4; ++w2) {
+        if (w2 == wave) continue;
+        const uint64_t* run = s_max + w2 * 64;
+        auto before = [&](uint64_t o) { return o > m || (o == m && w2 < wave); };
+        int cnt = 0;
+#pragma unroll
+        for (int step = 32; step >= 1; step >>= 1)
+            if (before(run[cnt + step - 1])) cnt += step;
+        if (cnt == 63 && before(run[63])) cnt = 64;
+        rank += cnt;
+    }
+    if (rank == k - 1) s_thr = m;
+    __syncthreads();
+    const uint64_t thr = s_thr;
+#pragma unroll
+    for (int j = 0; j < kSelE; ++j) {
+        if (it[j] >= thr && (uint32_t)it[j] != 0u) {      // low half 0: padding
+            const int slot = atomicAdd(&s_count, 1);
+            s_list[slot] = it[j];
+        }
+    }
+    __syncthreads();
+    const int n = s_count;
+    if (n <= 128) {
+        if (tid < kWave) {
+            uint64_t a0 = tid < n ? s_list[tid] : kTopkPad;
+            uint64_t a1 = tid + 64 < n ? s_list[tid + 64] : kTopkPad;
+            wave_sort128_desc(a0, a1, tid);
+            s_list[tid] = a0;
+        }
+    } else {
+        int n2 = 256;
+        while (n2 < n) n2 <<= 1;
+        for (int t = n + tid; t < n2; t += 256) s_list[t] = kTopkPad;
+        __syncthreads();
+        lds_sort_desc(s_list, n2, tid);
+    }
+    __syncthreads();
+    if constexpr (!FINAL) {
+        if (tid < k) out[((size_t)b * gridDim.x + c) * (size_t)k + tid] = s_list[tid];
+    } else {
+        if (tid < kWave) {
+            const uint64_t w = tid < k ? s_list[tid] : kTopkPad;
+            topk_finish(fin, b, k, tid, topk_key(w), topk_id(w));
+            if (fix.cand) {                      // uniform over the launch
+                int t = -1;
+                bool flagged = false;
+                if ((uint32_t)w != 0u) {
+                    t = (topk_id(w) - fix.vocab_offset) >> 7;
+                    flagged = fix.cand[((size_t)b * fix.T + t) * (size_t)fix.m + (fix.m - 1)] == w;
+                }
+                const uint64_t fb = __ballot(flagged);
+                const int nfix = (int)__builtin_popcountll(fb);      // <= k / m: a listed tile has m winners
+                if (tid == 0) { fix.n_fix[b] = nfix; s_nfix = nfix; }
+                if (nfix != 0) {
+                    if (flagged) {
+                        const int sl = (int)__builtin_popcountll(fb & ((1ull << tid) - 1ull));
+                        fix.fix_tiles[b * kTopkFixMax + sl] = t;
+                        fix.tile_flag[t] = 1;
+                    }
+                    bool listed = false;
+                    for (uint64_t r = fb; r != 0ull; r &= r - 1ull) {
+                        const int tf = __shfl(t, (int)__builtin_ctzll(r), kWave);
+                        listed = listed || t == tf;
+                    }
+                    if (tid < k) fix.rowbuf[(size_t)b * fix.rowbuf_stride + tid] = listed ? kTopkPad : w;
+                }
+            }
+        }
+        if (fix.cand) {
+            __syncthreads();
+            if (s_nfix != 0)
+                for (int t = tid; t < kTopkFixMax * k; t += 256) fix.rowbuf[(size_t)b * fix.rowbuf_stride + k + t] = kTopkPad;
+        }
     }
 }
 

@@ -160,6 +160,58 @@ def test_adversarial_orders_and_ties_in_the_selection(fs, orc):
     assert np.array_equal(got[3], ref["top_id"]) and got[0][0] == ref["idx"][0]
 
 
+def _one_hot_problem(logit_rows, D):
+    """hidden[b] = e_b and W[v, b] = logit_rows[b][v] (values exact in bf16): logits under full control."""
+    B, V = len(logit_rows), len(logit_rows[0])
+    H = np.zeros((B, D), dtype=np.uint16)
+    W = np.zeros((V, D), dtype=np.uint16)
+    for b in range(B):
+        H[b, b] = 0x3F80
+        W[:, b] = wl.f32_to_bf16_bits(np.asarray(logit_rows[b], dtype=np.float32))
+    return H, W
+
+
+@pytest.mark.parametrize("k", [9, 50, 64])
+def test_fused_second_pass_when_winners_crowd_a_tile(fs, orc, k):
+    # the fused first pass keeps 8 candidates per 128-id tile; these rows put far more of the top k into
+    # single tiles, so the exact result needs the second pass (values on a grid that bf16 holds exactly)
+    rng = np.random.default_rng(580 + k)
+    V, D = 5000, 192
+    rows = []
+    rows.append(np.arange(V) * 0.03125 - 60.0)                                  # ascending: winners fill the last tiles
+    r = np.round(rng.normal(0, 8, V) * 4) / 4                                    # three crowded tiles plus scattered ids
+    for t, cnt in ((3, 16), (17, 16), (30, 9)):
+        r[t * 128 + rng.choice(128, cnt, replace=False)] = 100.0 + np.arange(cnt)
+    rows.append(r)
+    rows.append(np.round(rng.normal(0, 8, V) * 4) / 4)                           # ordinary row beside them
+    r = np.full(V, -3.0); r[1000:1100] = 7.0                                     # 100 equal maxima in two tiles: lowest ids win
+    rows.append(r)
+    for b in range(4, 132):                                                      # second batch tile, rows of both kinds
+        r = np.round(rng.normal(0, 8, V) * 4) / 4
+        if b % 3 == 0:
+            t = int(rng.integers(0, 39))
+            r[t * 128:(t + 1) * 128] += 64.0
+        rows.append(r)
+    H, W = _one_hot_problem(rows, D)
+    B = len(rows)
+    tau = np.ones(B, dtype=np.float32)
+    for mode, p in ((TRUNC, 0.9), (GUMBEL, 1.0)):
+        ref = orc.sample_topk(H, W, tau, k, top_p=p, mode=mode, seed=9, vocab_offset=128)
+        got = run(fs, H, W, tau, k, p, mode, True, seed=9, vocab_offset=128)
+        if mode == TRUNC:                        # keys are the exact logits: everything is unique
+            assert np.array_equal(got[3], ref["top_id"])
+            assert np.array_equal(got[0], ref["idx"])
+            assert np.array_equal(got[4], ref["n_kept"])
+        else:
+            exact, near = judge_topk(orc, H, W, tau, k, p, mode, ref, got, seed=9, vocab_offset=128)
+            assert near <= 3, (exact, near)
+    # a second call with ordinary rows on the same workspace-sized problem: no stale flags
+    H2, W2 = wl.make_small(D=D, V=V, B=B, data_seed=590)
+    ref = orc.sample_topk(H2, W2, tau, k, top_p=0.9, mode=TRUNC, seed=9)
+    got = run(fs, H2, W2, tau, k, 0.9, TRUNC, True, seed=9)
+    judge_topk(orc, H2, W2, tau, k, 0.9, TRUNC, ref, got, seed=9)
+
+
 def test_topk_at_llama_shape_every_row(fs, orc):
     w = wl.WORKLOADS["C2"]
     Wb = wl.make_weights(w)
