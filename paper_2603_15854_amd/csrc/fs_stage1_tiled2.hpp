@@ -324,25 +324,43 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             }
         }
         __syncthreads();
-        for (int u = wave; u < BT * Cfg::kCandTiles; u += Cfg::kWaves) {     // unit = (batch row, candidate tile)
-            const int bl = u % BT, ct = u / BT;
-            const int b = b0 + bl;
-            const int ctile = tile * Cfg::kCandTiles + ct;
-            if (b >= B || ctile >= T) continue;                              // wave-uniform
-            const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-            const float v0 = keys[bl * KSTRIDE + ct * kVocabTile + lane];
-            const float v1 = keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane];
-            if constexpr (TOPK == 1) {
-                const int kt = p.topk_k;
-                const uint64_t r = wave_top_m(v0, v1, e0 < V, e1 < V, p.vocab_offset + tile_row0 + ct * kVocabTile, kt, lane);
-                if (lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = r;
-            } else {
-                if (p.tile_flag[ctile] == 0) continue;
+        constexpr int NUNIT = BT * Cfg::kCandTiles;          // unit = (batch row, candidate tile)
+        if constexpr (TOPK == 1) {
+            constexpr int U = 4;                             // units a wave works on at once
+            static_assert(NUNIT % (Cfg::kWaves * U) == 0, "units per wave");
+            const int kt = p.topk_k;
+            for (int ub = wave * U; ub < NUNIT; ub += Cfg::kWaves * U) {
+                uint32_t k0[U], k1[U];
+                int32_t id0[U];
+#pragma unroll
+                for (int q = 0; q < U; ++q) {
+                    const int u = ub + q, bl = u % BT, ct = u / BT;
+                    const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
+                    k0[q] = e0 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + lane]) : 0u;
+                    k1[q] = e1 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane]) : 0u;
+                    id0[q] = p.vocab_offset + tile_row0 + ct * kVocabTile;
+                }
+                uint64_t res[U];
+                wave_top_m<U>(k0, k1, id0, kt, lane, res);
+#pragma unroll
+                for (int q = 0; q < U; ++q) {
+                    const int u = ub + q, bl = u % BT, ct = u / BT;
+                    const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
+                    if (b < B && ctile < T && lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = res[q];
+                }
+            }
+        } else {
+            for (int u = wave; u < NUNIT; u += Cfg::kWaves) {
+                const int bl = u % BT, ct = u / BT;
+                const int b = b0 + bl;
+                const int ctile = tile * Cfg::kCandTiles + ct;
+                if (b >= B || ctile >= T || p.tile_flag[ctile] == 0) continue;      // wave-uniform
+                const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
                 const int nf = p.n_fix[b];
                 for (int sl = 0; sl < nf; ++sl) {
                     if (p.fix_tiles[b * kTopkFixMax + sl] != ctile) continue;
-                    uint64_t a0 = e0 < V ? topk_pack(v0, p.vocab_offset + e0) : kTopkPad;
-                    uint64_t a1 = e1 < V ? topk_pack(v1, p.vocab_offset + e1) : kTopkPad;
+                    uint64_t a0 = e0 < V ? topk_pack(keys[bl * KSTRIDE + ct * kVocabTile + lane], p.vocab_offset + e0) : kTopkPad;
+                    uint64_t a1 = e1 < V ? topk_pack(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane], p.vocab_offset + e1) : kTopkPad;
                     wave_sort128_desc(a0, a1, lane);
                     const int kf = p.topk_kfull;
                     if (lane < kf) p.rowbuf[(size_t)b * p.rowbuf_stride + (size_t)kf * (1 + sl) + lane] = a0;

@@ -63,13 +63,18 @@ struct TopkFix {
 
 __device__ __forceinline__ float key_sanitize(float k) { return k == k ? k : -__builtin_inff(); }
 
-__device__ __forceinline__ uint64_t topk_pack(float key, int32_t id)
+// key -> unsigned integer with the same order (NaN -> -inf, -0 -> +0 first); never 0
+__device__ __forceinline__ uint32_t topk_ordered(float key)
 {
     key = key_sanitize(key);
     key = key == 0.0f ? 0.0f : key;
-    uint32_t b = __float_as_uint(key);
-    b ^= (uint32_t)((int32_t)b >> 31) | 0x80000000u;
-    return ((uint64_t)b << 32) | (uint64_t)(~(uint32_t)id);
+    const uint32_t b = __float_as_uint(key);
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
+}
+
+__device__ __forceinline__ uint64_t topk_pack(float key, int32_t id)
+{
+    return ((uint64_t)topk_ordered(key) << 32) | (uint64_t)(~(uint32_t)id);
 }
 
 constexpr uint64_t kTopkPad = 0x007FFFFF00000000ull;      // topk_pack(-inf, -1)
@@ -123,48 +128,67 @@ __device__ __forceinline__ void wave_sort64_desc(uint64_t& a, int lane)
     }
 }
 
-// Maximum of a float over the wave, in every lane.  Six steps through the data-parallel lane
-// permutes of the vector ALU (no LDS traffic): quads, half rows, rows of 16, then row 0 -> 1 and
-// 2 -> 3 and rows 0..1 -> 2..3 broadcasts, after which lane 63 holds the maximum.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_max_step(float x)
+// Maximum of an unsigned word over the wave, for four independent words at once.  Six steps through
+// the data-parallel lane permutes of the vector ALU (no LDS traffic): quads, half rows, rows of 16,
+// then the row 0 -> 1 and 2 -> 3 and the rows 0..1 -> 2..3 broadcasts, after which lane 63 holds the
+// maximum.  Written as one assembly block because the compiler does not fold the permute into the
+// max (three instructions per step instead of one).  A permuting instruction must not read a
+// register in the two issue slots after a vector instruction wrote it: the four chains are
+// interleaved, so the three instructions of the other chains fill those slots, and a two-slot nop
+// separates the block from whatever wrote the inputs.
+__device__ __forceinline__ void wave_max4(uint32_t& a, uint32_t& b, uint32_t& c, uint32_t& d)
 {
-    const int y = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xF, false);
-    return fmaxf(x, __int_as_float(y));
+#define FS_DPP_MAX4(ctrl)                                   \
+    "v_max_u32_dpp %0, %0, %0 " ctrl "\n\t"                 \
+    "v_max_u32_dpp %1, %1, %1 " ctrl "\n\t"                 \
+    "v_max_u32_dpp %2, %2, %2 " ctrl "\n\t"                 \
+    "v_max_u32_dpp %3, %3, %3 " ctrl "\n\t"
+    asm volatile("s_nop 1\n\t"
+                 FS_DPP_MAX4("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")
+                 FS_DPP_MAX4("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")
+                 FS_DPP_MAX4("row_half_mirror row_mask:0xf bank_mask:0xf")
+                 FS_DPP_MAX4("row_mirror row_mask:0xf bank_mask:0xf")
+                 FS_DPP_MAX4("row_bcast:15 row_mask:0xa bank_mask:0xf")
+                 FS_DPP_MAX4("row_bcast:31 row_mask:0xc bank_mask:0xf")
+                 "s_nop 1"
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+#undef FS_DPP_MAX4
+    a = (uint32_t)__builtin_amdgcn_readlane((int)a, 63);
+    b = (uint32_t)__builtin_amdgcn_readlane((int)b, 63);
+    c = (uint32_t)__builtin_amdgcn_readlane((int)c, 63);
+    d = (uint32_t)__builtin_amdgcn_readlane((int)d, 63);
 }
 
-__device__ __forceinline__ float wave_max(float x)
+// The m best of the 128 keys of each of U tiles at once (m <= 64 and small).  Unit u: k0[u] is the
+// ordered key (topk_ordered) of id id0[u] + lane, k1[u] of id0[u] + 64 + lane, 0 where the id does not
+// exist.  m rounds of (wave maximum, lowest id that attains it, strike it); the U chains are
+// independent, which is what hides the latency of a round.  Lane j < m gets the j-th best of unit u
+// in res[u], packed; padding where the tile has fewer.
+template <int U>
+__device__ __forceinline__ void wave_top_m(uint32_t (&k0)[U], uint32_t (&k1)[U], const int32_t (&id0)[U], int m, int lane,
+                                           uint64_t (&res)[U])
 {
-    x = dpp_max_step<0xB1, 0xF>(x);      // quad_perm [1,0,3,2]
-    x = dpp_max_step<0x4E, 0xF>(x);      // quad_perm [2,3,0,1]
-    x = dpp_max_step<0x141, 0xF>(x);     // row_half_mirror
-    x = dpp_max_step<0x140, 0xF>(x);     // row_mirror
-    x = dpp_max_step<0x142, 0xA>(x);     // row_bcast15 into rows 1 and 3
-    x = dpp_max_step<0x143, 0xC>(x);     // row_bcast31 into rows 2 and 3
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
-// The m best of the 128 keys of a tile, m <= 64 and small: key v0 belongs to id id0 + lane, v1 to
-// id0 + 64 + lane; live0 / live1 say which of them exist.  m rounds of (wave maximum, lowest id that
-// attains it, strike it).  Lane j < m returns the j-th best, packed; padding where the tile has fewer.
-__device__ __forceinline__ uint64_t wave_top_m(float v0, float v1, bool live0, bool live1, int32_t id0, int m, int lane)
-{
-    const float ninf = -__builtin_inff();
-    v0 = live0 ? key_sanitize(v0) : ninf;
-    v1 = live1 ? key_sanitize(v1) : ninf;
-    uint64_t res = kTopkPad;
+    static_assert(U == 4, "four chains fill each other's permute wait slots");
+#pragma unroll
+    for (int u = 0; u < U; ++u) res[u] = kTopkPad;
     for (int j = 0; j < m; ++j) {
-        const float mx = wave_max(fmaxf(v0, v1));
-        const uint64_t b0 = __ballot(live0 && v0 == mx), b1 = __ballot(live1 && v1 == mx);
-        if ((b0 | b1) == 0ull) break;                    // nothing left (wave-uniform)
-        const bool first = b0 != 0ull;
-        const int win = __builtin_ctzll(first ? b0 : b1);
-        if (lane == j) res = topk_pack(mx, id0 + win + (first ? 0 : 64));
-        if (lane == win) {
-            if (first) { live0 = false; v0 = ninf; } else { live1 = false; v1 = ninf; }
+        uint32_t mxs[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) mxs[u] = k0[u] > k1[u] ? k0[u] : k1[u];
+        wave_max4(mxs[0], mxs[1], mxs[2], mxs[3]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t mx = mxs[u];
+            const uint64_t b0 = __ballot(k0[u] == mx), b1 = __ballot(k1[u] == mx);
+            const bool any = mx != 0u;                       // wave-uniform: something is left
+            const bool first = b0 != 0ull;
+            const int win = __builtin_ctzll(first ? b0 : b1);
+            if (any && lane == j) res[u] = ((uint64_t)mx << 32) | (uint64_t)(~(uint32_t)(id0[u] + win + (first ? 0 : 64)));
+            if (any && lane == win) {
+                if (first) k0[u] = 0u; else k1[u] = 0u;
+            }
         }
     }
-    return res;
 }
 
 }  // namespace fs
