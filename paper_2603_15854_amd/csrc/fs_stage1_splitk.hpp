@@ -249,8 +249,11 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
                         const int c = 4 * s + g;
                         a = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(stage + rd_row_off + ((c ^ n) << 4)));
                     } else {   // 8 one-byte elements: half of chunk 2 s + g / 2
-                        const int c = 2 * s + (g >> 1);
-                        const uint2 q = *reinterpret_cast<const uint2*>(stage + rd_row_off + ((c ^ n) << 4) + ((g & 1) << 3));
+                        // slot (c ^ n) with c = 2 s + g / 2: the lane's part of the XOR is one register and the
+                        // XOR is redone at every read; kept as SK loop-invariant offsets it cost scratch spills
+                        uint32_t gn = (uint32_t)((g >> 1) ^ n) << 4;
+                        asm volatile("" : "+v"(gn));
+                        const uint2 q = *reinterpret_cast<const uint2*>(stage + rd_row_off + (((uint32_t)s << 5) ^ gn) + ((g & 1) << 3));
                         a = e4m3x8_to_bf16x8(q.x, q.y);
                     }
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, hreg[h * SK + s], acc, 0, 0, 0);

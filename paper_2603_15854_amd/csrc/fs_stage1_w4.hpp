@@ -94,26 +94,53 @@ stage1_w4_kernel(const Stage1Params p, const uint8_t* __restrict__ w_scales, con
         if (rtl >= nrt) return 0;
         return ((int)blockIdx.x + (rtl >> 3) * (int)gridDim.x) * kVocabTile + (rtl & 7) * 16;
     };
-    // all loads are unconditional (rows past V re-read row V - 1 and only feed masked outputs)
+    // All loads are unconditional (rows past V re-read row V - 1 and only feed masked outputs).
+    // 32 steps per wave: address = a base that is uniform over the wave (the row-tile's first row, in
+    // scalar registers) + a 32-bit lane offset inside the row-tile, so that no 64-bit address lives in
+    // vector registers (the kernel has none to spare); 16 steps per wave: plain per-lane addresses,
+    // which the compiler keeps in registers across row-tiles (measured 3 % faster there).
     auto issue_loads = [&](uint4 (&dst)[NI], uint4 (&sdst)[NS], int rtl) {
-        const int rb = row_base(rtl);
-        const unsigned char* src = reinterpret_cast<const unsigned char*>(p.W) + (size_t)(ks0 + ld_chunk) * 16;
+        if constexpr (KPW == 32) {
+            const int rb = __builtin_amdgcn_readfirstlane(row_base(rtl));
+            const uint32_t last = (uint32_t)(V - 1 - rb);      // rows of this tile past `last` do not exist
+            const unsigned char* src = reinterpret_cast<const unsigned char*>(p.W) + (size_t)rb * rowbytes;
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            int row = rb + j * RPI + ld_row;
-            row = row < V - 1 ? row : V - 1;
-            dst[j] = ld_global_16B_stream(reinterpret_cast<const uint16_t*>(src + (size_t)row * rowbytes));
+            for (int j = 0; j < NI; ++j) {
+                uint32_t r = (uint32_t)(j * RPI + ld_row);
+                r = r < last ? r : last;
+                const uint32_t off = r * (uint32_t)rowbytes + (uint32_t)(ks0 + ld_chunk) * 16u;
+                dst[j] = ld_global_16B_stream(reinterpret_cast<const uint16_t*>(src + off));
+            }
+            const unsigned char* ssrc = w_scales + (size_t)rb * scalebytes;
+            uint32_t sr = (uint32_t)n;
+            sr = sr < last ? sr : last;
+#pragma unroll
+            for (int u = 0; u < NS; ++u)
+                sdst[u] = ld_global_16B(reinterpret_cast<const uint16_t*>(ssrc + sr * (uint32_t)scalebytes + (uint32_t)(ks0 + 16 * u)));
+        } else {
+            const int rb = row_base(rtl);
+            const unsigned char* src = reinterpret_cast<const unsigned char*>(p.W) + (size_t)(ks0 + ld_chunk) * 16;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                int row = rb + j * RPI + ld_row;
+                row = row < V - 1 ? row : V - 1;
+                dst[j] = ld_global_16B_stream(reinterpret_cast<const uint16_t*>(src + (size_t)row * rowbytes));
+            }
+            int srow = rb + n;
+            srow = srow < V - 1 ? srow : V - 1;
+#pragma unroll
+            for (int u = 0; u < NS; ++u)
+                sdst[u] = ld_global_16B(reinterpret_cast<const uint16_t*>(w_scales + (size_t)srow * scalebytes + ks0 + 16 * u));
         }
-        int srow = rb + n;
-        srow = srow < V - 1 ? srow : V - 1;
-#pragma unroll
-        for (int u = 0; u < NS; ++u)
-            sdst[u] = ld_global_16B(reinterpret_cast<const uint16_t*>(w_scales + (size_t)srow * scalebytes + ks0 + 16 * u));
     };
 
     // LDS stage: [16 rows][ROWB bytes], 16-byte chunk c of row r in slot c ^ r
     const int st_base = ld_row * ROWB + ((ld_chunk ^ ld_row) << 4);
-    auto st_off = [&](int j) -> int { return (st_base ^ (((j * RPI) & 15) << 4)) + j * RPI * ROWB; };
+    auto st_off = [&](int j) -> int {      // 32 steps per wave: recomputed at every use (see the reads below)
+        int sb = st_base;
+        if constexpr (KPW == 32) asm volatile("" : "+v"(sb));
+        return (sb ^ (((j * RPI) & 15) << 4)) + j * RPI * ROWB;
+    };
     const int rd_off = n * ROWB + (g << 2);
 
 #pragma unroll
@@ -144,7 +171,12 @@ stage1_w4_kernel(const Stage1Params p, const uint8_t* __restrict__ w_scales, con
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < KPW; ++s) {
-                const uint32_t codes = *reinterpret_cast<const uint32_t*>(stage + rd_off + ((s ^ n) << 4));
+                // slot (s ^ n) of row n: the XOR is redone here (one instruction) rather than kept as KPW
+                // loop-invariant offsets in registers, which is what pushed the 32-step kernel into scratch
+                // (the 16-step kernel has the registers and is 6 % faster with the offsets kept)
+                uint32_t nx = (uint32_t)n << 4;
+                if constexpr (KPW == 32) asm volatile("" : "+v"(nx));
+                const uint32_t codes = *reinterpret_cast<const uint32_t*>(stage + rd_off + (((uint32_t)s << 4) ^ nx));
                 const uint32_t e = (scw[s >> 2] >> (8 * (s & 3))) & 0xFFu;
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mxfp4x8_to_bf16x8(codes, e), hreg[s], acc, 0, 0, 0);
             }
