@@ -12,6 +12,7 @@ line carries, unless --quick is given:
                   kernel times) and C5 (B=1/8/64/256/512), fused and unfused
   epilogue_share  stage 1 with the noise switched off (FS_FLAG_GREEDY) against the sampling form
   top_k           the fused top-k / top-p draw against "logits-store GEMM + top-k kernel"
+  stream_fit      steady streaming rate and fixed cost per call of the B <= 16 kernels (bf16, FP8, MXFP4)
   fp8_weights, mxfp4_weights   the same call on lower-precision weights
   cpu_baseline    the CPU oracle on the host cores (bounded sample)
 
@@ -370,6 +371,49 @@ def main() -> int:
         out["mxfp4_weights"] = {"format": "OCP MXFP4: E2M1 codes, one E8M0 scale per 32 elements, hidden bf16",
                                 "rows": rows4}
         del W4d, S4d, c4, s4
+
+        # -------------------------------------------------------------- streaming rate vs fixed cost per call
+        # whole calls at V = 256 * 128 * k (k vocabulary tiles per persistent workgroup), B = 16: the slope
+        # over k is the steady streaming rate, the intercept what a call costs before and after it
+        # (launch, first-byte latency, last tile's epilogue, stage 2)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(11)
+        fit_rows = []
+        legq = Leg(w, Wd, 16)
+        ks = (1, 2, 4, 8)
+        for fmt, row_bytes in (("bf16", 2 * D), ("fp8_e4m3", D + 4), ("mxfp4", D // 2 + D // 32)):
+            us = []
+            for kk in ks:
+                Vk = 256 * fs.FS_VOCAB_TILE * kk
+                wsk = torch.empty(fs.flash_sample_workspace_bytes(16, Vk), dtype=torch.uint8, device="cuda")
+                if fmt == "bf16":
+                    Wk = (torch.randn((Vk, D), device="cuda", generator=g) / 64).to(torch.bfloat16)
+                    fn = lambda: fs.flash_sample_ex(legq.Hd, Wk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                    workspace=wsk, stream=stream)
+                elif fmt == "fp8_e4m3":
+                    Wk = torch.randint(0, 120, (Vk, D), dtype=torch.uint8, device="cuda", generator=g)
+                    sk = torch.ones(Vk, device="cuda")
+                    fn = lambda: fs.flash_sample_w8(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                    workspace=wsk, stream=stream)
+                else:
+                    Wk = torch.randint(0, 256, (Vk, D // 2), dtype=torch.uint8, device="cuda", generator=g)
+                    sk = torch.randint(120, 130, (Vk, D // 32), dtype=torch.uint8, device="cuda", generator=g)
+                    fn = lambda: fs.flash_sample_w4(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                    workspace=wsk, stream=stream)
+                us.append(per_call_us(fn, calls=50, repeats=3)["median_us"])
+                del Wk, wsk
+            slope, intercept = np.polyfit(np.array(ks, dtype=np.float64), np.array(us), 1)
+            step_bytes = 256 * fs.FS_VOCAB_TILE * row_bytes
+            fit_rows.append({"weights": fmt, "us_at_k": dict(zip(map(str, ks), us)), "us_per_tile_round": round(float(slope), 3),
+                             "steady_gbs": round(step_bytes / slope / 1e3, 1),
+                             "steady_pct_hbm_peak": round(100.0 * step_bytes / slope / 1e3 / HBM_PEAK_GBS, 2),
+                             "fixed_us_per_call": round(float(intercept), 2)})
+        out["stream_fit"] = {
+            "what": "whole calls at B=16, D=%d, V = 256*128*k for k = 1, 2, 4, 8 (random weights; the values do not "
+                    "matter for time): least-squares line through the medians.  steady = bytes of one round of "
+                    "256 vocabulary tiles / slope; fixed = intercept" % D,
+            "rows": fit_rows}
+        torch.cuda.empty_cache()
 
         # -------------------------------------------------------------- the other workloads
         # C3 (Qwen-style vocabulary), C4 (D=8192: the shape of the paper's only absolute kernel

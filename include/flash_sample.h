@@ -91,8 +91,8 @@ typedef enum {
 /* bits 16..19: tuning aid.  FS_VARIANT_SPLITK: workgroups per compute unit (0 = automatic).
  * FS_VARIANT_TILED2: tile shape (vocabulary rows x batch rows, waves), 0 = automatic,
  * 1 = 128x32 (4 waves), 2 = 256x64 (8), 3 = 256x128 (8), 4 = 128x128 (4), 5 = 128x64 (4),
- * 6 = 512x32 (8), 7 = 512x64 (8), 8 = 256x32 (4), 10 = 512x128 (8), 12 = 256x256 (4 waves, tiles loaded
- * from global memory straight into LDS).  A hidden size that is not a multiple of 64 always runs on
+ * 6 = 512x32 (8), 7 = 512x64 (8), 8 = 256x32 (4), 10 = 512x128 (8), 12 = 256x256 and 13 = 256x128 (4 waves,
+ * tiles loaded from global memory straight into LDS).  A hidden size that is not a multiple of 64 always runs on
  * shapes 8, 5 or 4 (by batch size). */
 #define FS_TUNE_WGS_PER_CU(n) (((uint32_t)(n) & 0xFu) << 16)
 #define FS_TUNE_TILE_SHAPE(n) FS_TUNE_WGS_PER_CU(n)

@@ -32,9 +32,10 @@ fs_status launch_dma(const Stage1Params& p, hipStream_t st)
 
 }  // namespace
 
-// 256 vocabulary rows x 256 batch rows per workgroup
-fs_status launch_stage1_dma(const Stage1Params& p, bool full, hipStream_t st)
+// 256 vocabulary rows x 256 (or 128) batch rows per workgroup
+fs_status launch_stage1_dma(const Stage1Params& p, bool full, int batch_tile, hipStream_t st)
 {
+    if (batch_tile == 128) return full ? launch_dma<DmaCfg<128>, true>(p, st) : launch_dma<DmaCfg<128>, false>(p, st);
     return full ? launch_dma<DmaCfg<256>, true>(p, st) : launch_dma<DmaCfg<256>, false>(p, st);
 }
 

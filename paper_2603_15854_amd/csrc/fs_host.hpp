@@ -60,13 +60,13 @@ struct PerDevice {
 inline int num_tiles(int V) { return (V + kVocabTile - 1) / kVocabTile; }
 
 // Tile shape (FS_TUNE_TILE_SHAPE number) the tiled kernel takes for (B, V) on `cus` compute units.
-int pick_tile_shape(int B, int V, int cus);
+int pick_tile_shape(int B, int D, int V, int cus);
 
 // Stage-1 launchers, one per kernel family / translation unit.  `shape` = 0: automatic.
 fs_status launch_stage1_splitk(const Stage1Params& p, bool full, int wgs_per_cu, hipStream_t st);
 fs_status launch_stage1_tiled(const Stage1Params& p, int shape, hipStream_t st);
 fs_status launch_stage1_tiled_full(const Stage1Params& p, int shape, hipStream_t st);
-fs_status launch_stage1_dma(const Stage1Params& p, bool full, hipStream_t st);
+fs_status launch_stage1_dma(const Stage1Params& p, bool full, int batch_tile, hipStream_t st);
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
 // truncated supports (fs_topk.hip)

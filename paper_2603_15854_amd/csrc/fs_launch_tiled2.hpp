@@ -47,6 +47,7 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 //  10: 512 x 128  8 waves, one per CU, one register set of prefetch (128 accumulator VGPRs, 160 KB of LDS)
 //  12: 256 x 256  4 waves, the kernel with direct global -> LDS loads of fs_stage1_dma.hpp (another
 //      translation unit); 9 was the 256 x 256 shape of this kernel, which 12 replaced
+//  13: 256 x 128  the same kernel with 128 batch rows per workgroup
 using Shape1 = Tiled2Cfg<32, 4, 1, 4>;
 using Shape2 = Tiled2Cfg<64, 4, 2, 2, 2, 256>;
 using Shape3 = Tiled2Cfg<128, 4, 2, 1, 2, 256>;
@@ -67,7 +68,7 @@ fs_status launch_tiled2_ragged(const Stage1Params& p, hipStream_t st)
     return launch_tiled2<Shape4, FULL, WB, false, true>(p, st);
 }
 
-// bf16 weights.  `shape` = 0 picks by pick_tile_shape; 1..8, 10, 12 force one shape (tuning aid and
+// bf16 weights.  `shape` = 0 picks by pick_tile_shape; 1..8, 10, 12, 13 force one shape (tuning aid and
 // tiling-invariance tests; honoured for whole-K-step hidden sizes only).
 template <bool FULL>
 fs_status launch_tiled2_bf16(const Stage1Params& p, int shape, hipStream_t st)
@@ -77,7 +78,7 @@ fs_status launch_tiled2_bf16(const Stage1Params& p, int shape, hipStream_t st)
         int cus = 0;
         const fs_status ds = current_device(nullptr, &cus);
         if (ds != FS_OK) return ds;
-        shape = pick_tile_shape(p.B, p.V, cus);
+        shape = pick_tile_shape(p.B, p.D, p.V, cus);
     }
     switch (shape) {
     case 1: return launch_tiled2<Shape1, FULL>(p, st);
@@ -89,7 +90,8 @@ fs_status launch_tiled2_bf16(const Stage1Params& p, int shape, hipStream_t st)
     case 7: return launch_tiled2<Shape7, FULL>(p, st);
     case 8: return launch_tiled2<Shape8, FULL>(p, st);
     case 10: return launch_tiled2<Shape10, FULL>(p, st);
-    case 12: return launch_stage1_dma(p, FULL, st);
+    case 12: return launch_stage1_dma(p, FULL, 256, st);
+    case 13: return launch_stage1_dma(p, FULL, 128, st);
     default: break;
     }
     return FS_ERR_UNSUPPORTED;

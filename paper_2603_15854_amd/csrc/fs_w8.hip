@@ -31,7 +31,7 @@ fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStre
         int cus = 0;
         const fs_status ds = current_device(nullptr, &cus);
         if (ds != FS_OK) return ds;
-        shape = pick_tile_shape(p.B, p.V, cus);
+        shape = pick_tile_shape(p.B, 0, p.V, cus);   // hidden size 0: only shapes this kernel family has
     }
     switch (shape) {
     case 1: return launch_tiled2<Tiled2Cfg<32, 4, 1, 2>, false, 1, true>(p, st);

@@ -159,6 +159,7 @@ def test_kernel_choice_by_shape():
     assert [kc(B, 4096, 128256) for B in (1, 16)] == [0, 0]
     assert [kc(B, 4096, 128256) for B in (17, 32, 64, 128, 129, 256, 512)] == [6, 6, 7, 10, 12, 12, 12]
     assert kc(16, 8192, 128256) == 6 and kc(1, 7168, 129280) == 6          # wide hidden sizes: tiled
+    assert kc(128, 8192, 128256) == 13 and kc(128, 7168, 129280) == 13      # ... and direct-to-LDS loads at B <= 128
     # the choices measured fastest on the machine (D = 4096, 256 CUs)
     assert [kc(32, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [1, 8, 6, 1, 6]
     assert [kc(64, 4096, V) for V in (32000, 50304, 100352, 152064)] == [5, 2, 7, 5]

@@ -155,7 +155,7 @@ def test_larger_batches_and_wide_hidden_tiled(fs, orc, shape):
         _small_case(fs, orc, B, D, V, variant, data_seed=70 + B, tune=tune)
 
 
-@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12])
+@pytest.mark.parametrize("tile_shape", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 13])
 def test_every_tile_shape_of_the_tiled_kernel(fs, orc, tile_shape):
     # the shapes the launcher can pick (128/256/512 vocabulary rows x 32/64/128 batch rows), each on
     # ragged V, B smaller and larger than its batch tile, and a K tail (D % 64 != 0)
@@ -387,7 +387,7 @@ def test_config_c4_compute_leaning_peaky(fs, orc):
     assert (ui.cpu().numpy() != fi).sum() <= 2
 
 
-@pytest.mark.parametrize("B", [1, 8, 64, 256, 512])
+@pytest.mark.parametrize("B", [1, 8, 64, 128, 256, 512])
 def test_config_c5_wide_hidden(fs, orc, B):
     _full_config(fs, orc, "C5", B)
 
