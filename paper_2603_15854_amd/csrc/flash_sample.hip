@@ -603,40 +603,26 @@ fs_status flash_sample_gumbel_transform(const uint32_t* words, int n, float* g_o
 namespace {
 
 struct TopkWs {
-    uint64_t* cand;        // [B, T * kt]   first-pass candidates (fused path only)
+    uint64_t* cand;        // [B, T * m]   stage-1 candidates (fused path only)
     uint64_t* buf[2];      // intermediate selection levels
-    uint64_t* rowbuf;      // [B, k (1 + kTopkFixMax)]   second selection of the fused path (k > kTopkTileM only)
-    int32_t* tile_flag;    // [T]
-    int32_t* n_fix;        // [B]
-    int32_t* fix_tiles;    // [B, kTopkFixMax]
     size_t bytes;
 };
 
-// candidates a tile emits in the fused first pass
+// candidates a tile emits in the fused form
 int topk_tile_m(int k) { return k < kTopkTileM ? k : kTopkTileM; }
 
 TopkWs carve_topk(void* ws, int B, int V, int k, bool fused)
 {
-    const int T = num_tiles(V);
-    const int n_cand = fused ? T * topk_tile_m(k) : V;
+    const int n_cand = fused ? num_tiles(V) * topk_tile_m(k) : V;
     const TopkPlan pl = topk_plan(B, n_cand, k);
-    const bool two_pass = fused && k > kTopkTileM;
     const size_t cand = fused ? align_up((size_t)B * (size_t)n_cand * 8, 256) : 0;
     const size_t b0 = align_up(pl.buf_words[0] * 8, 256), b1 = align_up(pl.buf_words[1] * 8, 256);
-    const size_t rowbuf = two_pass ? align_up((size_t)B * k * (1 + kTopkFixMax) * 8, 256) : 0;
-    const size_t flag = two_pass ? align_up((size_t)T * 4, 256) : 0;
-    const size_t nfix = two_pass ? align_up((size_t)B * 4, 256) : 0;
-    const size_t tiles = two_pass ? align_up((size_t)B * kTopkFixMax * 4, 256) : 0;
     unsigned char* q = static_cast<unsigned char*>(ws);
     TopkWs w;
-    w.cand = reinterpret_cast<uint64_t*>(q); q += cand;
-    w.buf[0] = reinterpret_cast<uint64_t*>(q); q += b0;
-    w.buf[1] = reinterpret_cast<uint64_t*>(q); q += b1;
-    w.rowbuf = reinterpret_cast<uint64_t*>(q); q += rowbuf;
-    w.tile_flag = reinterpret_cast<int32_t*>(q); q += flag;
-    w.n_fix = reinterpret_cast<int32_t*>(q); q += nfix;
-    w.fix_tiles = reinterpret_cast<int32_t*>(q); q += tiles;
-    w.bytes = cand + b0 + b1 + rowbuf + flag + nfix + tiles;
+    w.cand = reinterpret_cast<uint64_t*>(q);
+    w.buf[0] = reinterpret_cast<uint64_t*>(q + cand);
+    w.buf[1] = reinterpret_cast<uint64_t*>(q + cand + b0);
+    w.bytes = cand + b0 + b1;
     return w;
 }
 
@@ -683,25 +669,13 @@ fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int
     const int m = topk_tile_m(k);
     Stage1Params p = make_params(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset, flags);
     p.topk_out = ws.cand; p.topk_k = m; p.topk_mode = mode;
-    const bool two_pass = k > m;
-    if (two_pass) p.tile_flag = ws.tile_flag;
-    s = launch_stage1_topk(p, 1, st);
+    s = launch_stage1_topk(p, st);
     if (s != FS_OK) return s;
     const int n_cand = p.T * m;
     const TopkFinish fin = {top_p, mode, seed, row_seeds, row_offset, epi_bits(flags), out_idx, out_val, topk_val, topk_idx, n_kept};
-    const int rb_stride = k * (1 + kTopkFixMax);
-    TopkFix fix = {};
-    if (two_pass)
-        fix = TopkFix{ws.cand, p.T, m, vocab_offset, ws.tile_flag, ws.n_fix, ws.fix_tiles, ws.rowbuf, rb_stride, nullptr};
-    s = launch_topk_reduce(ws.cand, nullptr, B, n_cand, (int64_t)n_cand, 0, k, ws.buf[0], ws.buf[1], fin, two_pass ? &fix : nullptr, st);
-    if (s != FS_OK || !two_pass) return s;
-    // second pass: the listed tiles in full (the other workgroups leave at once), then the listed rows again
-    p.n_fix = ws.n_fix; p.fix_tiles = ws.fix_tiles; p.rowbuf = ws.rowbuf; p.rowbuf_stride = rb_stride; p.topk_kfull = k;
-    s = launch_stage1_topk(p, 2, st);
-    if (s != FS_OK) return s;
-    TopkFix gate = {};
-    gate.row_gate = ws.n_fix;
-    return launch_topk_reduce(ws.rowbuf, nullptr, B, rb_stride, (int64_t)rb_stride, 0, k, nullptr, nullptr, fin, &gate, st);
+    // more than m wanted: the last selection level checks for tiles that hold more winners than they emitted
+    const TopkCrowd crowd = {ws.cand, p.T, m, vocab_offset, p.H, p.W, D, V, temperature};
+    return launch_topk_reduce(ws.cand, nullptr, B, n_cand, (int64_t)n_cand, 0, k, ws.buf[0], ws.buf[1], fin, k > m ? &crowd : nullptr, st);
 }
 
 fs_status flash_sample_topk_unfused(const void* hidden, const void* W, int B, int D, int V,

@@ -37,21 +37,11 @@ struct Stage1Params {
     const float* w_scale = nullptr;   // [V] fp32 per-row scale of the logits, or nullptr (= 1)
     // epilogue mode bits (FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG of the C ABI)
     uint32_t epi_flags = 0;
-    // Truncated supports (kernels instantiated with TOPK != 0 only).
-    // TOPK = 1, first pass: the topk_k best candidates of every (row, 128-id tile), sorted, packed
-    // (fs_topk_common.hpp), at topk_out[(b T + t) topk_k + j]; clears tile_flag[t].
-    // TOPK = 2, second pass: for the tiles with tile_flag[t] set, and the rows b that list t in
-    // fix_tiles[b kTopkFixMax + s], s < n_fix[b]: the tile's topk_kfull best candidates, sorted, at
-    // rowbuf[b rowbuf_stride + topk_kfull (1 + s) + j].
+    // Truncated supports (kernels instantiated with TOPK only): the topk_k best candidates of every
+    // (row, 128-id tile), sorted, packed (fs_topk_common.hpp), at topk_out[(b T + t) topk_k + j]
     uint64_t* topk_out = nullptr;
     int topk_k = 0;
     int topk_mode = 0;                // 0: key = y / tau; 1: key = y / tau + Gumbel noise
-    int32_t* tile_flag = nullptr;     // [T]
-    const int32_t* n_fix = nullptr;   // [B]
-    const int32_t* fix_tiles = nullptr;   // [B, kTopkFixMax]
-    uint64_t* rowbuf = nullptr;       // [B, rowbuf_stride]
-    int rowbuf_stride = 0;
-    int topk_kfull = 0;
 };
 
 constexpr uint32_t kEpiGreedy = 0x1u;     // no noise: the candidate is the arg max of the transformed logits

@@ -70,7 +70,7 @@ fs_status launch_stage1_dma(const Stage1Params& p, bool full, int batch_tile, hi
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
 // truncated supports (fs_topk.hip)
-fs_status launch_stage1_topk(const Stage1Params& p, int pass, hipStream_t st);
+fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st);
 struct TopkPlan {                 // selection levels for rows of N candidates (topk_plan)
     static constexpr int kMaxLevels = 4;
     int levels;
@@ -80,9 +80,9 @@ struct TopkPlan {                 // selection levels for rows of N candidates (
 };
 TopkPlan topk_plan(int B, int N, int k);
 // keys: how stored logits become keys (input = fp32 [B, N] logits), or null (input = packed candidates);
-// fix: the fused path's check for tiles that need all their candidates, or null
+// crowd: the fused path's check for tiles that hold more winners than they emitted, or null
 fs_status launch_topk_reduce(const void* in, const TopkKeys* keys, int B, int N, int64_t row_stride, int32_t id_base, int k,
-                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkFix* fix, hipStream_t st);
+                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkCrowd* crowd, hipStream_t st);
 fs_status launch_mxfp4_decode(const uint32_t* codes, const uint8_t* scales, int n8, float* out, hipStream_t st);
 
 }  // namespace fs

@@ -11,14 +11,14 @@ namespace fs {
 // BOTH: also build the form with cacheable W loads for launches with several batch tiles (the
 // workgroups that share a W tile then run on one XCD and the second read hits its L2); without it
 // such launches stream W with non-temporal loads like single-batch-tile ones.
-template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = false, bool BOTH = false, int TOPK = 0>
+template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = false, bool BOTH = false, bool TOPK = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
     if (!KRAG && p.D % (WCODES ? 128 : 64) != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
     // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles; the
     // per-tile top-k epilogue stages the keys of the whole tile ([BT][VT + 4] floats)
     constexpr size_t kLdsLoop = 2 * ((size_t)Cfg::kWBytes + (WCODES ? 2 : 1) * (size_t)Cfg::kHBytes);
-    constexpr size_t kLdsKeys = TOPK != 0 ? (size_t)Cfg::BT * (Cfg::VT + 4) * 4 : 0;
+    constexpr size_t kLdsKeys = TOPK ? (size_t)Cfg::BT * (Cfg::VT + 4) * 4 : 0;
     constexpr size_t kLds = kLdsLoop > kLdsKeys ? kLdsLoop : kLdsKeys;
     static_assert(kLds <= kLdsPerCU, "tile shape does not fit LDS");
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;

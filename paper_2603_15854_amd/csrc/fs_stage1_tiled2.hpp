@@ -86,15 +86,12 @@ struct Tiled2Cfg {
 // TOPK (Section "Top-k, Nucleus Sampling, and Masking": per-tile candidates): instead of one
 // candidate per (row, 128-id tile) the epilogue writes several, sorted and packed.  The keys of the
 // workgroup tile are staged in LDS as [BT][VT + 4] floats and one wave handles a (row, candidate
-// tile) unit.  TOPK = 1: the p.topk_k <= 8 best of every unit (wave_top_m).  TOPK = 2: only the tiles
-// flagged in p.tile_flag run (the other workgroups leave at once); the units listed in p.fix_tiles
-// are sorted completely (wave_sort128_desc) and their p.topk_kfull best written.  Both passes use
-// the same tile shape and K order, so the keys of the second pass equal those of the first bit for bit.
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, int TOPK = 0>
+// tile) unit, four units at once: the p.topk_k <= 8 best of every unit (wave_top_m).
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, bool TOPK = false>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
-    static_assert(TOPK == 0 || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
+    static_assert(!TOPK || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
     static_assert(!WCODES || WB == 1, "codes in LDS only for one-byte W elements");
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
     constexpr int KS = WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
@@ -130,18 +127,6 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     const int tile = group * 8 + (rem & 7);      // macro tile of VT vocabulary rows
     const int bt = rem >> 3;
     if (tile * VT >= V) return;                  // whole workgroup leaves: no barrier is skipped
-    if constexpr (TOPK == 2) {
-        bool any = false;
-        for (int ct = 0; ct < Cfg::kCandTiles; ++ct) {
-            const int ctile = tile * Cfg::kCandTiles + ct;
-            if (ctile < p.T && p.tile_flag[ctile] != 0) any = true;
-        }
-        if (!any) return;                        // uniform over the workgroup
-    }
-    if constexpr (TOPK == 1) {
-        if (bt == 0 && p.tile_flag && (int)threadIdx.x < Cfg::kCandTiles && tile * Cfg::kCandTiles + (int)threadIdx.x < p.T)
-            p.tile_flag[tile * Cfg::kCandTiles + (int)threadIdx.x] = 0;
-    }
     const int b0 = bt * BT;
     const int tile_row0 = tile * VT;
 
@@ -299,7 +284,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     for (; base + 2 * GS <= nk; base += 2 * GS) body(base, std::false_type{});
     if (base < nk) body(base, std::true_type{});
 
-    if constexpr (TOPK != 0) {
+    if constexpr (TOPK) {
         // the last K step ended with a barrier: the tile buffers are free
         constexpr int KSTRIDE = VT + 4;                   // floats per batch row of the key array
         float* keys = reinterpret_cast<float*>(smem);
@@ -325,46 +310,27 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
         __syncthreads();
         constexpr int NUNIT = BT * Cfg::kCandTiles;          // unit = (batch row, candidate tile)
-        if constexpr (TOPK == 1) {
-            constexpr int U = 4;                             // units a wave works on at once
-            static_assert(NUNIT % (Cfg::kWaves * U) == 0, "units per wave");
-            const int kt = p.topk_k;
-            for (int ub = wave * U; ub < NUNIT; ub += Cfg::kWaves * U) {
-                uint32_t k0[U], k1[U];
-                int32_t id0[U];
+        constexpr int U = 4;                                 // units a wave works on at once
+        static_assert(NUNIT % (Cfg::kWaves * U) == 0, "units per wave");
+        const int kt = p.topk_k;
+        for (int ub = wave * U; ub < NUNIT; ub += Cfg::kWaves * U) {
+            uint32_t k0[U], k1[U];
+            int32_t id0[U];
 #pragma unroll
-                for (int q = 0; q < U; ++q) {
-                    const int u = ub + q, bl = u % BT, ct = u / BT;
-                    const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-                    k0[q] = e0 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + lane]) : 0u;
-                    k1[q] = e1 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane]) : 0u;
-                    id0[q] = p.vocab_offset + tile_row0 + ct * kVocabTile;
-                }
-                uint64_t res[U];
-                wave_top_m<U>(k0, k1, id0, kt, lane, res);
-#pragma unroll
-                for (int q = 0; q < U; ++q) {
-                    const int u = ub + q, bl = u % BT, ct = u / BT;
-                    const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
-                    if (b < B && ctile < T && lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = res[q];
-                }
-            }
-        } else {
-            for (int u = wave; u < NUNIT; u += Cfg::kWaves) {
-                const int bl = u % BT, ct = u / BT;
-                const int b = b0 + bl;
-                const int ctile = tile * Cfg::kCandTiles + ct;
-                if (b >= B || ctile >= T || p.tile_flag[ctile] == 0) continue;      // wave-uniform
+            for (int q = 0; q < U; ++q) {
+                const int u = ub + q, bl = u % BT, ct = u / BT;
                 const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-                const int nf = p.n_fix[b];
-                for (int sl = 0; sl < nf; ++sl) {
-                    if (p.fix_tiles[b * kTopkFixMax + sl] != ctile) continue;
-                    uint64_t a0 = e0 < V ? topk_pack(keys[bl * KSTRIDE + ct * kVocabTile + lane], p.vocab_offset + e0) : kTopkPad;
-                    uint64_t a1 = e1 < V ? topk_pack(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane], p.vocab_offset + e1) : kTopkPad;
-                    wave_sort128_desc(a0, a1, lane);
-                    const int kf = p.topk_kfull;
-                    if (lane < kf) p.rowbuf[(size_t)b * p.rowbuf_stride + (size_t)kf * (1 + sl) + lane] = a0;
-                }
+                k0[q] = e0 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + lane]) : 0u;
+                k1[q] = e1 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane]) : 0u;
+                id0[q] = p.vocab_offset + tile_row0 + ct * kVocabTile;
+            }
+            uint64_t res[U];
+            wave_top_m<U>(k0, k1, id0, kt, lane, res);
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int u = ub + q, bl = u % BT, ct = u / BT;
+                const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
+                if (b < B && ctile < T && lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = res[q];
             }
         }
         return;

@@ -5,19 +5,13 @@
 
 namespace fs {
 
-// Stage 1 with the per-tile candidate epilogue, first (pass = 1) or second (pass = 2) pass.  Three
-// tile shapes (by batch size), whole K steps only; both passes of a call take the same shape.
-fs_status launch_stage1_topk(const Stage1Params& p, int pass, hipStream_t st)
+// Stage 1 with the per-tile candidate epilogue.  Three tile shapes (by batch size), whole K steps only.
+fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
-    if (pass == 1) {
-        if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, 1>(p, st);   // 512 x 32
-        if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, 1>(p, st);   // 512 x 64
-        return launch_tiled2<Shape3, false, 2, false, false, true, 1>(p, st);                   // 256 x 128, batch tiles XCD-paired
-    }
-    if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, 2>(p, st);
-    if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, 2>(p, st);
-    return launch_tiled2<Shape3, false, 2, false, false, true, 2>(p, st);
+    if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
+    if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
+    return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);                   // 256 x 128, batch tiles XCD-paired
 }
 
 // Selection levels for rows of N candidates: every level cuts a row into chunks of at most kSelChunk
@@ -53,12 +47,12 @@ TopkPlan topk_plan(int B, int N, int k)
 // The k best of every row of [B, N] candidates, then the nucleus rule and the draw.  buf0 / buf1:
 // topk_plan's buffers.
 fs_status launch_topk_reduce(const void* in, const TopkKeys* keys, int B, int N, int64_t row_stride, int32_t id_base, int k,
-                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkFix* fix, hipStream_t st)
+                             uint64_t* buf0, uint64_t* buf1, const TopkFinish& fin, const TopkCrowd* crowd, hipStream_t st)
 {
     const TopkPlan pl = topk_plan(B, N, k);
     if (pl.chunks[pl.levels - 1] != 1 || B > 65535) return FS_ERR_SHAPE;
     const TopkKeys kp = keys ? *keys : TopkKeys{};
-    const TopkFix none = {};
+    const TopkCrowd none = {};
     const void* src = in;
     for (int lvl = 0; lvl < pl.levels; ++lvl) {
         const int c = pl.chunks[lvl], n = pl.n[lvl];
@@ -69,13 +63,13 @@ fs_status launch_topk_reduce(const void* in, const TopkKeys* keys, int B, int N,
         const bool from_keys = keys && lvl == 0;
         const int64_t stride = lvl == 0 ? row_stride : (int64_t)n;
         const int32_t base = lvl == 0 ? id_base : 0;
-        const TopkFix fx = last && fix ? *fix : none;
         fs_status s;
         const dim3 grid(c, B), block(256);
-        if (from_keys && last) s = launch(topk_select_kernel<true, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
-        else if (from_keys) s = launch(topk_select_kernel<true, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
-        else if (last) s = launch(topk_select_kernel<false, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
-        else s = launch(topk_select_kernel<false, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, fx);
+        if (from_keys && last) s = launch(topk_select_kernel<true, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, none);
+        else if (from_keys) s = launch(topk_select_kernel<true, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, none);
+        else if (last && crowd) s = launch(topk_select_kernel<false, true, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, *crowd);
+        else if (last) s = launch(topk_select_kernel<false, true>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, none);
+        else s = launch(topk_select_kernel<false, false>, grid, block, 0, st, src, stride, n, base, chunk_len, k, dst, kp, fin, none);
         if (s != FS_OK) return s;
         src = dst;
     }

@@ -14,7 +14,7 @@ namespace fs {
 
 constexpr int kTopkMax = 64;          // FS_TOPK_MAX_K
 constexpr int kTopkTileM = 8;         // candidates a 128-id tile emits in the fused first pass
-constexpr int kTopkFixMax = kTopkMax / kTopkTileM;   // tiles of one row that can need all their candidates
+constexpr int kTopkCrowdMax = kTopkMax / kTopkTileM;   // tiles of one row that can need all their keys
 constexpr int kTopkTruncate = 0, kTopkGumbel = 1;
 
 // What the last selection level does with the k sorted candidates of a row.
@@ -43,22 +43,20 @@ struct TopkKeys {
     uint32_t epi_flags;
 };
 
-// Fused path with more than kTopkTileM candidates wanted: the first pass kept only the m best of
-// every tile.  A tile whose m-th candidate is among the k winners of a row may hold more of the true
-// top k; every other tile cannot (what it did not emit comes after its m-th, which already lost).
-// The last selection level finds those tiles (at most k / m per row), lists them for the second
-// stage-1 pass, and prepares the row's second selection: rowbuf[b] = k winners (those of listed
-// tiles blanked) followed by kTopkFixMax runs of k words, blank until the second pass fills them.
-struct TopkFix {
-    const uint64_t* cand;     // [B, T, m] first-pass candidates; null: nothing to check
+// Fused path with more than kTopkTileM candidates wanted: stage 1 kept only the m best of every
+// tile.  A tile whose m-th candidate is among the k winners of a row may hold more of the true top
+// k; every other tile cannot (what it did not emit comes after its m-th, which already lost).  The
+// last selection level finds those tiles (at most k / m per row, none for typical logits),
+// recomputes their 128 keys from the row's hidden state and W (plain fp32 dot products), and
+// selects again among the winners of the other tiles and those keys.
+struct TopkCrowd {
+    const uint64_t* cand;     // [B, T, m] stage-1 candidates; null: nothing to check
     int T, m;
     int32_t vocab_offset;
-    int32_t* tile_flag;       // [T]
-    int32_t* n_fix;           // [B]
-    int32_t* fix_tiles;       // [B, kTopkFixMax]
-    uint64_t* rowbuf;         // [B, rowbuf_stride]
-    int rowbuf_stride;
-    const int32_t* row_gate;  // second selection: rows with row_gate[b] == 0 leave at once; null: all rows run
+    const uint16_t* H;        // [B, D] bf16
+    const uint16_t* W;        // [V, D] bf16
+    int D, V;
+    const float* tau;         // [B]
 };
 
 __device__ __forceinline__ float key_sanitize(float k) { return k == k ? k : -__builtin_inff(); }

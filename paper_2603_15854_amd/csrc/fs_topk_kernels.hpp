@@ -104,6 +104,8 @@ __device__ __forceinline__ void topk_finish(const TopkFinish& f, int b, int k, i
 //          otherwise packed candidates
 //   FINAL  one chunk per row: nucleus rule and draw follow (topk_finish); otherwise the k words go
 //          to out[(b * chunks + c) * k + j], sorted, padded
+//   CROWD  (with FINAL, fused path, k > kTopkTileM) before the draw, look for tiles that hold more
+//          winners than stage 1 emitted (TopkCrowd), recompute their keys and select again
 //
 // Every thread holds kSelE candidates of the chunk in registers.  The k-th largest of the 256
 // per-thread maxima is a lower bound of the chunk's k-th largest candidate (k threads hold one at
@@ -133,19 +135,19 @@ __device__ __forceinline__ void lds_sort_desc(uint64_t* s, int n, int tid)   // 
     }
 }
 
-template <bool KEYS, bool FINAL>
+template <bool KEYS, bool FINAL, bool CROWD = false>
 __global__ void __launch_bounds__(256)
 topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32_t id_base, int chunk_len, int k,
-                   uint64_t* __restrict__ out, TopkKeys kp, TopkFinish fin, TopkFix fix)
+                   uint64_t* __restrict__ out, TopkKeys kp, TopkFinish fin, TopkCrowd crowd)
 {
     __shared__ uint64_t s_list[kSelList];
     __shared__ uint64_t s_max[256];
     __shared__ uint64_t s_thr;
     __shared__ int s_count;
-    __shared__ int s_nfix;
+    __shared__ int s_ncrowd;
+    __shared__ int s_crowd_tile[kTopkCrowdMax];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.y, c = blockIdx.x;
-    if (FINAL && fix.row_gate && fix.row_gate[b] == 0) return;       // uniform over the workgroup
     const int begin = c * chunk_len;
     int end = begin + chunk_len;
     end = end < N ? end : N;
@@ -237,39 +239,97 @@ topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32
     __syncthreads();
     if constexpr (!FINAL) {
         if (tid < k) out[((size_t)b * gridDim.x + c) * (size_t)k + tid] = s_list[tid];
-    } else {
+    } else if constexpr (!CROWD) {
         if (tid < kWave) {
             const uint64_t w = tid < k ? s_list[tid] : kTopkPad;
             topk_finish(fin, b, k, tid, topk_key(w), topk_id(w));
-            if (fix.cand) {                      // uniform over the launch
-                int t = -1;
-                bool flagged = false;
-                if ((uint32_t)w != 0u) {
-                    t = (topk_id(w) - fix.vocab_offset) >> 7;
-                    flagged = fix.cand[((size_t)b * fix.T + t) * (size_t)fix.m + (fix.m - 1)] == w;
+        }
+    } else {
+        // which winners are the m-th (last) candidate of their tile?
+        if (tid < kWave) {
+            const uint64_t w = tid < k ? s_list[tid] : kTopkPad;
+            int t = -1;
+            bool flagged = false;
+            if ((uint32_t)w != 0u) {
+                t = (topk_id(w) - crowd.vocab_offset) >> 7;
+                flagged = crowd.cand[((size_t)b * crowd.T + t) * (size_t)crowd.m + (crowd.m - 1)] == w;
+            }
+            const uint64_t fb = __ballot(flagged);
+            const int ncrowd = (int)__builtin_popcountll(fb);        // <= k / m: such a tile holds m winners
+            if (tid == 0) s_ncrowd = ncrowd;
+            if (ncrowd == 0) {
+                topk_finish(fin, b, k, tid, topk_key(w), topk_id(w));
+            } else {
+                if (flagged) s_crowd_tile[(int)__builtin_popcountll(fb & ((1ull << tid) - 1ull))] = t;
+                bool listed = false;
+                for (uint64_t r = fb; r != 0ull; r &= r - 1ull) {
+                    const int tf = __shfl(t, (int)__builtin_ctzll(r), kWave);
+                    listed = listed || t == tf;
                 }
-                const uint64_t fb = __ballot(flagged);
-                const int nfix = (int)__builtin_popcountll(fb);      // <= k / m: a listed tile has m winners
-                if (tid == 0) { fix.n_fix[b] = nfix; s_nfix = nfix; }
-                if (nfix != 0) {
-                    if (flagged) {
-                        const int sl = (int)__builtin_popcountll(fb & ((1ull << tid) - 1ull));
-                        fix.fix_tiles[b * kTopkFixMax + sl] = t;
-                        fix.tile_flag[t] = 1;
-                    }
-                    bool listed = false;
-                    for (uint64_t r = fb; r != 0ull; r &= r - 1ull) {
-                        const int tf = __shfl(t, (int)__builtin_ctzll(r), kWave);
-                        listed = listed || t == tf;
-                    }
-                    if (tid < k) fix.rowbuf[(size_t)b * fix.rowbuf_stride + tid] = listed ? kTopkPad : w;
-                }
+                s_list[tid] = listed ? kTopkPad : w;        // the listed tiles come back whole below
             }
         }
-        if (fix.cand) {
-            __syncthreads();
-            if (s_nfix != 0)
-                for (int t = tid; t < kTopkFixMax * k; t += 256) fix.rowbuf[(size_t)b * fix.rowbuf_stride + k + t] = kTopkPad;
+        __syncthreads();
+        const int ncrowd = s_ncrowd;
+        if (ncrowd == 0) return;                                     // uniform over the workgroup
+        // keys of the listed tiles: wave w takes rows 32 w .. 32 w + 31 of a tile, its lanes split K
+        const int D = crowd.D;
+        const uint16_t* h = crowd.H + (size_t)b * D;
+        const float inv_tau = 1.0f / crowd.tau[b];
+        const uint64_t sd = fin.row_seeds ? fin.row_seeds[b] : fin.seed;
+        for (int f = 0; f < ncrowd; ++f) {
+            const int v0 = s_crowd_tile[f] * kVocabTile + wave * 32;
+            float acc[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) acc[i] = 0.0f;
+            for (int kc = lane * 8; kc < D; kc += 512) {
+                const uint4 hv = *reinterpret_cast<const uint4*>(h + kc);
+                const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+                for (int i = 0; i < 32; ++i) {
+                    int row = v0 + i;
+                    row = row < crowd.V - 1 ? row : crowd.V - 1;
+                    const uint4 wv = *reinterpret_cast<const uint4*>(crowd.W + (size_t)row * D + kc);
+                    const uint32_t ww[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc[i] = fmaf(__uint_as_float(hw[q] << 16), __uint_as_float(ww[q] << 16), acc[i]);
+                        acc[i] = fmaf(__uint_as_float(hw[q] & 0xFFFF0000u), __uint_as_float(ww[q] & 0xFFFF0000u), acc[i]);
+                    }
+                }
+            }
+            float y = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                float a = acc[i];
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) a += __shfl_xor(a, off, kWave);
+                y = lane == i ? a : y;
+            }
+            if (lane < 32) {
+                const int v = v0 + lane;
+                const int32_t id = crowd.vocab_offset + v;
+                float g = 0.0f;
+                if (fin.mode == kTopkGumbel) {
+                    uint32_t pw[4];
+                    philox4x32_10((uint32_t)id >> 2, (uint32_t)(uint64_t)(fin.row_offset + b), 0u, 0u, (uint32_t)sd, (uint32_t)(sd >> 32), pw);
+                    const uint32_t q = (uint32_t)id & 3u;
+                    const uint32_t r = q == 0u ? pw[0] : q == 1u ? pw[1] : q == 2u ? pw[2] : pw[3];
+                    g = (fin.epi_flags & kEpiExactLog) ? gumbel_from_word_exact(r) : gumbel_from_word(r);
+                }
+                s_list[64 + f * kVocabTile + wave * 32 + lane] = v < crowd.V ? topk_pack(fmaf(y, inv_tau, g), id) : kTopkPad;
+            }
+        }
+        const int n = 64 + ncrowd * kVocabTile;
+        int n2 = 256;
+        while (n2 < n) n2 <<= 1;
+        for (int t2 = k + tid; t2 < 64; t2 += 256) s_list[t2] = kTopkPad;
+        for (int t2 = n + tid; t2 < n2; t2 += 256) s_list[t2] = kTopkPad;
+        __syncthreads();
+        lds_sort_desc(s_list, n2, tid);                               // ends with a barrier
+        if (tid < kWave) {
+            const uint64_t w = tid < k ? s_list[tid] : kTopkPad;
+            topk_finish(fin, b, k, tid, topk_key(w), topk_id(w));
         }
     }
 }
