@@ -8,12 +8,12 @@ namespace fs {
 
 // nw waves of kpw k-steps each; the grid is as many workgroups as are resident at once
 // (registers and LDS decide), or wgs_per_cu_override per compute unit when that is > 0.
-template <class Cfg, bool FULL = false>
+template <class Cfg, bool FULL = false, bool TOPK = false>
 fs_status launch_splitk(const Stage1Params& p, int kpw, int nw, int wgs_per_cu_override, hipStream_t st)
 {
-    const size_t lds = Cfg::lds_bytes(nw);
+    const size_t lds = TOPK ? Cfg::lds_bytes_topk(nw) : Cfg::lds_bytes(nw);
     if (nw > Cfg::kMaxWaves || lds > kLdsPerCU) return FS_ERR_UNSUPPORTED;
-    auto kernel = stage1_splitk_kernel<Cfg, FULL>;
+    auto kernel = stage1_splitk_kernel<Cfg, FULL, TOPK>;
     int dev = 0, cus = 0;
     const fs_status ds = current_device(&dev, &cus);
     if (ds != FS_OK) return ds;

@@ -16,4 +16,14 @@ fs_status launch_stage1_splitk(const Stage1Params& p, bool full, int wgs_per_cu,
                 : launch_splitk<Cfg, false>(p, kpw, nw, wgs_per_cu, st);
 }
 
+// The same kernel with the per-tile candidate epilogue of the truncated-support path.
+fs_status launch_stage1_splitk_topk(const Stage1Params& p, hipStream_t st)
+{
+    const int ksteps = (p.D + 31) / 32;
+    if (p.B > 16 || ksteps > 32 * 4) return FS_ERR_UNSUPPORTED;
+    const int nw = (ksteps + 31) / 32;
+    const int kpw = (ksteps + nw - 1) / nw;
+    return launch_splitk<SplitKCfg<32, 8, 2, 4>, false, true>(p, kpw, nw, 0, st);
+}
+
 }  // namespace fs

@@ -23,6 +23,7 @@
 #pragma once
 
 #include "fs_common.hpp"
+#include "fs_topk_common.hpp"   // wave_top_m
 
 namespace fs {
 
@@ -52,6 +53,9 @@ struct SplitKCfg {
     {
         return (size_t)nw * kStageBytes + (size_t)8 * nw * 1024 + (size_t)nw * 16 * 8 * 2;
     }
+    // per-tile candidate epilogue (TOPK): the keys of the tile, [16 batch columns][128 + 4] floats, behind the rest
+    static constexpr int kKeyStride = kVocabTile + 4;
+    static constexpr size_t lds_bytes_topk(int nw) { return lds_bytes(nw) + (size_t)16 * kKeyStride * 4; }
 };
 
 // End of one vocabulary tile in the split-K kernels.  Every wave has stored its eight partial
@@ -60,11 +64,16 @@ struct SplitKCfg {
 // order (deterministic), scaled if the weights carry per-row scales, optionally stored as logits,
 // and run through the sampling epilogue; after the second one lane per batch column merges the
 // waves' candidates (and log-sum-exp states) and writes the tile's entry of the candidate buffer.
-template <bool FULL, bool ROW_SCALE>
+// TOPK (Section "Top-k, Nucleus Sampling, and Masking", per-tile candidates): the summed keys go to
+// `keys` ([16][128 + 4] floats) instead, and after the second barrier the waves find the p.topk_k <= 8
+// best of each batch column's 128 keys, four columns at a time (wave_top_m), and write them packed.
+template <bool FULL, bool ROW_SCALE, bool TOPK = false>
 __device__ __forceinline__ void splitk_finish_tile(const Stage1Params& p, const RowEpi& repi, const f32x4* partial,
                                                    float2* wave_cand, float2* wave_lse, int nw, int wave,
-                                                   int lane, int tile)
+                                                   int lane, int tile, float* keys = nullptr)
 {
+    static_assert(!TOPK || (!FULL && !ROW_SCALE), "per-tile candidates: bf16 weights, plain transform");
+    constexpr int KSTRIDE = kVocabTile + 4;
     const int n = lane & 15, g = lane >> 4;
     const int B = p.B, V = p.V, T = p.T;
     const int tile_row0 = tile * kVocabTile;
@@ -95,6 +104,37 @@ __device__ __forceinline__ void splitk_finish_tile(const Stage1Params& p, const 
             }
             if (p.cand_val) epilogue_quad<FULL>(p, repi, y, v0, V, best, best_id, lmax, lsum);
         }
+        if constexpr (TOPK) {
+            float gn[4] = {0.f, 0.f, 0.f, 0.f};
+            if (p.topk_mode == kTopkGumbel)
+                gumbel4(repi.seed, repi.row_word, (uint32_t)(p.vocab_offset + v0), gn, (p.epi_flags & kEpiExactLog) != 0u);
+            f32x4 kq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) kq[j] = key_sanitize(fmaf(y[j], repi.inv_tau, gn[j]));
+            *reinterpret_cast<f32x4*>(keys + n * KSTRIDE + r8 * 16 + 4 * g) = kq;
+        }
+    }
+    if constexpr (TOPK) {
+        __syncthreads();   // keys of the tile complete; partial buffer free again
+        constexpr int U = 4;
+        const int kt = p.topk_k;
+        for (int ub = wave * U; ub < 16; ub += nw * U) {      // unit = batch column
+            uint32_t k0[U], k1[U];
+            int32_t id0[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int e0 = tile_row0 + lane, e1 = e0 + 64;
+                k0[q] = e0 < V ? topk_ordered(keys[(ub + q) * KSTRIDE + lane]) : 0u;
+                k1[q] = e1 < V ? topk_ordered(keys[(ub + q) * KSTRIDE + 64 + lane]) : 0u;
+                id0[q] = p.vocab_offset + tile_row0;
+            }
+            uint64_t res[U];
+            wave_top_m<U>(k0, k1, id0, kt, lane, res);
+#pragma unroll
+            for (int q = 0; q < U; ++q)
+                if (ub + q < B && lane < kt) p.topk_out[((size_t)(ub + q) * T + tile) * (size_t)kt + lane] = res[q];
+        }
+        return;
     }
     cand_reduce_lane_groups(best, best_id);
     if (g == 0) wave_cand[wave * 16 + n] = make_float2(best, __int_as_float(best_id));
@@ -126,7 +166,7 @@ __device__ __forceinline__ void splitk_finish_tile(const Stage1Params& p, const 
     }
 }
 
-template <class Cfg, bool FULL = false>
+template <class Cfg, bool FULL = false, bool TOPK = false>
 __global__ void __launch_bounds__(Cfg::kMaxWaves * kWave)
 stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
 {
@@ -160,10 +200,11 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
     float2* wave_cand = reinterpret_cast<float2*>(smem + (size_t)nw * Cfg::kStageBytes +
                                                   (size_t)8 * nw * 1024);
     float2* wave_lse = wave_cand + nw * 16;
+    float* keys = reinterpret_cast<float*>(smem + Cfg::lds_bytes(nw));      // TOPK only
 
     // per-row epilogue constants (logits-only launches pass no temperatures)
     RowEpi repi = {1.0f, p.seed, (uint32_t)(uint64_t)(p.row_offset + n), nullptr};
-    if (n < B && p.cand_val) repi = make_row_epi<FULL>(p, n);
+    if (n < B && (p.cand_val || TOPK)) repi = make_row_epi<FULL>(p, n);
 
     // row-tiles of this workgroup, in processing order
     const int T = p.T;
@@ -265,7 +306,7 @@ stage1_splitk_kernel(const Stage1Params p, const int nw, const int kpw)
 
         if (rt == 7) {
             const int tile = (int)blockIdx.x + (rtl >> 3) * (int)gridDim.x;
-            splitk_finish_tile<FULL, WB == 1>(p, repi, partial, wave_cand, wave_lse, nw, wave, lane, tile);
+            splitk_finish_tile<FULL, WB == 1, TOPK>(p, repi, partial, wave_cand, wave_lse, nw, wave, lane, tile, keys);
         }
     }
 }

@@ -5,10 +5,12 @@
 
 namespace fs {
 
-// Stage 1 with the per-tile candidate epilogue.  Three tile shapes (by batch size), whole K steps only.
+// Stage 1 with the per-tile candidate epilogue: the split-K kernel in the decode regime, else three
+// tile shapes of the tiled kernel (by batch size), whole K steps only.
 fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
+    if (p.B <= 16 && p.D <= 4096) return launch_stage1_splitk_topk(p, st);
     if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
     if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
     return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);                   // 256 x 128, batch tiles XCD-paired

@@ -127,11 +127,20 @@ def test_fused_and_unfused_agree_and_gumbel_first_is_the_plain_sample(fs, orc):
     f = run(fs, H, W, tau, k, 1.0, GUMBEL, True, seed=4)
     u = run(fs, H, W, tau, k, 1.0, GUMBEL, False, seed=4)
     assert (f[3] != u[3]).sum() <= 2                         # same ids up to fp32 summation order
-    # first element = the plain sampler's draw, bit for bit when the same kernel and tile shape form the logits
+    # first element = the plain sampler's draw, bit for bit when the same kernel forms the logits (B <= 16: split-K)
     pi, pv = fs.flash_sample_ex(to_device_bf16(H), to_device_bf16(W), dev(tau, np.float32), seed=4,
-                                flags=fs.FS_VARIANT(fs.FS_VARIANT_TILED2) | fs.FS_TUNE_TILE_SHAPE(6))
+                                flags=fs.FS_VARIANT(fs.FS_VARIANT_SPLITK))
     torch.cuda.synchronize()
     assert np.array_equal(pi.cpu().numpy(), f[0]) and np.array_equal(pv.cpu().numpy(), f[1])
+    # ... and at B > 16 the tiled kernel, same tile shape
+    B2 = 24
+    H2, _ = wl.make_small(D=D, V=8, B=B2, data_seed=561)
+    tau2 = np.full(B2, 0.9, dtype=np.float32)
+    f2 = run(fs, H2, W, tau2, k, 1.0, GUMBEL, True, seed=4)
+    pi, pv = fs.flash_sample_ex(to_device_bf16(H2), to_device_bf16(W), dev(tau2, np.float32), seed=4,
+                                flags=fs.FS_VARIANT(fs.FS_VARIANT_TILED2) | fs.FS_TUNE_TILE_SHAPE(6))
+    torch.cuda.synchronize()
+    assert np.array_equal(pi.cpu().numpy(), f2[0]) and np.array_equal(pv.cpu().numpy(), f2[1])
     # k = 1 truncation is greedy decoding: the arg max of the logits
     t = run(fs, H, W, tau, 1, 1.0, TRUNC, True, seed=4)
     g, _ = fs.flash_sample_ex(to_device_bf16(H), to_device_bf16(W), dev(tau, np.float32), seed=4, flags=fs.FS_FLAG_GREEDY)
