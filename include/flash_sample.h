@@ -201,10 +201,11 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
  *   workspace  at least flash_sample_topk_workspace_bytes(B, V, k) bytes, 256-byte aligned
  *   flags      FS_FLAG_NONE or FS_FLAG_EXACT_LOG
  * NaN logits count as -inf.  flash_sample_topk is the fused form: the [B, V] logits never reach device
- * memory.  Stage 1 writes the min(k, 8) best candidates of every row and 128-id tile and a selection
- * reduces them to k per row.  For k > 8 a tile whose 8th candidate is among a row's k may hold more
- * of them (no other tile can): the last selection level recomputes the 128 keys of just those tiles
- * (at most k / 8 per row; none for typical logits) from the row's hidden state and W by plain fp32
+ * memory.  Stage 1 writes the min(k, m) best candidates of every row and 128-id tile (m = 8 for
+ * B <= 32, 4 above) and a selection reduces them to k per row.  For k > m a tile whose m-th candidate
+ * is among a row's k may hold more of them (no other tile can): the last selection level recomputes
+ * the 128 keys of just those tiles (at most k / m per row; none for typical logits) from the row's
+ * hidden state and W by plain fp32
  * dot products and selects again, so the result is the top k for any input.  It needs D % 64 == 0
  * (FS_ERR_UNSUPPORTED otherwise).  flash_sample_topk_unfused is the comparison form for any D: the
  * logits-store GEMM writes `logits` (fp32 [B, V], the raw logits y), and the same selection runs over

@@ -609,11 +609,15 @@ struct TopkWs {
 };
 
 // candidates a tile emits in the fused form
-int topk_tile_m(int k) { return k < kTopkTileM ? k : kTopkTileM; }
+int topk_tile_m(int k, int B)
+{
+    const int m = B <= 32 ? kTopkTileM : kTopkTileMLargeB;
+    return k < m ? k : m;
+}
 
 TopkWs carve_topk(void* ws, int B, int V, int k, bool fused)
 {
-    const int n_cand = fused ? num_tiles(V) * topk_tile_m(k) : V;
+    const int n_cand = fused ? num_tiles(V) * topk_tile_m(k, B) : V;
     const TopkPlan pl = topk_plan(B, n_cand, k);
     const size_t cand = fused ? align_up((size_t)B * (size_t)n_cand * 8, 256) : 0;
     const size_t b0 = align_up(pl.buf_words[0] * 8, 256), b1 = align_up(pl.buf_words[1] * 8, 256);
@@ -666,7 +670,7 @@ fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int
     const TopkWs ws = carve_topk(workspace, B, V, k, true);
     if (!workspace || !aligned(workspace, 256) || workspace_bytes_given < ws.bytes) return FS_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int m = topk_tile_m(k);
+    const int m = topk_tile_m(k, B);
     Stage1Params p = make_params(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset, flags);
     p.topk_out = ws.cand; p.topk_k = m; p.topk_mode = mode;
     s = launch_stage1_topk(p, st);

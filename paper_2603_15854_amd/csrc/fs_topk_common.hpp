@@ -13,8 +13,11 @@
 namespace fs {
 
 constexpr int kTopkMax = 64;          // FS_TOPK_MAX_K
-constexpr int kTopkTileM = 8;         // candidates a 128-id tile emits in the fused first pass
-constexpr int kTopkCrowdMax = kTopkMax / kTopkTileM;   // tiles of one row that can need all their keys
+// Candidates a 128-id tile emits in the fused form: 8 where the stage-1 epilogue is hidden behind the
+// W stream (B <= 32), 4 above (every round of the per-tile selection is exposed there; tiles that hold
+// more winners than they emit are recomputed by the last selection level either way).
+constexpr int kTopkTileM = 8, kTopkTileMLargeB = 4;
+constexpr int kTopkCrowdMax = kTopkMax / kTopkTileMLargeB;   // tiles of one row that can need all their keys
 constexpr int kTopkTruncate = 0, kTopkGumbel = 1;
 
 // What the last selection level does with the k sorted candidates of a row.

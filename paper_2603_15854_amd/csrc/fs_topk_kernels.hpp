@@ -140,7 +140,8 @@ __global__ void __launch_bounds__(256)
 topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32_t id_base, int chunk_len, int k,
                    uint64_t* __restrict__ out, TopkKeys kp, TopkFinish fin, TopkCrowd crowd)
 {
-    __shared__ uint64_t s_list[kSelList];
+    // CROWD: room for 64 winners + kTopkCrowdMax whole tiles, padded to a power of two for the sort
+    __shared__ uint64_t s_list[CROWD ? 4096 : kSelList];
     __shared__ uint64_t s_max[256];
     __shared__ uint64_t s_thr;
     __shared__ int s_count;
@@ -320,6 +321,7 @@ topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32
                 s_list[64 + f * kVocabTile + wave * 32 + lane] = v < crowd.V ? topk_pack(fmaf(y, inv_tau, g), id) : kTopkPad;
             }
         }
+        static_assert(64 + kTopkCrowdMax * kVocabTile <= 4096, "list of the second selection");
         const int n = 64 + ncrowd * kVocabTile;
         int n2 = 256;
         while (n2 < n) n2 <<= 1;

@@ -180,10 +180,12 @@ def _one_hot_problem(logit_rows, D):
     return H, W
 
 
+@pytest.mark.parametrize("nrows", [4, 24, 132])
 @pytest.mark.parametrize("k", [9, 50, 64])
-def test_fused_second_pass_when_winners_crowd_a_tile(fs, orc, k):
-    # the fused first pass keeps 8 candidates per 128-id tile; these rows put far more of the top k into
-    # single tiles, so the exact result needs the second pass (values on a grid that bf16 holds exactly)
+def test_fused_form_when_winners_crowd_a_tile(fs, orc, k, nrows):
+    # the fused stage 1 keeps 8 (B <= 32) or 4 candidates per 128-id tile; these rows put far more of the top k
+    # into single tiles, so the result needs the recomputation of those tiles by the last selection level
+    # (values on a grid that bf16 holds exactly; 4 rows: split-K kernel, 24: tiled, 132: two batch tiles)
     rng = np.random.default_rng(580 + k)
     V, D = 5000, 192
     rows = []
@@ -201,6 +203,7 @@ def test_fused_second_pass_when_winners_crowd_a_tile(fs, orc, k):
             t = int(rng.integers(0, 39))
             r[t * 128:(t + 1) * 128] += 64.0
         rows.append(r)
+    rows = rows[:nrows]
     H, W = _one_hot_problem(rows, D)
     B = len(rows)
     tau = np.ones(B, dtype=np.float32)
