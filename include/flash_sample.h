@@ -309,7 +309,9 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
  * Codes and scale are combined into bf16 values on chip (exactly), then contracted like the bf16
  * path.  Built for the bandwidth-bound decode regime only:
  *   B <= 16 and D % 512 == 0, D <= 4096, or D % 1024 == 0, D <= 8192; anything else returns
- *   FS_ERR_UNSUPPORTED
+ *   FS_ERR_UNSUPPORTED.  (No tiled form for larger batches exists: there the call stops being bound
+ *   by the W bytes, which is all MXFP4 saves; weights dequantised once to E4M3 or bf16 run on
+ *   flash_sample_w8 / flash_sample_ex at any B.)
  *   W4, w_scales   device pointers, 16-byte aligned; scale bytes above 252 must not occur (253 and
  *                  254 overflow the bf16 range of a scaled element, 255 is NaN)
  *   logits         NULL, or fp32 [B, V]: also store y
