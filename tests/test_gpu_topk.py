@@ -258,6 +258,45 @@ def test_truncated_draw_follows_the_renormalised_softmax_on_the_gpu(fs, orc):
     assert chi2 < stats.chi2.ppf(0.999, keep.sum() - 1), chi2
 
 
+def test_topk_graph_capture_and_replay_matches_eager(fs):
+    # both forms allocate nothing and launch only kernels on the caller's stream: a call can be recorded
+    # into a HIP graph; every replay is checked against the eager result for the inputs it ran on
+    for B, D, V, k, fused in [(8, 1024, 5000, 20, True), (48, 512, 3000, 50, True), (8, 1024, 5000, 20, False)]:
+        H, W = wl.make_small(D=D, V=V, B=B, data_seed=620 + B)
+        Hd, Wd = to_device_bf16(H), to_device_bf16(W)
+        tau = torch.full((B,), 0.9, device="cuda")
+        ws = torch.empty(fs.flash_sample_topk_workspace_bytes(B, V, k), dtype=torch.uint8, device="cuda")
+        lg = torch.empty((B, V), dtype=torch.float32, device="cuda")
+        out = dict(out_idx=torch.empty(B, dtype=torch.int32, device="cuda"), out_val=torch.empty(B, device="cuda"),
+                   topk_val=torch.empty((B, k), device="cuda"), topk_idx=torch.empty((B, k), dtype=torch.int32, device="cuda"),
+                   n_kept=torch.empty(B, dtype=torch.int32, device="cuda"))
+        side = torch.cuda.Stream()
+
+        def call(stream, **kw):
+            return fs.flash_sample_topk(Hd, Wd, tau, k, top_p=0.9, seed=3, fused=fused, logits=lg, workspace=ws,
+                                        stream=stream, **kw)
+
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            call(side, **out)                                   # eager first: per-kernel set-up
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            call(side, **out)
+        for rep in range(3):
+            Hnew, _ = wl.make_small(D=D, V=8, B=B, data_seed=720 + rep)
+            Hd.copy_(to_device_bf16(Hnew))
+            ws2 = torch.empty_like(ws)
+            e = fs.flash_sample_topk(Hd, Wd, tau, k, top_p=0.9, seed=3, fused=fused, logits=torch.empty_like(lg), workspace=ws2)
+            torch.cuda.synchronize()
+            out["out_idx"].fill_(-7)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out["out_idx"], e[0]) and torch.equal(out["out_val"], e[1]), (B, fused, rep)
+            assert torch.equal(out["topk_idx"], e[3]) and torch.equal(out["n_kept"], e[4]), (B, fused, rep)
+
+
 def test_topk_rejects_bad_arguments(fs):
     H = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda")
     W = torch.zeros((300, 256), dtype=torch.bfloat16, device="cuda")
