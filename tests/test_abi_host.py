@@ -152,6 +152,39 @@ def test_bad_arguments_are_rejected_before_any_device_work():
     assert L.flash_group_choose(FAKE, FAKE, 2, 8, 0, 0, None, 0, -1, FAKE, None, None) == fs.FS_ERR_SHAPE
 
 
+def test_topk_arguments_and_workspace_without_a_device():
+    L = fs.lib()
+    wsb = fs.flash_sample_topk_workspace_bytes
+
+    def tk(B=4, D=256, V=4096, k=8, top_p=1.0, mode=0, tau=FAKE, out_idx=FAKE, out_val=FAKE, ws=FAKE + 0x100000,
+           ws_bytes=1 << 24, flags=0, fused=True, logits=FAKE):
+        common = (FAKE, FAKE, B, D, V, tau, 0, None, 0, 0, k, top_p, mode)
+        tail = (out_idx, out_val, None, None, None, ws, ws_bytes, None, flags)
+        return L.flash_sample_topk(*common, *tail) if fused else L.flash_sample_topk_unfused(*common, logits, *tail)
+
+    for fused in (True, False):
+        assert tk(B=0, fused=fused) == fs.FS_OK
+        assert tk(k=0, fused=fused) == fs.FS_ERR_SHAPE and tk(k=fs.FS_TOPK_MAX_K + 1, fused=fused) == fs.FS_ERR_SHAPE
+        assert tk(top_p=0.0, fused=fused) == fs.FS_ERR_SHAPE and tk(top_p=1.01, fused=fused) == fs.FS_ERR_SHAPE
+        assert tk(top_p=float("nan"), fused=fused) == fs.FS_ERR_SHAPE
+        assert tk(mode=2, fused=fused) == fs.FS_ERR_SHAPE
+        assert tk(mode=fs.FS_TOPK_GUMBEL, top_p=0.9, fused=fused) == fs.FS_ERR_SHAPE     # the candidates are the draw
+        assert tk(flags=fs.FS_FLAG_GREEDY, fused=fused) == fs.FS_ERR_UNSUPPORTED
+        assert tk(tau=None, fused=fused) == fs.FS_ERR_NULL and tk(out_idx=None, fused=fused) == fs.FS_ERR_NULL
+        assert tk(out_val=FAKE + 2, fused=fused) == fs.FS_ERR_ALIGN
+        assert tk(ws=None, fused=fused) == fs.FS_ERR_WORKSPACE
+        assert tk(D=252, fused=fused) == fs.FS_ERR_SHAPE
+    assert tk(ws_bytes=wsb(4, 4096, 8) - 1) == fs.FS_ERR_WORKSPACE   # (the form over stored logits needs less)
+    assert tk(D=200) == fs.FS_ERR_UNSUPPORTED                  # the fused form takes whole K steps only
+    assert tk(fused=False, logits=None) == fs.FS_ERR_NULL
+    # workspace: zero for impossible arguments, monotone in B, the fused candidates dominate
+    assert wsb(0, 4096, 8) == 0 and wsb(4, 4096, 0) == 0 and wsb(4, 4096, 65) == 0
+    assert wsb(4, 4096, 8) >= 4 * 32 * 8 * 8                    # B x T x m words
+    assert wsb(256, 128256, 50) >= 256 * 1002 * 4 * 8 and wsb(256, 128256, 50) < 32 << 20
+    assert wsb(16, 128256, 50) >= 16 * 1002 * 8 * 8
+    assert wsb(8, 128256, 50) <= wsb(16, 128256, 50) <= wsb(32, 128256, 50) * 2
+
+
 def test_kernel_choice_by_shape():
     # the launcher's rule: split-K while the hidden slice of a wave fits its registers, else the
     # tile shape with the cheapest busiest CU, ceil(workgroups / CUs) * (rows + columns), finer on ties
