@@ -15,6 +15,7 @@ line carries, unless --quick is given:
   stream_fit      steady streaming rate and fixed cost per call of the B <= 16 kernels (bf16, FP8, MXFP4)
   fp8_weights, mxfp4_weights   the same call on lower-precision weights
   cpu_baseline    the CPU oracle on the host cores (bounded sample)
+`--legs a,b` runs only the named legs beside the headline (profiles of one leg use it).
 
 Timing.  Headline: W warm-up calls, then exactly K calls bracketed by events on the stream the
 kernels are launched on (torch's current stream, which is passed to the library), with a device
@@ -81,6 +82,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--quick", "--no-sweep", dest="quick", action="store_true",
                     help="headline and roofline only (what the profiler runs use)")
+    ap.add_argument("--legs", default="all",
+                    help="comma-separated legs to run beside the headline: sweep, epilogue_share, top_k, low_precision, "
+                         "stream_fit, configs (default: all; --quick runs none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time of the CPU-oracle leg")
     ap.add_argument("--variant", type=int, default=0, help="stage-1 kernel variant (0 = automatic)")
@@ -145,6 +149,11 @@ def main() -> int:
             fs.flash_sample_unfused(self.Hd, self.Wd, self.tau, seed=self.w.seed, row_seeds=self.seeds,
                                     logits=self.lg, out_idx=self.oi, out_val=self.ov, workspace=self.ws,
                                     stream=stream, flags=flags)
+
+    legs = set(args.legs.split(","))
+
+    def want(name):
+        return "all" in legs or name in legs
 
     def spin_up(fn):
         """Keep the GPU busy with the call about to be measured for args.spinup_ms: after host-side
@@ -291,153 +300,159 @@ def main() -> int:
         out["calibration"] = {"probe_bytes": int(Wd.numel() * 2), "launches_each": args.calibrate}
         del dst
 
+    keep_head = (head.oi.clone(), head.H, head.tau_h, head.seeds_h)
     if not args.quick:
         # -------------------------------------------------------------- sweep B = 1..256 at the headline shape
-        sweep = []
-        for Bs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
-            sweep.append(fused_vs_unfused(Leg(w, Wd, Bs, want_logits=True)))
-        out["sweep"] = sweep
+        if want("sweep"):
+            sweep = []
+            for Bs in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+                sweep.append(fused_vs_unfused(Leg(w, Wd, Bs, want_logits=True)))
+            out["sweep"] = sweep
 
         # -------------------------------------------------------------- sampling epilogue share of stage 1
-        share = []
-        for Bs in (1, 16, 64, 256):
-            leg = Leg(w, Wd, Bs)
-            on = per_call_us(leg.stage1)
-            off = per_call_us(leg.stage1_greedy)
-            share.append({"B": Bs, "stage1_sampling_us": on["median_us"], "stage1_noise_off_us": off["median_us"],
-                          "noise_share_pct": round(100.0 * (on["median_us"] - off["median_us"]) / on["median_us"], 2),
-                          "paper_sampling_share_pct": PAPER_SAMPLING_SHARE_PCT[Bs]})
-        out["epilogue_share"] = {
-            "what": "stage 1 with the noise switched off (FS_FLAG_GREEDY: no Philox, no logarithms; the 1/tau "
-                    "scaling, the per-tile arg max and the candidate store stay) against the sampling kernel; "
-                    "the paper's column is its sampling share of the fused kernel on its own GPU (context)",
-            "rows": share}
+        if want("epilogue_share"):
+            share = []
+            for Bs in (1, 16, 64, 256):
+                leg = Leg(w, Wd, Bs)
+                on = per_call_us(leg.stage1)
+                off = per_call_us(leg.stage1_greedy)
+                share.append({"B": Bs, "stage1_sampling_us": on["median_us"], "stage1_noise_off_us": off["median_us"],
+                              "noise_share_pct": round(100.0 * (on["median_us"] - off["median_us"]) / on["median_us"], 2),
+                              "paper_sampling_share_pct": PAPER_SAMPLING_SHARE_PCT[Bs]})
+            out["epilogue_share"] = {
+                "what": "stage 1 with the noise switched off (FS_FLAG_GREEDY: no Philox, no logarithms; the 1/tau "
+                        "scaling, the per-tile arg max and the candidate store stay) against the sampling kernel; "
+                        "the paper's column is its sampling share of the fused kernel on its own GPU (context)",
+                "rows": share}
 
         # -------------------------------------------------------------- top-k / top-p: fused against stored logits
-        rows_k = []
-        for Bs, kk in ((16, 50), (64, 50), (256, 50), (64, 8), (64, 64)):
-            leg = Leg(w, Wd, Bs, want_logits=True)
-            wsk = torch.empty(fs.flash_sample_topk_workspace_bytes(Bs, V, kk), dtype=torch.uint8, device="cuda")
-            tv = torch.empty((Bs, kk), dtype=torch.float32, device="cuda")
-            ti = torch.empty((Bs, kk), dtype=torch.int32, device="cuda")
-            nk = torch.empty(Bs, dtype=torch.int32, device="cuda")
+        if want("top_k"):
+            rows_k = []
+            for Bs, kk in ((16, 50), (64, 50), (256, 50), (64, 8), (64, 64)):
+                leg = Leg(w, Wd, Bs, want_logits=True)
+                wsk = torch.empty(fs.flash_sample_topk_workspace_bytes(Bs, V, kk), dtype=torch.uint8, device="cuda")
+                tv = torch.empty((Bs, kk), dtype=torch.float32, device="cuda")
+                ti = torch.empty((Bs, kk), dtype=torch.int32, device="cuda")
+                nk = torch.empty(Bs, dtype=torch.int32, device="cuda")
 
-            def topk(fused, leg=leg, kk=kk, wsk=wsk, tv=tv, ti=ti, nk=nk):
-                fs.flash_sample_topk(leg.Hd, leg.Wd, leg.tau, kk, top_p=0.9, mode=fs.FS_TOPK_TRUNCATE, seed=w.seed,
-                                     row_seeds=leg.seeds, fused=fused, logits=leg.lg, out_idx=leg.oi, out_val=leg.ov,
-                                     topk_val=tv, topk_idx=ti, n_kept=nk, workspace=wsk, stream=stream)
+                def topk(fused, leg=leg, kk=kk, wsk=wsk, tv=tv, ti=ti, nk=nk):
+                    fs.flash_sample_topk(leg.Hd, leg.Wd, leg.tau, kk, top_p=0.9, mode=fs.FS_TOPK_TRUNCATE, seed=w.seed,
+                                         row_seeds=leg.seeds, fused=fused, logits=leg.lg, out_idx=leg.oi, out_val=leg.ov,
+                                         topk_val=tv, topk_idx=ti, n_kept=nk, workspace=wsk, stream=stream)
 
-            plain = per_call_us(leg.fused)
-            f = per_call_us(lambda: topk(True))
-            u = per_call_us(lambda: topk(False))
-            rows_k.append({"B": Bs, "k": kk, "top_p": 0.9, "plain_sample_us": plain["median_us"],
-                           "fused_topk_us": f["median_us"], "fused_topk_min_us": f["min_us"], "fused_topk_max_us": f["max_us"],
-                           "stored_logits_topk_us": u["median_us"], "stored_logits_topk_min_us": u["min_us"],
-                           "stored_logits_topk_max_us": u["max_us"],
-                           "fused_over_stored_speedup": round(u["median_us"] / f["median_us"], 4),
-                           "fused_topk_over_plain": round(f["median_us"] / plain["median_us"], 4)})
-            del leg, wsk
-        out["top_k"] = {
-            "what": "top-k truncation + nucleus on the k candidates + Gumbel-max over the kept ids: the fused form "
-                    "(per-tile top-k in the stage-1 epilogue, no logits in HBM) against the form over stored logits "
-                    "(logits-store GEMM, then keys, selection and draw kernels); plain_sample is the untruncated draw",
-            "rows": rows_k}
+                plain = per_call_us(leg.fused)
+                f = per_call_us(lambda: topk(True))
+                u = per_call_us(lambda: topk(False))
+                rows_k.append({"B": Bs, "k": kk, "top_p": 0.9, "plain_sample_us": plain["median_us"],
+                               "fused_topk_us": f["median_us"], "fused_topk_min_us": f["min_us"], "fused_topk_max_us": f["max_us"],
+                               "stored_logits_topk_us": u["median_us"], "stored_logits_topk_min_us": u["min_us"],
+                               "stored_logits_topk_max_us": u["max_us"],
+                               "fused_over_stored_speedup": round(u["median_us"] / f["median_us"], 4),
+                               "fused_topk_over_plain": round(f["median_us"] / plain["median_us"], 4)})
+                del leg, wsk
+            out["top_k"] = {
+                "what": "top-k truncation + nucleus on the k candidates + Gumbel-max over the kept ids: the fused form "
+                        "(per-tile top-k in the stage-1 epilogue, no logits in HBM) against the form over stored logits "
+                        "(logits-store GEMM, then keys, selection and draw kernels); plain_sample is the untruncated draw",
+                "rows": rows_k}
 
         # -------------------------------------------------------------- FP8 / MXFP4 weights (same shape)
-        codes, wscale = wl.quantize_e4m3(Wb)
-        W8d = torch.from_numpy(codes).cuda()
-        scd = torch.from_numpy(wscale).cuda()
-        rows8 = []
-        for Bq in (1, 16, 64):
-            q = Leg(w, Wd, Bq)
-            d8 = per_call_us(lambda: fs.flash_sample_w8(q.Hd, W8d, scd, q.tau, seed=w.seed, row_seeds=q.seeds,
-                                                        out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
-            r = {"B": Bq, "fused_us": d8["median_us"], "fused_min_us": d8["min_us"], "fused_max_us": d8["max_us"]}
-            r.update(rates(Bq, D, V, d8["median_us"], w_bytes_per_row=D + 4))
-            rows8.append(r)
-        out["fp8_weights"] = {"format": "OCP E4M3 codes + fp32 scale per vocabulary row, hidden bf16", "rows": rows8}
-        del W8d, scd, codes
-        c4, s4 = wl.quantize_mxfp4(Wb)
-        W4d = torch.from_numpy(c4).cuda()
-        S4d = torch.from_numpy(s4).cuda()
-        rows4 = []
-        for Bq in (1, 16):
-            q = Leg(w, Wd, Bq)
-            d4 = per_call_us(lambda: fs.flash_sample_w4(q.Hd, W4d, S4d, q.tau, seed=w.seed, row_seeds=q.seeds,
-                                                        out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
-            r = {"B": Bq, "fused_us": d4["median_us"], "fused_min_us": d4["min_us"], "fused_max_us": d4["max_us"]}
-            r.update(rates(Bq, D, V, d4["median_us"], w_bytes_per_row=D // 2 + D // 32))
-            rows4.append(r)
-        out["mxfp4_weights"] = {"format": "OCP MXFP4: E2M1 codes, one E8M0 scale per 32 elements, hidden bf16",
-                                "rows": rows4}
-        del W4d, S4d, c4, s4
+        if want("low_precision"):
+            codes, wscale = wl.quantize_e4m3(Wb)
+            W8d = torch.from_numpy(codes).cuda()
+            scd = torch.from_numpy(wscale).cuda()
+            rows8 = []
+            for Bq in (1, 16, 64):
+                q = Leg(w, Wd, Bq)
+                d8 = per_call_us(lambda: fs.flash_sample_w8(q.Hd, W8d, scd, q.tau, seed=w.seed, row_seeds=q.seeds,
+                                                            out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
+                r = {"B": Bq, "fused_us": d8["median_us"], "fused_min_us": d8["min_us"], "fused_max_us": d8["max_us"]}
+                r.update(rates(Bq, D, V, d8["median_us"], w_bytes_per_row=D + 4))
+                rows8.append(r)
+            out["fp8_weights"] = {"format": "OCP E4M3 codes + fp32 scale per vocabulary row, hidden bf16", "rows": rows8}
+            del W8d, scd, codes
+            c4, s4 = wl.quantize_mxfp4(Wb)
+            W4d = torch.from_numpy(c4).cuda()
+            S4d = torch.from_numpy(s4).cuda()
+            rows4 = []
+            for Bq in (1, 16):
+                q = Leg(w, Wd, Bq)
+                d4 = per_call_us(lambda: fs.flash_sample_w4(q.Hd, W4d, S4d, q.tau, seed=w.seed, row_seeds=q.seeds,
+                                                            out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))
+                r = {"B": Bq, "fused_us": d4["median_us"], "fused_min_us": d4["min_us"], "fused_max_us": d4["max_us"]}
+                r.update(rates(Bq, D, V, d4["median_us"], w_bytes_per_row=D // 2 + D // 32))
+                rows4.append(r)
+            out["mxfp4_weights"] = {"format": "OCP MXFP4: E2M1 codes, one E8M0 scale per 32 elements, hidden bf16",
+                                    "rows": rows4}
+            del W4d, S4d, c4, s4
 
         # -------------------------------------------------------------- streaming rate vs fixed cost per call
-        # whole calls at V = 256 * 128 * k (k vocabulary tiles per persistent workgroup), B = 16: the slope
-        # over k is the steady streaming rate, the intercept what a call costs before and after it
-        # (launch, first-byte latency, last tile's epilogue, stage 2)
-        g = torch.Generator(device="cuda")
-        g.manual_seed(11)
-        fit_rows = []
-        legq = Leg(w, Wd, 16)
-        ks = (1, 2, 4, 8)
-        for fmt, row_bytes in (("bf16", 2 * D), ("fp8_e4m3", D + 4), ("mxfp4", D // 2 + D // 32)):
-            us = []
-            for kk in ks:
-                Vk = 256 * fs.FS_VOCAB_TILE * kk
-                wsk = torch.empty(fs.flash_sample_workspace_bytes(16, Vk), dtype=torch.uint8, device="cuda")
-                if fmt == "bf16":
-                    Wk = (torch.randn((Vk, D), device="cuda", generator=g) / 64).to(torch.bfloat16)
-                    fn = lambda: fs.flash_sample_ex(legq.Hd, Wk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
-                                                    workspace=wsk, stream=stream)
-                elif fmt == "fp8_e4m3":
-                    Wk = torch.randint(0, 120, (Vk, D), dtype=torch.uint8, device="cuda", generator=g)
-                    sk = torch.ones(Vk, device="cuda")
-                    fn = lambda: fs.flash_sample_w8(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
-                                                    workspace=wsk, stream=stream)
-                else:
-                    Wk = torch.randint(0, 256, (Vk, D // 2), dtype=torch.uint8, device="cuda", generator=g)
-                    sk = torch.randint(120, 130, (Vk, D // 32), dtype=torch.uint8, device="cuda", generator=g)
-                    fn = lambda: fs.flash_sample_w4(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
-                                                    workspace=wsk, stream=stream)
-                us.append(per_call_us(fn, calls=50, repeats=3)["median_us"])
-                del Wk, wsk
-            slope, intercept = np.polyfit(np.array(ks, dtype=np.float64), np.array(us), 1)
-            step_bytes = 256 * fs.FS_VOCAB_TILE * row_bytes
-            fit_rows.append({"weights": fmt, "us_at_k": dict(zip(map(str, ks), us)), "us_per_tile_round": round(float(slope), 3),
-                             "steady_gbs": round(step_bytes / slope / 1e3, 1),
-                             "steady_pct_hbm_peak": round(100.0 * step_bytes / slope / 1e3 / HBM_PEAK_GBS, 2),
-                             "fixed_us_per_call": round(float(intercept), 2)})
-        out["stream_fit"] = {
-            "what": "whole calls at B=16, D=%d, V = 256*128*k for k = 1, 2, 4, 8 (random weights; the values do not "
-                    "matter for time): least-squares line through the medians.  steady = bytes of one round of "
-                    "256 vocabulary tiles / slope; fixed = intercept" % D,
-            "rows": fit_rows}
-        torch.cuda.empty_cache()
+        if want("stream_fit"):
+            # whole calls at V = 256 * 128 * k (k vocabulary tiles per persistent workgroup), B = 16: the slope
+            # over k is the steady streaming rate, the intercept what a call costs before and after it
+            # (launch, first-byte latency, last tile's epilogue, stage 2)
+            g = torch.Generator(device="cuda")
+            g.manual_seed(11)
+            fit_rows = []
+            legq = Leg(w, Wd, 16)
+            ks = (1, 2, 4, 8)
+            for fmt, row_bytes in (("bf16", 2 * D), ("fp8_e4m3", D + 4), ("mxfp4", D // 2 + D // 32)):
+                us = []
+                for kk in ks:
+                    Vk = 256 * fs.FS_VOCAB_TILE * kk
+                    wsk = torch.empty(fs.flash_sample_workspace_bytes(16, Vk), dtype=torch.uint8, device="cuda")
+                    if fmt == "bf16":
+                        Wk = (torch.randn((Vk, D), device="cuda", generator=g) / 64).to(torch.bfloat16)
+                        fn = lambda: fs.flash_sample_ex(legq.Hd, Wk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                        workspace=wsk, stream=stream)
+                    elif fmt == "fp8_e4m3":
+                        Wk = torch.randint(0, 120, (Vk, D), dtype=torch.uint8, device="cuda", generator=g)
+                        sk = torch.ones(Vk, device="cuda")
+                        fn = lambda: fs.flash_sample_w8(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                        workspace=wsk, stream=stream)
+                    else:
+                        Wk = torch.randint(0, 256, (Vk, D // 2), dtype=torch.uint8, device="cuda", generator=g)
+                        sk = torch.randint(120, 130, (Vk, D // 32), dtype=torch.uint8, device="cuda", generator=g)
+                        fn = lambda: fs.flash_sample_w4(legq.Hd, Wk, sk, legq.tau, seed=1, out_idx=legq.oi, out_val=legq.ov,
+                                                        workspace=wsk, stream=stream)
+                    us.append(per_call_us(fn, calls=50, repeats=3)["median_us"])
+                    del Wk, wsk
+                slope, intercept = np.polyfit(np.array(ks, dtype=np.float64), np.array(us), 1)
+                step_bytes = 256 * fs.FS_VOCAB_TILE * row_bytes
+                fit_rows.append({"weights": fmt, "us_at_k": dict(zip(map(str, ks), us)), "us_per_tile_round": round(float(slope), 3),
+                                 "steady_gbs": round(step_bytes / slope / 1e3, 1),
+                                 "steady_pct_hbm_peak": round(100.0 * step_bytes / slope / 1e3 / HBM_PEAK_GBS, 2),
+                                 "fixed_us_per_call": round(float(intercept), 2)})
+            out["stream_fit"] = {
+                "what": "whole calls at B=16, D=%d, V = 256*128*k for k = 1, 2, 4, 8 (random weights; the values do not "
+                        "matter for time): least-squares line through the medians.  steady = bytes of one round of "
+                        "256 vocabulary tiles / slope; fixed = intercept" % D,
+                "rows": fit_rows}
+            torch.cuda.empty_cache()
 
         # -------------------------------------------------------------- the other workloads
-        # C3 (Qwen-style vocabulary), C4 (D=8192: the shape of the paper's only absolute kernel
-        # times, which sit beside these rows as context: another machine, another kernel) and C5
-        # (wide hidden sweep); one weight matrix on the device at a time.
-        out["configs"] = {}
-        keep_head = (head.oi.clone(), head.H, head.tau_h, head.seeds_h)
-        del Wd, head
-        torch.cuda.empty_cache()
-        for name, batches in (("C3", (32, 64, 128)), ("C4", (16, 64, 256)), ("C5", (1, 8, 64, 256, 512))):
-            wk = wl.WORKLOADS[name]
-            Wk = to_device_bf16(wl.make_weights(wk))
-            rows = []
-            for Bq in batches:
-                row = fused_vs_unfused(Leg(wk, Wk, Bq, want_logits=True))
-                if name == "C4":
-                    row["paper_fused_us"], row["paper_gumbel_on_stored_logits_us"] = PAPER_ABS_US[Bq]
-                rows.append(row)
-            out["configs"][name] = {"D": wk.D, "V": wk.V, "note": wk.note, "rows": rows}
-            del Wk
+        if want("configs"):
+            # C3 (Qwen-style vocabulary), C4 (D=8192: the shape of the paper's only absolute kernel
+            # times, which sit beside these rows as context: another machine, another kernel) and C5
+            # (wide hidden sweep); one weight matrix on the device at a time.
+            out["configs"] = {}
+            del Wd, head
             torch.cuda.empty_cache()
-        out["configs"]["C4"]["paper_numbers"] = (
-            "appendix table of tensor-parallel runtimes, TP=1 column: the paper's fused kernel and its FlashInfer "
-            "Gumbel-max baseline on an 8 TB/s-class NVIDIA GPU; context only (other hardware, other software)")
+            for name, batches in (("C3", (32, 64, 128)), ("C4", (16, 64, 256)), ("C5", (1, 8, 64, 256, 512))):
+                wk = wl.WORKLOADS[name]
+                Wk = to_device_bf16(wl.make_weights(wk))
+                rows = []
+                for Bq in batches:
+                    row = fused_vs_unfused(Leg(wk, Wk, Bq, want_logits=True))
+                    if name == "C4":
+                        row["paper_fused_us"], row["paper_gumbel_on_stored_logits_us"] = PAPER_ABS_US[Bq]
+                    rows.append(row)
+                out["configs"][name] = {"D": wk.D, "V": wk.V, "note": wk.note, "rows": rows}
+                del Wk
+                torch.cuda.empty_cache()
+            out["configs"]["C4"]["paper_numbers"] = (
+                "appendix table of tensor-parallel runtimes, TP=1 column: the paper's fused kernel and its FlashInfer "
+                "Gumbel-max baseline on an 8 TB/s-class NVIDIA GPU; context only (other hardware, other software)")
         head_oi, head_H, head_tau, head_seeds = keep_head
     else:
         head_oi, head_H, head_tau, head_seeds = head.oi, head.H, head.tau_h, head.seeds_h
