@@ -181,9 +181,9 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
                             void* workspace, size_t workspace_bytes, void* stream, uint32_t flags);
 
 /*
- * Truncated supports (Section "Top-k, Nucleus Sampling, and Masking": each tile computes its top-k
- * candidates locally, a second stage reduces them to a global top-k, and the nucleus rule is applied
- * on the k candidates; the paper gives the scheme and leaves the implementation open).  With
+ * Truncated supports (Section "Top-k, Nucleus Sampling, and Masking": the scheme given there is
+ * per-tile candidate lists merged by a second stage into the k best of the row, with the nucleus
+ * rule run on those k; the implementation is left open).  With
  * z_{b,i} = y_{b,i} / temperature_b and the per-id noise g of the main path:
  *   FS_TOPK_TRUNCATE  S_b = the k ids with the largest z (ties: lower id first).  If top_p < 1 the
  *                     candidates, in that order, get q_j = softmax over S_b, and only the shortest
