@@ -257,9 +257,9 @@ int fso_sample_tiled(const uint16_t* H, const uint16_t* W, int64_t B, int64_t D,
 
 /* ------------------------------------------------------------------ full transform + log-normaliser */
 /*
- * Transformed logits of one row (Section "Background", Notation: "deterministic operations such as
- * additive bias, temperature scaling, or masking"; Alg. 1, "transform"; Section "Top-k, Nucleus
- * Sampling, and Masking": forbidden ids are set to -inf before perturbation):
+ * Transformed logits of one row (Section "Background", Notation: the logits after the deterministic
+ * steps, of which it names a bias added, a temperature and a mask; Alg. 1, "transform"; Section
+ * "Top-k, Nucleus Sampling, and Masking": forbidden ids are set to -inf before perturbation):
  *      z_i = (y_i + bias_i) / tau            if id i is allowed
  *      z_i = -inf                             if id i is masked out
  * bias is fp32 [V] or NULL (indexed by the local id i); allowed is a bit array of V bits packed in
