@@ -56,12 +56,23 @@ fs_status current_device(int* dev_out, int* cus_out)
 // kernel it replaced ran at 301 and 566) and at D = 8192, V = 128256, B <= 16: s6 307, s8 315, s1 317.
 int pick_tile_shape(int B, int D, int V, int cus)
 {
+    if (B > 128) {
+        // The kernel with direct global -> LDS loads, 256 x 256 or 256 x 128 tiles.  A round of 256 x 256
+        // workgroups takes 123 us and one of 256 x 128 workgroups 73 us at D = 4096 (the ratio holds at
+        // D = 8192); the launch lasts rounds x that.  256 x 128 wins where the last 256-row batch tile
+        // would be at most half full (B = 320, 384: 10-20 % ahead) and where 256-row tiles leave CUs
+        // without work (V = 32000 at B <= 256); checked against a sweep over V in {32000 .. 256000} x
+        // B in {160, 256, 320, 384, 512, 768}.  On near-ties the larger tile (fewer bytes into the CUs).
+        const long long mt = (V + 255) / 256;
+        const long long r256 = (mt * ((B + 255) / 256) + cus - 1) / cus;
+        const long long r128 = (mt * ((B + 127) / 128) + cus - 1) / cus;
+        return r128 * 73 * 100 < r256 * 123 * 97 ? 13 : 12;
+    }
     struct TileShape { int id, vt, bt; };
     static constexpr TileShape b32[] = {{1, 128, 32}, {8, 256, 32}, {6, 512, 32}};
     static constexpr TileShape b64[] = {{5, 128, 64}, {2, 256, 64}, {7, 512, 64}};
     static constexpr TileShape b128[] = {{4, 128, 128}, {3, 256, 128}, {10, 512, 128}};
-    static constexpr TileShape big[] = {{4, 128, 128}, {3, 256, 128}, {12, 256, 256}};
-    const TileShape* cand = B <= 32 ? b32 : B <= 64 ? b64 : B <= 128 ? b128 : big;
+    const TileShape* cand = B <= 32 ? b32 : B <= 64 ? b64 : b128;
     int best = cand[0].id;
     long long best_cost = -1;
     for (int i = 0; i < 3; ++i) {   // fine to coarse; a coarser shape must be strictly cheaper

@@ -42,8 +42,9 @@ fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStre
     case 7: return launch_tiled2<Tiled2Cfg<64, 4, 2, 1, 1, 512, 1>, false, 1, true>(p, st);
     case 8: return launch_tiled2<Tiled2Cfg<32, 4, 1, 1, 2, 256>, false, 1, true>(p, st);
     case 3:
-    case 10:   // 512 x 128 and 256 x 256 do not fit LDS with two hidden sub-tiles per step:
-    case 12:   // both run as 256 x 128
+    case 10:   // 512 x 128 and 256 x 256 do not fit LDS with two hidden sub-tiles per step, and the
+    case 12:   // direct-to-LDS kernel exists for bf16 only: all run as 256 x 128
+    case 13:
         return launch_tiled2<Tiled2Cfg<128, 4, 2, 1, 2, 256>, false, 1, true, false, true>(p, st);
     default: break;
     }

@@ -197,7 +197,10 @@ def test_kernel_choice_by_shape():
     assert [kc(32, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [1, 8, 6, 1, 6]
     assert [kc(64, 4096, V) for V in (32000, 50304, 100352, 152064)] == [5, 2, 7, 5]
     assert [kc(128, 4096, V) for V in (32000, 50304, 100352, 152064, 201088, 256000)] == [4, 3, 10, 4, 10, 10]
-    assert [kc(256, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [3, 12, 12, 12, 12]
+    assert [kc(256, 4096, V) for V in (32000, 50304, 100352, 152064, 201088)] == [13, 12, 12, 12, 12]
+    # above 128 rows: 256 x 128 tiles where the last 256-row batch tile would be at most half full
+    assert [kc(B, 4096, 128256) for B in (160, 320, 384, 512, 640, 768)] == [12, 13, 13, 12, 12, 12]
+    assert [kc(B, 4096, 32000) for B in (160, 320, 512, 768)] == [13, 12, 12, 13]
     assert [kc(B, 520, 128256) for B in (20, 64, 200)] == [8, 5, 4]        # D % 64 != 0
     assert kc(4, 4096, 1000) == 0 and kc(40, 4096, 1000) == 5              # a handful of tiles: fine shapes
     assert kc(0, 4096, 10) == -1 and kc(4, 4100, 10) == -1 and kc(4, 4096, 10, 0) == -1

@@ -366,6 +366,13 @@ def test_config_c2_llama_shape(fs, orc, B):
     assert np.allclose(gv, tv, rtol=0, atol=1e-4)
 
 
+@pytest.mark.parametrize("B", [160, 320])
+def test_config_c2_shape_above_128_rows(fs, orc, B):
+    # beyond the paper's batch sizes for this shape: one 256-row batch tile partly full (160), and three
+    # 128-row batch tiles that share every W tile (320: the 256 x 128 form of the direct-to-LDS kernel)
+    _full_config(fs, orc, "C2", B)
+
+
 @pytest.mark.parametrize("B", [32, 64, 128])
 def test_config_c3_qwen_shape(fs, orc, B):
     _full_config(fs, orc, "C3", B)
