@@ -120,6 +120,29 @@ def test_topk_matches_oracle(fs, orc, case, mode, fused):
     assert near <= max(2, B // 10), (exact, near)
 
 
+def test_topk_seeded_random_shapes(fs, orc):
+    # a seeded sweep over batch sizes on both sides of every kernel boundary, ragged vocabularies, k, top_p,
+    # both modes and forms, and vocabulary offsets that are not multiples of the four ids of a noise block
+    rng = np.random.default_rng(77)
+    for it in range(40):
+        B = int(rng.choice([1, 2, 3, 7, 16, 17, 31, 33, 64, 65, 129, 200]))
+        D = int(rng.choice([64, 128, 256, 512, 1024])) if B > 64 else int(rng.choice([64, 192, 512, 1024, 4096]))
+        V = int(rng.integers(1, 6000)) if it % 3 else int(rng.integers(8000, 30000))
+        k = int(rng.integers(1, 65))
+        mode = int(rng.integers(0, 2))
+        p = 1.0 if mode == GUMBEL else float(rng.choice([1.0, 0.9, 0.5, 0.99]))
+        fused = bool(rng.integers(0, 2))
+        vo, ro = int(rng.choice([0, 3, 5, 129])), int(rng.integers(0, 100))
+        print(f"random case {it}: B={B} D={D} V={V} k={k} p={p} mode={mode} fused={fused} vocab_offset={vo}", flush=True)
+        H, W = wl.make_small(D=D, V=V, B=B, data_seed=3000 + it, w_row_scale=float(rng.choice([1.0, 2.0, 4.0])))
+        tau = rng.uniform(0.5, 1.5, B).astype(np.float32)
+        seeds = rng.integers(0, 2**62, B).astype(np.uint64)
+        ref = orc.sample_topk(H, W, tau, k, top_p=p, mode=mode, row_seeds=seeds, row_offset=ro, vocab_offset=vo)
+        got = run(fs, H, W, tau, k, p, mode, fused, row_seeds=seeds, row_offset=ro, vocab_offset=vo)
+        exact, near = judge_topk(orc, H, W, tau, k, p, mode, ref, got, row_seeds=seeds, row_offset=ro, vocab_offset=vo)
+        assert near <= max(2, B // 10), (it, exact, near)
+
+
 def test_fused_and_unfused_agree_and_gumbel_first_is_the_plain_sample(fs, orc):
     B, D, V, k = 8, 1024, 20000, 32
     H, W = wl.make_small(D=D, V=V, B=B, data_seed=560)
