@@ -375,7 +375,7 @@ def main() -> int:
             W4d = torch.from_numpy(c4).cuda()
             S4d = torch.from_numpy(s4).cuda()
             rows4 = []
-            for Bq in (1, 16):
+            for Bq in (1, 16, 32, 64):
                 q = Leg(w, Wd, Bq)
                 d4 = per_call_us(lambda: fs.flash_sample_w4(q.Hd, W4d, S4d, q.tau, seed=w.seed, row_seeds=q.seeds,
                                                             out_idx=q.oi, out_val=q.ov, workspace=q.ws, stream=stream))

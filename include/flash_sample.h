@@ -307,11 +307,10 @@ fs_status flash_sample_w8(const void* hidden, const void* W8, const float* w_sca
  * a row, worth 2^(e - 127); hidden stays bf16:
  *      y_{b,i} = sum_d hidden[b,d] * e2m1(W4[i,d]) * 2^(w_scales[i, d/32] - 127)
  * Codes and scale are combined into bf16 values on chip (exactly), then contracted like the bf16
- * path.  Built for the bandwidth-bound decode regime only:
- *   B <= 16 and D % 512 == 0, D <= 4096, or D % 1024 == 0, D <= 8192; anything else returns
- *   FS_ERR_UNSUPPORTED.  (No tiled form for larger batches exists: there the call stops being bound
- *   by the W bytes, which is all MXFP4 saves; weights dequantised once to E4M3 or bf16 run on
- *   flash_sample_w8 / flash_sample_ex at any B.)
+ * path.  D must be a multiple of 256 (FS_ERR_UNSUPPORTED otherwise).  Two kernels: the split-K form
+ * of the bandwidth-bound decode regime (B <= 16 and D % 512 == 0, D <= 4096, or D % 1024 == 0,
+ * D <= 8192), and a tiled form with the codes and scale bytes kept in LDS for everything else (any B;
+ * it pays off up to B = 64, where the call is still bound by the W bytes, which is all MXFP4 saves).
  *   W4, w_scales   device pointers, 16-byte aligned; scale bytes above 252 must not occur (253 and
  *                  254 overflow the bf16 range of a scaled element, 255 is NaN)
  *   logits         NULL, or fp32 [B, V]: also store y

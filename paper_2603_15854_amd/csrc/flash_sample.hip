@@ -504,7 +504,7 @@ fs_status flash_sample_w4(const void* hidden, const void* W4, const void* w_scal
     if (s != FS_OK) return s;
     if (flags & ~(kTuneMask | kEpiMask)) return FS_ERR_UNSUPPORTED;
     if (B == 0) return FS_OK;
-    if (B > 16 || (D & 511) != 0 || D > 8192 || (D > 4096 && (D & 1023) != 0)) return FS_ERR_UNSUPPORTED;
+    if ((D & 255) != 0) return FS_ERR_UNSUPPORTED;          // whole blocks of 32 and whole K steps of the tiled form
     if (!w_scales || !temperature || !out_idx || !out_val) return FS_ERR_NULL;
     if (!aligned(w_scales, 16) || !aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(temperature, 4) ||
         !aligned(row_seeds, 8) || !aligned(logits, 16))

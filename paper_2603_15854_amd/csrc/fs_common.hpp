@@ -35,6 +35,7 @@ struct Stage1Params {
     float* lse_sum;           // [B, T] sum of exp(z - max) per (row, tile)
     // FP8 weights (kernels instantiated for one-byte W elements only): W points at E4M3 codes
     const float* w_scale = nullptr;   // [V] fp32 per-row scale of the logits, or nullptr (= 1)
+    const uint8_t* w4_scales = nullptr;   // MXFP4 (tiled kernel, W4): E8M0 block scales [V, D / 32]
     // epilogue mode bits (FS_FLAG_GREEDY, FS_FLAG_EXACT_LOG of the C ABI)
     uint32_t epi_flags = 0;
     // Truncated supports (kernels instantiated with TOPK only): the topk_k best candidates of every
@@ -305,5 +306,19 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi)
     v.w = __builtin_bit_cast(uint32_t, d);
     return __builtin_bit_cast(bf16x8, v);
 }
+
+// Eight E2M1 codes (one dword, element k in nibble k) times 2^(e - 127) -> eight bf16 values.
+__device__ __forceinline__ bf16x8 mxfp4x8_to_bf16x8(uint32_t codes, uint32_t e8m0)
+{
+    // 2^(e - 127) as an fp32: exponent field e (e = 0 is the denormal 2^-127)
+    const float scale = __uint_as_float(e8m0 ? e8m0 << 23 : 0x00400000u);
+    uint4 v;
+    v.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0));
+    v.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1));
+    v.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2));
+    v.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3));
+    return __builtin_bit_cast(bf16x8, v);
+}
+
 
 }  // namespace fs

@@ -11,13 +11,15 @@ namespace fs {
 // BOTH: also build the form with cacheable W loads for launches with several batch tiles (the
 // workgroups that share a W tile then run on one XCD and the second read hits its L2); without it
 // such launches stream W with non-temporal loads like single-batch-tile ones.
-template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = false, bool BOTH = false, bool TOPK = false>
+template <class Cfg, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = false, bool BOTH = false, bool TOPK = false,
+          bool W4 = false>
 fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
-    if (!KRAG && p.D % (WCODES ? 128 : 64) != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
-    // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles; the
-    // per-tile top-k epilogue stages the keys of the whole tile ([BT][VT + 4] floats)
-    constexpr size_t kLdsLoop = 2 * ((size_t)Cfg::kWBytes + (WCODES ? 2 : 1) * (size_t)Cfg::kHBytes);
+    if (!KRAG && p.D % (W4 ? 256 : WCODES ? 128 : 64) != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
+    // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles (four with
+    // MXFP4 codes, plus 8 scale bytes per row); the per-tile top-k epilogue stages the keys of the whole
+    // tile ([BT][VT + 4] floats)
+    constexpr size_t kLdsLoop = 2 * ((size_t)Cfg::kWBytes + (W4 ? 4 : WCODES ? 2 : 1) * (size_t)Cfg::kHBytes + (W4 ? Cfg::VT * 8 : 0));
     constexpr size_t kLdsKeys = TOPK ? (size_t)Cfg::BT * (Cfg::VT + 4) * 4 : 0;
     constexpr size_t kLds = kLdsLoop > kLdsKeys ? kLdsLoop : kLdsKeys;
     static_assert(kLds <= kLdsPerCU, "tile shape does not fit LDS");
@@ -28,8 +30,8 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
     int dev = 0;
     const fs_status ds = current_device(&dev, nullptr);
     if (ds != FS_OK) return ds;
-    auto k_stream = stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES, KRAG, TOPK>;
-    auto k_shared = stage1_tiled2_kernel<Cfg, !BOTH, FULL, WB, WCODES, KRAG, TOPK>;   // the same kernel unless BOTH
+    auto k_stream = stage1_tiled2_kernel<Cfg, true, FULL, WB, WCODES, KRAG, TOPK, W4>;
+    auto k_shared = stage1_tiled2_kernel<Cfg, !BOTH, FULL, WB, WCODES, KRAG, TOPK, W4>;   // the same kernel unless BOTH
     static PerDevice<> state;
     if (!state.attr[dev].load(std::memory_order_acquire)) {
         if (allow_lds(k_stream, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;

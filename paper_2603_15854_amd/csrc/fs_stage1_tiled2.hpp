@@ -87,27 +87,36 @@ struct Tiled2Cfg {
 // candidate per (row, 128-id tile) the epilogue writes several, sorted and packed.  The keys of the
 // workgroup tile are staged in LDS as [BT][VT + 4] floats and one wave handles a (row, candidate
 // tile) unit, four units at once: the p.topk_k <= 8 best of every unit (wave_top_m).
-template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, bool TOPK = false>
+// W4 (with WB = 1, WCODES): MXFP4 weights.  p.W holds E2M1 codes, two per byte, p.w4_scales one E8M0 byte
+// per 32 elements of a row.  A K step is 256 elements = again the same 128 bytes of a W row; LDS holds
+// the codes and, behind the tiles, the step's 8 scale bytes of every row; the hidden tile of a step is
+// four 64-element sub-tiles; a lane reads the 8 codes of its MFMA operand as one dword and widens them
+// with the block scale (mxfp4x8_to_bf16x8).  Whole K steps only (D % 256 == 0).
+template <class Cfg, bool STREAM_W, bool FULL = false, int WB = 2, bool WCODES = false, bool KRAG = true, bool TOPK = false,
+          bool W4 = false>
 __global__ void __launch_bounds__(Cfg::kThreads, Cfg::OCC)
 stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 {
     static_assert(!TOPK || (!FULL && WB == 2), "per-tile top-k: bf16 weights, plain transform");
     static_assert(!WCODES || WB == 1, "codes in LDS only for one-byte W elements");
+    static_assert(!W4 || (WCODES && !KRAG && !FULL && Cfg::VT <= Cfg::kThreads), "MXFP4: codes in LDS, whole K steps, plain transform");
     constexpr int BT = Cfg::BT, WM = Cfg::WM, WN = Cfg::WN, RB = Cfg::RB, CB = Cfg::CB, GS = Cfg::GS;
-    constexpr int KS = WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
+    constexpr int KS = W4 ? 4 * Cfg::kKS : WCODES ? 2 * Cfg::kKS : Cfg::kKS, VT = Cfg::VT, RPP = Cfg::kRowsPerPass;
     constexpr int HH = KS / 64;                      // 64-element hidden sub-tiles per K step
     constexpr int NHL = Cfg::kHLoads * HH;           // hidden loads per thread and K step
-    constexpr int WEPC = 16 / WB;                    // W elements per 16-byte load
+    constexpr int WEPC = W4 ? 32 : 16 / WB;          // W elements per 16-byte load
     constexpr int WCH = KS / WEPC;                   // loads per W row and K step (8 or 4)
     constexpr int WRPP = Cfg::kThreads / WCH;        // W rows one workgroup-wide load covers
     constexpr int NWL = VT / WRPP;                   // W loads per thread and K step
     static_assert(VT % WRPP == 0 && NWL >= 1, "W tile rows per load pass");
     constexpr int HSUB = BT * 128;                   // bytes of one hidden sub-tile
-    constexpr int BUFB = Cfg::kWBytes + HH * HSUB;   // bytes of one LDS buffer (one K step)
+    constexpr int SCB = W4 ? VT * 8 : 0;             // scale bytes of one K step (MXFP4)
+    constexpr int BUFB = Cfg::kWBytes + HH * HSUB + SCB;   // bytes of one LDS buffer (one K step)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     auto w_lds = [&](int buf) { return smem + buf * BUFB; };
     auto h_lds = [&](int buf) { return smem + buf * BUFB + Cfg::kWBytes; };
+    auto s_lds = [&](int buf) { return smem + buf * BUFB + Cfg::kWBytes + HH * HSUB; };
     // epilogue scratch, aliased onto the tile buffers: first written after the barrier that ends
     // the last K step, when no wave reads or parks tiles any more
     float2* wave_cand = reinterpret_cast<float2*>(smem);                        // [WM][BT]
@@ -148,6 +157,7 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     constexpr int NSET = Cfg::NSET;
     uint4 wst[NSET][GS][NWL];        // NSET groups of GS steps
     uint4 hst[NSET][NHL];            // NSET steps
+    uint2 sst[NSET][GS];             // MXFP4: the 8 scale bytes of row tid % VT, per step
 
     // Every load of the K loop is unconditional, so the compiler can count the loads in flight and
     // wait for exactly the step it parks (s_waitcnt vmcnt(N)) instead of draining the prefetch:
@@ -164,14 +174,26 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
             int row = tile_row0 + wld_row + WRPP * i;
             row = row < V - 1 ? row : V - 1;
             row = over ? tile_row0 : row;
-            const uint16_t* src = reinterpret_cast<const uint16_t*>(
-                reinterpret_cast<const unsigned char*>(p.W) + ((size_t)row * D + k) * WB);
+            const size_t off = W4 ? ((size_t)row * D + k) >> 1 : ((size_t)row * D + k) * WB;
+            const uint16_t* src = reinterpret_cast<const uint16_t*>(reinterpret_cast<const unsigned char*>(p.W) + off);
             wr[i] = STREAM_W ? ld_global_16B_stream(src) : ld_global_16B(src);
         }
     };
-    auto fetch_w_group = [&](uint4 (&grp)[GS][NWL], int group) {
+    // MXFP4: scale bytes k0/32 .. k0/32 + 7 of row tile_row0 + tid % VT (clamped like the W rows)
+    auto fetch_s = [&](uint2& sr, int k0) {
+        const bool over = k0 >= D;
+        int row = tile_row0 + (tid % VT);
+        row = row < V - 1 ? row : V - 1;
+        row = over ? tile_row0 : row;
+        const int kb = over ? 0 : k0 >> 5;
+        sr = *reinterpret_cast<const uint2*>(p.w4_scales + (size_t)row * (D >> 5) + kb);
+    };
+    auto fetch_w_group = [&](uint4 (&grp)[GS][NWL], uint2 (&sgrp)[GS], int group) {
 #pragma unroll
-        for (int s = 0; s < GS; ++s) fetch_w(grp[s], kmap(group * GS + s) * KS);
+        for (int s = 0; s < GS; ++s) {
+            fetch_w(grp[s], kmap(group * GS + s) * KS);
+            if constexpr (W4) fetch_s(sgrp[s], kmap(group * GS + s) * KS);
+        }
     };
     auto fetch_h = [&](uint4 (&hr)[NHL], int k0) {
         const bool over = k0 >= D;
@@ -188,8 +210,11 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         }
     };
     // park K step `step` (registers -> LDS buffer buf)
-    auto park = [&](const uint4 (&wr)[NWL], const uint4 (&hr)[NHL], int buf, int step) {
+    auto park = [&](const uint4 (&wr)[NWL], const uint2& sr, const uint4 (&hr)[NHL], int buf, int step) {
         const bool wzero = k_ragged && (step * KS + wld_chunk * WEPC >= D);   // only in the last step
+        if constexpr (W4) {
+            if (tid < VT) *reinterpret_cast<uint2*>(s_lds(buf) + tid * 8) = sr;
+        }
 #pragma unroll
         for (int i = 0; i < NWL; ++i) {
             const int r = wld_row + WRPP * i;
@@ -223,6 +248,12 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         for (int j = 0; j < CB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto compute = [&](int buf) {
+        uint2 sc[RB];                         // MXFP4: the step's 8 scale bytes of this lane's RB operand rows
+        if constexpr (W4) {
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+                sc[i] = *reinterpret_cast<const uint2*>(s_lds(buf) + (wm * (16 * RB) + i * 16 + n) * 8);
+        }
 #pragma unroll
         for (int s = 0; s < KS / 32; ++s) {   // 32 contraction elements per MFMA
             const int c = 4 * (s & 1) + g;    // hidden chunk inside its 64-element sub-tile
@@ -230,7 +261,11 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 #pragma unroll
             for (int i = 0; i < RB; ++i) {
                 const int r = wm * (16 * RB) + i * 16 + n;
-                if constexpr (WCODES) {       // 8 codes: half of 16-byte chunk 2 s + g / 2
+                if constexpr (W4) {           // 8 codes: dword g of 16-byte chunk s (= K step of 32 elements)
+                    const uint32_t codes = *reinterpret_cast<const uint32_t*>(w_lds(buf) + tile_off(r, s) + (g << 2));
+                    const uint32_t e = ((s < 4 ? sc[i].x : sc[i].y) >> (8 * (s & 3))) & 0xFFu;
+                    a[i] = mxfp4x8_to_bf16x8(codes, e);
+                } else if constexpr (WCODES) {       // 8 codes: half of 16-byte chunk 2 s + g / 2
                     const uint2 q = *reinterpret_cast<const uint2*>(
                         w_lds(buf) + tile_off(r, 2 * s + (g >> 1)) + ((g & 1) << 3));
                     a[i] = e4m3x8_to_bf16x8(q.x, q.y);
@@ -253,13 +288,13 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
 
     // prologue: W groups 0 and 1 and hidden steps 0 and 1 in flight; step 0 parked
     // (fetches past the end of K read one fixed cache line)
-    fetch_w_group(wst[0], 0);
-    if constexpr (NSET == 2) fetch_w_group(wst[1], 1);
+    fetch_w_group(wst[0], sst[0], 0);
+    if constexpr (NSET == 2) fetch_w_group(wst[1], sst[1], 1);
     fetch_h(hst[0], kmap(0) * KS);
     if constexpr (NSET == 2) fetch_h(hst[1], kmap(1) * KS);
-    park(wst[0][0], hst[0], 0, kmap(0));
+    park(wst[0][0], sst[0][0], hst[0], 0, kmap(0));
     fetch_h(hst[0], kmap(NSET) * KS);
-    if (GS == 1) fetch_w_group(wst[0], NSET);
+    if (GS == 1) fetch_w_group(wst[0], sst[0], NSET);
     __syncthreads();
     // One body = 2*GS steps, after which the register sets are back in their starting roles.
     // Full bodies run without any condition (parking a step past the end only fills the LDS
@@ -272,9 +307,9 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
                 const int nset = NSET == 2 ? ((u + 1) / GS) & 1 : 0;   // register set and slot of step t + 1
                 const int hset = NSET == 2 ? (u + 1) & 1 : 0;
                 const int nslot = (u + 1) % GS;
-                park(wst[nset][nslot], hst[hset], (u + 1) & 1, kmap(t + 1));
+                park(wst[nset][nslot], sst[nset][nslot], hst[hset], (u + 1) & 1, kmap(t + 1));
                 fetch_h(hst[hset], kmap(t + 1 + NSET) * KS);
-                if (nslot == GS - 1) fetch_w_group(wst[nset], (t + 1) / GS + NSET);   // set is free again
+                if (nslot == GS - 1) fetch_w_group(wst[nset], sst[nset], (t + 1) / GS + NSET);   // set is free again
                 compute(u & 1);
                 __syncthreads();
             }

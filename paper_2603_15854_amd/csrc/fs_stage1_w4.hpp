@@ -29,21 +29,6 @@ constexpr size_t w4_lds_bytes(int kpw, int nw)
     return (size_t)nw * (16 * kpw * 16) + (size_t)8 * nw * 1024 + (size_t)nw * 16 * 8 * 2;
 }
 
-typedef __bf16 bf16x2_w4 __attribute__((ext_vector_type(2)));
-
-// Eight E2M1 codes (one dword, element k in nibble k) times 2^(e - 127) -> eight bf16 values.
-__device__ __forceinline__ bf16x8 mxfp4x8_to_bf16x8(uint32_t codes, uint32_t e8m0)
-{
-    // 2^(e - 127) as an fp32: exponent field e (e = 0 is the denormal 2^-127)
-    const float scale = __uint_as_float(e8m0 ? e8m0 << 23 : 0x00400000u);
-    uint4 v;
-    v.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0));
-    v.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1));
-    v.z = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2));
-    v.w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3));
-    return __builtin_bit_cast(bf16x8, v);
-}
-
 // KPW: K steps per wave (16: hidden slice in 64 VGPRs, 32: in 128); MAXW: waves per workgroup
 // (= D / (32 KPW)); PFD: row-tiles of W in flight per wave.
 // p.W points at the codes [V, D/2] bytes, w_scales at the E8M0 bytes [V, D/32].

@@ -43,7 +43,11 @@ def test_on_chip_decode_of_every_code_and_scale(fs, orc):
 
 
 CASES = [(1, 512, 4096), (5, 512, 1189), (16, 4096, 2048 + 64), (9, 1024, 520), (3, 1536, 127), (2, 512, 5),
-         (16, 3584, 700), (7, 8192, 300), (12, 7168, 400), (16, 5120, 130)]
+         (16, 3584, 700), (7, 8192, 300), (12, 7168, 400), (16, 5120, 130),
+         # the tiled form: B > 16 (256 x 32 and 256 x 64 tiles, several batch tiles, ragged vocabulary tiles),
+         # and small batches at hidden sizes the split-K form does not take (D % 512 != 0, D > 8192)
+         (17, 512, 700), (32, 1024, 1189), (40, 512, 515), (64, 768, 300), (100, 256, 640), (130, 1024, 257),
+         (4, 768, 520), (3, 256, 127), (5, 8704, 300), (33, 4096, 1000)]
 
 
 @pytest.mark.parametrize("shape", CASES)
@@ -98,9 +102,28 @@ def test_w4_at_llama_shape(fs, orc):
     assert v.ok, (str(v), v.failures[:3])
 
 
+def test_w4_at_llama_shape_larger_batches(fs, orc):
+    # the tiled form at full size, every row judged
+    w = wl.WORKLOADS["C2"]
+    W = wl.make_weights(w)
+    codes, scales = wl.quantize_mxfp4(W)
+    cd, sd = dev(codes, np.uint8), dev(scales, np.uint8)
+    for B in (32, 64):
+        print(f"w4 parity at D=4096 V=128256 B={B}", flush=True)
+        H = wl.make_hidden(w, B)
+        tau = wl.make_temperature(w, B)
+        seeds = wl.make_row_seeds(w, B)
+        ref = orc.sample_w4(H, codes, scales, tau, row_seeds=seeds)
+        gi, gv = fs.flash_sample_w4(to_device_bf16(H), cd, sd, dev(tau, np.float32), row_seeds=to_device_seeds(seeds))
+        torch.cuda.synchronize()
+        v = judge(orc, H, codes, tau, gi.cpu().numpy(), gv.cpu().numpy(), ref, row_seeds=seeds, w4_scales=scales)
+        print(f"[parity] w4 C2 B={B}: {v}", flush=True)
+        assert v.ok and v.rows == B, (B, str(v), v.failures[:3])
+
+
 def test_w4_shapes_outside_the_kernel_are_refused(fs):
     tau = torch.ones(17, device="cuda")
-    for B, D in [(17, 512), (4, 256), (4, 4608 + 512 * 8)]:
+    for B, D in [(17, 288), (4, 160), (4, 4608 + 32)]:          # hidden sizes that are not whole K steps of 256
         H = torch.zeros((B, D), dtype=torch.bfloat16, device="cuda")
         W4 = torch.zeros((256, D // 2), dtype=torch.uint8, device="cuda")
         S = torch.zeros((256, D // 32), dtype=torch.uint8, device="cuda")
