@@ -311,7 +311,8 @@ __device__ __forceinline__ bf16x8 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi)
 __device__ __forceinline__ bf16x8 mxfp4x8_to_bf16x8(uint32_t codes, uint32_t e8m0)
 {
     // 2^(e - 127) as an fp32: exponent field e (e = 0 is the denormal 2^-127)
-    const float scale = __uint_as_float(e8m0 ? e8m0 << 23 : 0x00400000u);
+    const uint32_t bits = e8m0 << 23;          // 0 only for e = 0; every other exponent field is above 0x00400000
+    const float scale = __uint_as_float(bits > 0x00400000u ? bits : 0x00400000u);
     uint4 v;
     v.x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0));
     v.y = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1));
