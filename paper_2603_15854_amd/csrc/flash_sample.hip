@@ -643,13 +643,13 @@ TopkWs carve_topk(void* ws, int B, int V, int k, bool fused)
 
 fs_status check_topk(int B, int k, float top_p, int mode, uint32_t flags, const void* temperature, const void* out_idx,
                      const void* out_val, const void* topk_val, const void* topk_idx, const void* n_kept,
-                     const void* row_seeds)
+                     const void* row_seeds, uint32_t tune_bits = 0u)
 {
     if (k < 1 || k > FS_TOPK_MAX_K) return FS_ERR_SHAPE;
     if (mode != FS_TOPK_TRUNCATE && mode != FS_TOPK_GUMBEL) return FS_ERR_SHAPE;
     if (!(top_p > 0.0f) || top_p > 1.0f) return FS_ERR_SHAPE;                 // also rejects NaN
     if (mode == FS_TOPK_GUMBEL && top_p != 1.0f) return FS_ERR_SHAPE;         // the candidates are the draw: nothing to cut
-    if (flags & ~(uint32_t)FS_FLAG_EXACT_LOG) return FS_ERR_UNSUPPORTED;
+    if (flags & ~((uint32_t)FS_FLAG_EXACT_LOG | tune_bits)) return FS_ERR_UNSUPPORTED;
     if (B == 0) return FS_OK;
     if (!temperature || !out_idx || !out_val) return FS_ERR_NULL;
     if (!aligned(temperature, 4) || !aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(topk_val, 4) ||
@@ -675,7 +675,7 @@ fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int
 {
     fs_status s = check_problem(hidden, W, B, D, V, row_offset, vocab_offset);
     if (s != FS_OK) return s;
-    s = check_topk(B, k, top_p, mode, flags, temperature, out_idx, out_val, topk_val, topk_idx, n_kept, row_seeds);
+    s = check_topk(B, k, top_p, mode, flags, temperature, out_idx, out_val, topk_val, topk_idx, n_kept, row_seeds, kTuneMask);
     if (s != FS_OK || B == 0) return s;
     if (D % 64 != 0) return FS_ERR_UNSUPPORTED;      // the per-tile top-k epilogue exists for whole K steps only
     const TopkWs ws = carve_topk(workspace, B, V, k, true);
@@ -684,7 +684,7 @@ fs_status flash_sample_topk(const void* hidden, const void* W, int B, int D, int
     const int m = topk_tile_m(k, B);
     Stage1Params p = make_params(hidden, W, B, D, V, temperature, seed, row_seeds, row_offset, vocab_offset, flags);
     p.topk_out = ws.cand; p.topk_k = m; p.topk_mode = mode;
-    s = launch_stage1_topk(p, st);
+    s = launch_stage1_topk(p, (int)((flags & kTuneMask) >> 16), st);
     if (s != FS_OK) return s;
     const int n_cand = p.T * m;
     const TopkFinish fin = {top_p, mode, seed, row_seeds, row_offset, epi_bits(flags), out_idx, out_val, topk_val, topk_idx, n_kept};

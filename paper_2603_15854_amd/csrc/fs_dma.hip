@@ -7,7 +7,7 @@ namespace fs {
 
 namespace {
 
-template <class Cfg, bool FULL>
+template <class Cfg, bool FULL, bool TOPK = false>
 fs_status launch_dma(const Stage1Params& p, hipStream_t st)
 {
     if (p.D % Cfg::kKS != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
@@ -19,8 +19,8 @@ fs_status launch_dma(const Stage1Params& p, hipStream_t st)
     int dev = 0;
     const fs_status ds = current_device(&dev, nullptr);
     if (ds != FS_OK) return ds;
-    auto k_stream = stage1_dma_kernel<Cfg, true, FULL>;    // one batch tile: W is read once, non-temporal
-    auto k_shared = stage1_dma_kernel<Cfg, false, FULL>;   // several: the second read of a W tile hits L2
+    auto k_stream = stage1_dma_kernel<Cfg, true, FULL, TOPK>;    // one batch tile: W is read once, non-temporal
+    auto k_shared = stage1_dma_kernel<Cfg, false, FULL, TOPK>;   // several: the second read of a W tile hits L2
     static PerDevice<> state;
     if (!state.attr[dev].load(std::memory_order_acquire)) {
         if (allow_lds(k_stream, kLdsPerCU) != hipSuccess) return FS_ERR_HIP;
@@ -37,6 +37,12 @@ fs_status launch_stage1_dma(const Stage1Params& p, bool full, int batch_tile, hi
 {
     if (batch_tile == 128) return full ? launch_dma<DmaCfg<128>, true>(p, st) : launch_dma<DmaCfg<128>, false>(p, st);
     return full ? launch_dma<DmaCfg<256>, true>(p, st) : launch_dma<DmaCfg<256>, false>(p, st);
+}
+
+// The same kernel with the per-tile candidate epilogue of the truncated-support path.
+fs_status launch_stage1_dma_topk(const Stage1Params& p, int batch_tile, hipStream_t st)
+{
+    return batch_tile == 128 ? launch_dma<DmaCfg<128>, false, true>(p, st) : launch_dma<DmaCfg<256>, false, true>(p, st);
 }
 
 }  // namespace fs

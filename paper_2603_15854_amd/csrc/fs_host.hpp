@@ -70,7 +70,8 @@ fs_status launch_stage1_dma(const Stage1Params& p, bool full, int batch_tile, hi
 fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStream_t st);
 fs_status launch_stage1_w4(const Stage1Params& p, const uint8_t* scales, int wgs_per_cu, hipStream_t st);
 // truncated supports (fs_topk.hip)
-fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st);
+fs_status launch_stage1_topk(const Stage1Params& p, int shape, hipStream_t st);
+fs_status launch_stage1_dma_topk(const Stage1Params& p, int batch_tile, hipStream_t st);   // fs_dma.hip
 fs_status launch_stage1_splitk_topk(const Stage1Params& p, hipStream_t st);   // fs_splitk.hip
 struct TopkPlan {                 // selection levels for rows of N candidates (topk_plan)
     static constexpr int kMaxLevels = 4;

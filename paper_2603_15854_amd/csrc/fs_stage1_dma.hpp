@@ -118,7 +118,7 @@ __device__ __forceinline__ void mfma_acc(f32x4& acc, const bf16x8 a, const bf16x
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
-template <class Cfg, bool STREAM_W, bool FULL = false>
+template <class Cfg, bool STREAM_W, bool FULL = false, bool TOPK = false>
 __global__ void __launch_bounds__(Cfg::kThreads, 1)
 stage1_dma_kernel(const Stage1Params p, const int nbt)
 {
@@ -300,8 +300,9 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
                  : "+a"(acc[0][CB - 1]), "+a"(acc[1][CB - 1]), "+a"(acc[2][CB - 1]), "+a"(acc[3][CB - 1]),
                    "+a"(acc[4][CB - 1]), "+a"(acc[5][CB - 1]), "+a"(acc[6][CB - 1]), "+a"(acc[7][CB - 1]));
 
-    // Epilogue.  acc[i][j][q] = logit of vocabulary row tile_row0 + 128 wm + 16 i + 4 g + q, batch row
-    // b0 + (BT/2) wn + 16 j + n.  Registers cannot be indexed by a loop variable, and the epilogue
+    // acc[i][j][q] = logit of vocabulary row tile_row0 + 128 wm + 16 i + 4 g + q, batch row
+    // b0 + (BT/2) wn + 16 j + n.
+    // Epilogue.  Registers cannot be indexed by a loop variable, and the epilogue
     // unrolled over all 8 x CB accumulator tiles is several hundred KB of code that each wave walks
     // through once per tile (instruction fetch and spills then cost more than its arithmetic).  So
     // each wave parks its accumulators in LDS, which is free now, CJ column blocks at a time, and
@@ -316,6 +317,85 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
 #pragma unroll
     for (int j = 0; j < CB; ++j) rowc_lds[j * 64] = rowc[j];
     const int ctile = tile * (VT / kVocabTile) + wm;
+    if constexpr (TOPK) {
+        // Truncated supports: the m best keys of every (batch row, 128-id tile) instead of one
+        // candidate.  A wave's 128 ids are one candidate tile and a lane holds 32 of them for each of
+        // its batch rows, so a lane keeps a sorted list of the best m of those 32 in registers (one
+        // insertion per key), the four lanes that share a row merge their lists, and each writes its
+        // share of the m words.  No scalar work, no cross-lane traffic before the merge.
+        const int vl0 = tile_row0 + wm * kVocabTile;            // first vocabulary row of this wave
+        const int kt = p.topk_k;
+        const bool noisy = p.topk_mode == kTopkGumbel;
+        const int nvalid = vl0 + kVocabTile <= V ? 1 << 20 : V - vl0 - 4 * g;   // local ids 16 i + q below this exist
+        auto rows = [&](auto mc) {
+            constexpr int M = decltype(mc)::value;
+#pragma unroll
+            for (int jc = 0; jc < CB; jc += CJ) {
+#pragma unroll
+                for (int jj = 0; jj < CJ; ++jj)
+#pragma unroll
+                    for (int i = 0; i < RB; ++i) park[(jj * RB + i) * 64] = acc[i][jc + jj];
+#pragma unroll 1
+                for (int jj = 0; jj < CJ; ++jj) {
+                    const int b = b0 + wn * (BT / 2) + (jc + jj) * 16 + n;
+                    const f32x4 rc = rowc_lds[(jc + jj) * 64];
+                    const float inv_tau = rc[0];
+                    const uint64_t sd = (uint64_t)__float_as_uint(rc[1]) | ((uint64_t)__float_as_uint(rc[2]) << 32);
+                    uint32_t ka[M];
+                    int32_t ke[M];
+#pragma unroll
+                    for (int s = 0; s < M; ++s) { ka[s] = 0u; ke[s] = 0; }
+#pragma unroll 1
+                    for (int i0 = 0; i0 < RB; i0 += U) {
+                        f32x4 y[U];
+                        float gn[U][4];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            y[u] = park[(jj * RB + i0 + u) * 64];
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) gn[u][q] = 0.0f;
+                        }
+                        if (noisy) {
+#pragma unroll
+                            for (int u = 0; u < U; ++u)
+                                gumbel4(sd, (uint32_t)(uint64_t)(p.row_offset + (b < B ? b : B - 1)),
+                                        (uint32_t)(p.vocab_offset + vl0 + (i0 + u) * 16 + 4 * g), gn[u],
+                                        (p.epi_flags & kEpiExactLog) != 0u);
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                const int e = (i0 + u) * 16 + q;
+                                const uint32_t o = topk_ordered(fmaf(y[u][q], inv_tau, gn[u][q]));
+                                top_insert<M>(ka, ke, e < nvalid ? o : 0u, e);
+                            }
+                    }
+                    // the row's best m: merge with the lanes 16 and 32 away (same row, other ids)
+                    uint64_t w[M];
+                    const int32_t id0 = p.vocab_offset + vl0 + 4 * g;
+#pragma unroll
+                    for (int s = 0; s < M; ++s)
+                        w[s] = ka[s] ? ((uint64_t)ka[s] << 32) | (uint64_t)(~(uint32_t)(id0 + ke[s])) : kTopkPad;
+                    top_merge<M>(w, 16);
+                    top_merge<M>(w, 32);
+                    if (b < B && ctile < T) {
+                        uint64_t* dst = p.topk_out + ((size_t)b * T + ctile) * (size_t)kt;
+#pragma unroll
+                        for (int s0 = 0; s0 < M; s0 += 4) {
+                            uint64_t mine = w[s0];
+#pragma unroll
+                            for (int t = 1; t < 4; ++t) mine = g == t ? w[s0 + t] : mine;
+                            if (s0 + g < kt) dst[s0 + g] = mine;
+                        }
+                    }
+                }
+            }
+        };
+        if (kt <= 4) rows(std::integral_constant<int, 4>{});
+        else rows(std::integral_constant<int, 8>{});
+        return;
+    }
     // No check is needed inside a quad when the whole tile lies inside the vocabulary, ids are
     // aligned to the Philox blocks, and nothing but the default sampling epilogue is asked for.
     const bool fast = !FULL && p.cand_val && !p.logits && p.epi_flags == 0u && (p.vocab_offset & 3) == 0 &&

@@ -119,13 +119,21 @@ __device__ __forceinline__ void splitk_finish_tile(const Stage1Params& p, const 
         constexpr int U = 4;
         const int kt = p.topk_k;
         for (int ub = wave * U; ub < 16; ub += nw * U) {      // unit = batch column
+            // every address is inside the key array: read first, all eight in flight, then mask
+            float f0[U], f1[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                f0[q] = keys[(ub + q) * KSTRIDE + lane];
+                f1[q] = keys[(ub + q) * KSTRIDE + 64 + lane];
+            }
             uint32_t k0[U], k1[U];
             int32_t id0[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) {
                 const int e0 = tile_row0 + lane, e1 = e0 + 64;
-                k0[q] = e0 < V ? topk_ordered(keys[(ub + q) * KSTRIDE + lane]) : 0u;
-                k1[q] = e1 < V ? topk_ordered(keys[(ub + q) * KSTRIDE + 64 + lane]) : 0u;
+                const uint32_t o0 = topk_ordered(f0[q]), o1 = topk_ordered(f1[q]);
+                k0[q] = e0 < V ? o0 : 0u;
+                k1[q] = e1 < V ? o1 : 0u;
                 id0[q] = p.vocab_offset + tile_row0;
             }
             uint64_t res[U];

@@ -349,14 +349,23 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
         static_assert(NUNIT % (Cfg::kWaves * U) == 0, "units per wave");
         const int kt = p.topk_k;
         for (int ub = wave * U; ub < NUNIT; ub += Cfg::kWaves * U) {
+            // every address is inside the key array: read first, all eight in flight, then mask
+            float f0[U], f1[U];
+#pragma unroll
+            for (int q = 0; q < U; ++q) {
+                const int u = ub + q, bl = u % BT, ct = u / BT;
+                f0[q] = keys[bl * KSTRIDE + ct * kVocabTile + lane];
+                f1[q] = keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane];
+            }
             uint32_t k0[U], k1[U];
             int32_t id0[U];
 #pragma unroll
             for (int q = 0; q < U; ++q) {
-                const int u = ub + q, bl = u % BT, ct = u / BT;
+                const int u = ub + q, ct = u / BT;
                 const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-                k0[q] = e0 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + lane]) : 0u;
-                k1[q] = e1 < V ? topk_ordered(keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane]) : 0u;
+                const uint32_t o0 = topk_ordered(f0[q]), o1 = topk_ordered(f1[q]);
+                k0[q] = e0 < V ? o0 : 0u;
+                k1[q] = e1 < V ? o1 : 0u;
                 id0[q] = p.vocab_offset + tile_row0 + ct * kVocabTile;
             }
             uint64_t res[U];

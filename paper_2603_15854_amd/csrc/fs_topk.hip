@@ -5,15 +5,32 @@
 
 namespace fs {
 
-// Stage 1 with the per-tile candidate epilogue: the split-K kernel in the decode regime, else three
-// tile shapes of the tiled kernel (by batch size), whole K steps only.
-fs_status launch_stage1_topk(const Stage1Params& p, hipStream_t st)
+// Stage 1 with the per-tile candidate epilogue, whole K steps only.  shape = 0: the split-K kernel in
+// the decode regime, two shapes of the tiled kernel up to 64 rows, its 256 x 128 shape up to 128 rows,
+// and above that the kernel with direct global -> LDS loads in the tile pick_tile_shape takes for the
+// plain path.  shape = 3, 6, 7, 12, 13 forces that shape (tuning aid and test hook).
+fs_status launch_stage1_topk(const Stage1Params& p, int shape, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
-    if (p.B <= 16 && p.D <= 4096) return launch_stage1_splitk_topk(p, st);
-    if (p.B <= 32) return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
-    if (p.B <= 64) return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
-    return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);                   // 256 x 128, batch tiles XCD-paired
+    if (shape == 0) {
+        if (p.B <= 16 && p.D <= 4096) return launch_stage1_splitk_topk(p, st);
+        if (p.B <= 128) {
+            shape = p.B <= 32 ? 6 : p.B <= 64 ? 7 : 3;
+        } else {
+            int cus = 0;
+            const fs_status ds = current_device(nullptr, &cus);
+            if (ds != FS_OK) return ds;
+            shape = pick_tile_shape(p.B, p.D, p.V, cus);
+        }
+    }
+    switch (shape) {
+    case 6: return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
+    case 7: return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
+    case 3: return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);    // 256 x 128, batch tiles XCD-paired
+    case 12: return launch_stage1_dma_topk(p, 256, st);
+    case 13: return launch_stage1_dma_topk(p, 128, st);
+    default: return FS_ERR_UNSUPPORTED;
+    }
 }
 
 // Selection levels for rows of N candidates: every level cuts a row into chunks of at most kSelChunk

@@ -192,4 +192,45 @@ __device__ __forceinline__ void wave_top_m(uint32_t (&k0)[U], uint32_t (&k1)[U],
     }
 }
 
+// A lane's sorted list of its M best (ordered key, payload) pairs, best first; ka = 0 marks an empty
+// place.  Inserts (x, e) behind every entry with a key >= x: among equal keys the pair inserted first
+// stays ahead, so a caller that inserts in ascending id order keeps the lowest ids.
+template <int M>
+__device__ __forceinline__ void top_insert(uint32_t (&ka)[M], int32_t (&ke)[M], uint32_t x, int32_t e)
+{
+    bool c[M];
+#pragma unroll
+    for (int s = 0; s < M; ++s) c[s] = x > ka[s];
+#pragma unroll
+    for (int s = M - 1; s > 0; --s) {
+        ka[s] = c[s - 1] ? ka[s - 1] : c[s] ? x : ka[s];
+        ke[s] = c[s - 1] ? ke[s - 1] : c[s] ? e : ke[s];
+    }
+    ka[0] = c[0] ? x : ka[0];
+    ke[0] = c[0] ? e : ke[0];
+}
+
+// w: this lane's M packed words in descending order.  Afterwards both this lane and the lane `step`
+// away (lane ^ step) hold the M largest of their 2 M words, in descending order: the elementwise
+// maximum with the partner's list reversed is the upper half as a bitonic sequence, which log2(M)
+// rounds of compare-exchange sort.  Packed words of different ids differ, so both lanes agree.
+template <int M>
+__device__ __forceinline__ void top_merge(uint64_t (&w)[M], int step)
+{
+    uint64_t o[M];
+#pragma unroll
+    for (int s = 0; s < M; ++s) o[s] = __shfl_xor((unsigned long long)w[M - 1 - s], step, kWave);
+#pragma unroll
+    for (int s = 0; s < M; ++s) w[s] = w[s] > o[s] ? w[s] : o[s];
+#pragma unroll
+    for (int d = M / 2; d > 0; d >>= 1)
+#pragma unroll
+        for (int s = 0; s < M; ++s)
+            if ((s & d) == 0) {
+                const uint64_t hi = w[s] > w[s + d] ? w[s] : w[s + d], lo = w[s] > w[s + d] ? w[s + d] : w[s];
+                w[s] = hi;
+                w[s + d] = lo;
+            }
+}
+
 }  // namespace fs

@@ -120,6 +120,25 @@ def test_topk_matches_oracle(fs, orc, case, mode, fused):
     assert near <= max(2, B // 10), (exact, near)
 
 
+@pytest.mark.parametrize("shape", [3, 6, 7, 12, 13])
+@pytest.mark.parametrize("mode", [TRUNC, GUMBEL])
+def test_fused_topk_on_every_stage1_kernel(fs, orc, shape, mode):
+    # the tile shape forced: every kernel with the per-tile candidate epilogue on batch sizes below, at and
+    # above its batch tile, with a vocabulary whose last 128-id tile holds one id (1153) or whose last
+    # 256-row tile is less than half full (1300), and k below and above the candidates kept per tile
+    for B, D, V, k in ((5, 64, 1153, 3), (70, 256, 1300, 50), (140, 512, 1153, 20), (300, 192, 2100, 64)):
+        p = 1.0 if mode == GUMBEL else 0.9
+        print(f"topk shape={shape} mode={mode} B={B} D={D} V={V} k={k}", flush=True)
+        H, W = wl.make_small(D=D, V=V, B=B, data_seed=900 + B + shape, w_row_scale=2.0)
+        tau = np.linspace(0.6, 1.5, B).astype(np.float32)
+        seeds = np.arange(B, dtype=np.uint64) * np.uint64(11) + np.uint64(5)
+        ref = orc.sample_topk(H, W, tau, k, top_p=p, mode=mode, row_seeds=seeds, row_offset=9, vocab_offset=130)
+        got = run(fs, H, W, tau, k, p, mode, True, row_seeds=seeds, row_offset=9, vocab_offset=130,
+                  flags=fs.FS_TUNE_TILE_SHAPE(shape))
+        exact, near = judge_topk(orc, H, W, tau, k, p, mode, ref, got, row_seeds=seeds, row_offset=9, vocab_offset=130)
+        assert near <= max(2, B // 10), (shape, B, exact, near)
+
+
 def test_topk_seeded_random_shapes(fs, orc):
     # a seeded sweep over batch sizes on both sides of every kernel boundary, ragged vocabularies, k, top_p,
     # both modes and forms, and vocabulary offsets that are not multiples of the four ids of a noise block
@@ -262,6 +281,24 @@ def test_topk_at_llama_shape_every_row(fs, orc):
             exact, near = judge_topk(orc, H, Wb, tau, k, pp, mode, ref, got, row_seeds=seeds)
             print(f"[parity] top-k C2 B={B} k={k} p={pp} mode={mode} fused={fused}: exact={exact} near_tie={near}", flush=True)
             assert near <= 2
+
+
+def test_topk_at_llama_shape_large_batch_every_row(fs, orc):
+    # the launch configuration the benchmark times at B = 256 (direct-to-LDS kernel, 256 x 256 tiles), with a
+    # batch tile that is not full; k above the four candidates a tile keeps
+    w = wl.WORKLOADS["C2"]
+    Wb = wl.make_weights(w)
+    Wd = to_device_bf16(Wb)
+    B, k, p = 200, 50, 0.9
+    H = wl.make_hidden(w, B)
+    tau = np.linspace(0.7, 1.3, B).astype(np.float32)
+    seeds = wl.make_row_seeds(w, B)
+    for mode, pp in ((TRUNC, p), (GUMBEL, 1.0)):
+        ref = orc.sample_topk(H, Wb, tau, k, top_p=pp, mode=mode, row_seeds=seeds)
+        got = run(fs, H, Wb, tau, k, pp, mode, True, Wd=Wd, row_seeds=seeds)
+        exact, near = judge_topk(orc, H, Wb, tau, k, pp, mode, ref, got, row_seeds=seeds)
+        print(f"[parity] top-k C2 B={B} k={k} p={pp} mode={mode} fused: exact={exact} near_tie={near}", flush=True)
+        assert near <= B // 10
 
 
 def test_truncated_draw_follows_the_renormalised_softmax_on_the_gpu(fs, orc):
