@@ -6,6 +6,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace fs {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -13,6 +16,19 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int kVocabTile = 128;  // vocabulary ids per candidate (FS_VOCAB_TILE)
 constexpr int kWave = 64;
+
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose
+// index is a constant expression in the body (immediate operands of inline assembly need one)
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 // Arguments of one stage-1 launch (Alg. 1, stage 1).
 struct Stage1Params {
@@ -127,6 +143,49 @@ __device__ __forceinline__ void gumbel4(uint64_t seed, uint32_t row, uint32_t vi
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) g[j] = gumbel_from_word(w[j]);
+    }
+}
+
+// gumbel4 for U quads of one row at once, all with the same vid0 % 4: the U generator chains are
+// independent and the two uniform branches (straddling quads, log mode) are taken once, so a wave that
+// is alone on its SIMD overlaps the chains.
+template <int U>
+__device__ __forceinline__ void gumbel4_multi(uint64_t seed, uint32_t row, const uint32_t (&vid0)[U], float (&g)[U][4],
+                                              bool exact_log)
+{
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t w[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) philox4x32_10(vid0[u] >> 2, row, 0u, 0u, k0, k1, w[u]);
+    const uint32_t sh = vid0[0] & 3u;
+    if (sh != 0u) {
+        uint32_t w2[U][4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) philox4x32_10((vid0[u] >> 2) + 1u, row, 0u, 0u, k0, k1, w2[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint32_t m[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t q = sh + (uint32_t)j;  // 1..6
+                const uint32_t lo = q == 1u ? w[u][1] : q == 2u ? w[u][2] : w[u][3];
+                const uint32_t hi = q == 4u ? w2[u][0] : q == 5u ? w2[u][1] : w2[u][2];
+                m[j] = q < 4u ? lo : hi;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[u][j] = m[j];
+        }
+    }
+    if (exact_log) {    // uniform over the launch
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) g[u][j] = gumbel_from_word_exact(w[u][j]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) g[u][j] = gumbel_from_word(w[u][j]);
     }
 }
 

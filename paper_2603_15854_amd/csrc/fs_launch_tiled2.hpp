@@ -17,11 +17,9 @@ fs_status launch_tiled2(const Stage1Params& p, hipStream_t st)
 {
     if (!KRAG && p.D % (W4 ? 256 : WCODES ? 128 : 64) != 0) return FS_ERR_UNSUPPORTED;   // whole K steps only
     // LDS: two buffers of one K step; with codes in LDS a step carries two hidden sub-tiles (four with
-    // MXFP4 codes, plus 8 scale bytes per row); the per-tile top-k epilogue stages the keys of the whole
-    // tile ([BT][VT + 4] floats)
+    // MXFP4 codes, plus 8 scale bytes per row)
     constexpr size_t kLdsLoop = 2 * ((size_t)Cfg::kWBytes + (W4 ? 4 : WCODES ? 2 : 1) * (size_t)Cfg::kHBytes + (W4 ? Cfg::VT * 8 : 0));
-    constexpr size_t kLdsKeys = TOPK ? (size_t)Cfg::BT * (Cfg::VT + 4) * 4 : 0;
-    constexpr size_t kLds = kLdsLoop > kLdsKeys ? kLdsLoop : kLdsKeys;
+    constexpr size_t kLds = kLdsLoop;
     static_assert(kLds <= kLdsPerCU, "tile shape does not fit LDS");
     const int nbt = (p.B + Cfg::BT - 1) / Cfg::BT;
     const int macro_tiles = (p.V + Cfg::VT - 1) / Cfg::VT;

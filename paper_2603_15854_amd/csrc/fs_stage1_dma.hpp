@@ -32,25 +32,10 @@
 // from the lane-group merge straight to the candidate buffer, without a cross-wave merge.
 #pragma once
 
-#include <utility>
-
 #include "fs_common.hpp"
 #include "fs_stage1_tiled2.hpp"   // tile_off
 
 namespace fs {
-
-// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose
-// index is a constant expression in the body (immediate operands of inline assembly need one)
-template <int... I, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
 
 template <int BT_>
 struct DmaCfg {
@@ -325,10 +310,10 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
         // share of the m words.  No scalar work, no cross-lane traffic before the merge.
         const int vl0 = tile_row0 + wm * kVocabTile;            // first vocabulary row of this wave
         const int kt = p.topk_k;
-        const bool noisy = p.topk_mode == kTopkGumbel;
         const int nvalid = vl0 + kVocabTile <= V ? 1 << 20 : V - vl0 - 4 * g;   // local ids 16 i + q below this exist
-        auto rows = [&](auto mc) {
+        auto rows = [&](auto mc, auto noisyc) {
             constexpr int M = decltype(mc)::value;
+            constexpr bool NOISY = decltype(noisyc)::value;
 #pragma unroll
             for (int jc = 0; jc < CB; jc += CJ) {
 #pragma unroll
@@ -355,12 +340,12 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
 #pragma unroll
                             for (int q = 0; q < 4; ++q) gn[u][q] = 0.0f;
                         }
-                        if (noisy) {
+                        if constexpr (NOISY) {
+                            uint32_t vid0[U];
 #pragma unroll
-                            for (int u = 0; u < U; ++u)
-                                gumbel4(sd, (uint32_t)(uint64_t)(p.row_offset + (b < B ? b : B - 1)),
-                                        (uint32_t)(p.vocab_offset + vl0 + (i0 + u) * 16 + 4 * g), gn[u],
-                                        (p.epi_flags & kEpiExactLog) != 0u);
+                            for (int u = 0; u < U; ++u) vid0[u] = (uint32_t)(p.vocab_offset + vl0 + (i0 + u) * 16 + 4 * g);
+                            gumbel4_multi<U>(sd, (uint32_t)(uint64_t)(p.row_offset + (b < B ? b : B - 1)), vid0, gn,
+                                             (p.epi_flags & kEpiExactLog) != 0u);
                         }
 #pragma unroll
                         for (int u = 0; u < U; ++u)
@@ -392,8 +377,15 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
                 }
             }
         };
-        if (kt <= 4) rows(std::integral_constant<int, 4>{});
-        else rows(std::integral_constant<int, 8>{});
+        using M4 = std::integral_constant<int, 4>;
+        using M8 = std::integral_constant<int, 8>;
+        if (p.topk_mode == kTopkGumbel) {
+            if (kt <= 4) rows(M4{}, std::true_type{});
+            else rows(M8{}, std::true_type{});
+        } else {
+            if (kt <= 4) rows(M4{}, std::false_type{});
+            else rows(M8{}, std::false_type{});
+        }
         return;
     }
     // No check is needed inside a quad when the whole tile lies inside the vocabulary, ids are

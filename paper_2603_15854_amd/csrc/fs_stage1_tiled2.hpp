@@ -21,7 +21,7 @@
 #include <type_traits>
 
 #include "fs_common.hpp"
-#include "fs_topk_common.hpp"   // wave_sort128_desc
+#include "fs_topk_common.hpp"   // top_insert, top_merge
 
 namespace fs {
 
@@ -84,9 +84,8 @@ struct Tiled2Cfg {
 // zeroed when parked).  The zeroing selects cost registers and time in the main loop (256 x 128:
 // 202 -> 158 VGPRs and -5 % time without them), so whole-step hidden sizes get KRAG = false.
 // TOPK (Section "Top-k, Nucleus Sampling, and Masking": per-tile candidates): instead of one
-// candidate per (row, 128-id tile) the epilogue writes several, sorted and packed.  The keys of the
-// workgroup tile are staged in LDS as [BT][VT + 4] floats and one wave handles a (row, candidate
-// tile) unit, four units at once: the p.topk_k <= 8 best of every unit (wave_top_m).
+// candidate per (row, 128-id tile) the epilogue writes the p.topk_k <= 8 best, sorted and packed
+// (per-lane sorted lists in registers, merged across the lanes and waves that share a tile).
 // W4 (with WB = 1, WCODES): MXFP4 weights.  p.W holds E2M1 codes, two per byte, p.w4_scales one E8M0 byte
 // per 32 elements of a row.  A K step is 256 elements = again the same 128 bytes of a W row; LDS holds
 // the codes and, behind the tiles, the step's 8 scale bytes of every row; the hidden tile of a step is
@@ -320,62 +319,96 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     if (base < nk) body(base, std::true_type{});
 
     if constexpr (TOPK) {
-        // the last K step ended with a barrier: the tile buffers are free
-        constexpr int KSTRIDE = VT + 4;                   // floats per batch row of the key array
-        float* keys = reinterpret_cast<float*>(smem);
-#pragma unroll
-        for (int j = 0; j < CB; ++j) {
-            const int bl = wn * (16 * CB) + j * 16 + n;
-            const int b = b0 + bl;
-            const int bc = b < B ? b : B - 1;
-            const float inv_tau = 1.0f / p.tau[bc];
-            const uint64_t sd = p.row_seeds ? p.row_seeds[bc] : p.seed;
-#pragma unroll
-            for (int i = 0; i < RB; ++i) {
-                const int vl = wm * (16 * RB) + i * 16 + 4 * g;
-                float gn[4] = {0.f, 0.f, 0.f, 0.f};
-                if (p.topk_mode == kTopkGumbel)
-                    gumbel4(sd, (uint32_t)(uint64_t)(p.row_offset + bc), (uint32_t)(p.vocab_offset + tile_row0 + vl), gn,
-                            (p.epi_flags & kEpiExactLog) != 0u);
-                f32x4 kq;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) kq[q] = key_sanitize(fmaf(acc[i][j][q], inv_tau, gn[q]));
-                *reinterpret_cast<f32x4*>(keys + bl * KSTRIDE + vl) = kq;
-            }
-        }
-        __syncthreads();
-        constexpr int NUNIT = BT * Cfg::kCandTiles;          // unit = (batch row, candidate tile)
-        constexpr int U = 4;                                 // units a wave works on at once
-        static_assert(NUNIT % (Cfg::kWaves * U) == 0, "units per wave");
+        // A lane holds 4 RB ids of each of its CB batch rows: it keeps a sorted list of the best m of
+        // them in registers (one insertion per key, ascending ids), the four lanes that share a row
+        // merge their lists, and -- where two waves share a 128-id candidate tile -- the two waves'
+        // lists meet in LDS (the last K step ended with a barrier: the tile buffers are free).
+        constexpr int WPT = Cfg::kWavesPerCandTile;
+        static_assert(WPT == 1 || WPT == 2, "one or two waves per candidate tile");
+        static_assert((size_t)WM * BT * kTopkTileM * 8 <= 2 * (size_t)BUFB, "wave lists fit the tile buffers");
         const int kt = p.topk_k;
-        for (int ub = wave * U; ub < NUNIT; ub += Cfg::kWaves * U) {
-            // every address is inside the key array: read first, all eight in flight, then mask
-            float f0[U], f1[U];
+        const int vw0 = tile_row0 + wm * (16 * RB);          // first vocabulary row of this wave
+        const int nvalid = vw0 + 16 * RB <= V ? 1 << 20 : V - vw0 - 4 * g;   // local ids 16 i + q below this exist
+        uint64_t* wave_list = reinterpret_cast<uint64_t*>(smem);             // [WM][BT][M], WPT == 2 only
+        // M: list length; NOISY: keys carry Gumbel noise (compile-time, so that the plain form holds no
+        // generator code and every unrolled loop stays within what the compiler unrolls)
+        auto rows = [&](auto mc, auto noisyc) {
+            constexpr int M = decltype(mc)::value;
+            constexpr bool NOISY = decltype(noisyc)::value;
+            static_for<CB>([&](auto jc) {      // not a loop: unrolled, its body is beyond what the compiler unrolls
+                constexpr int j = decltype(jc)::value;
+                const int bl = wn * (16 * CB) + j * 16 + n;
+                const int b = b0 + bl;
+                const int bc = b < B ? b : B - 1;
+                const float inv_tau = 1.0f / p.tau[bc];
+                const uint64_t sd = p.row_seeds ? p.row_seeds[bc] : p.seed;
+                uint32_t ka[M];
+                int32_t ke[M];
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int u = ub + q, bl = u % BT, ct = u / BT;
-                f0[q] = keys[bl * KSTRIDE + ct * kVocabTile + lane];
-                f1[q] = keys[bl * KSTRIDE + ct * kVocabTile + 64 + lane];
-            }
-            uint32_t k0[U], k1[U];
-            int32_t id0[U];
+                for (int s = 0; s < M; ++s) { ka[s] = 0u; ke[s] = 0; }
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int u = ub + q, ct = u / BT;
-                const int e0 = tile_row0 + ct * kVocabTile + lane, e1 = e0 + 64;
-                const uint32_t o0 = topk_ordered(f0[q]), o1 = topk_ordered(f1[q]);
-                k0[q] = e0 < V ? o0 : 0u;
-                k1[q] = e1 < V ? o1 : 0u;
-                id0[q] = p.vocab_offset + tile_row0 + ct * kVocabTile;
-            }
-            uint64_t res[U];
-            wave_top_m<U>(k0, k1, id0, kt, lane, res);
+                for (int i = 0; i < RB; ++i) {
+                    float gn[4] = {0.f, 0.f, 0.f, 0.f};
+                    if constexpr (NOISY)
+                        gumbel4(sd, (uint32_t)(uint64_t)(p.row_offset + bc), (uint32_t)(p.vocab_offset + vw0 + i * 16 + 4 * g), gn,
+                                (p.epi_flags & kEpiExactLog) != 0u);
 #pragma unroll
-            for (int q = 0; q < U; ++q) {
-                const int u = ub + q, bl = u % BT, ct = u / BT;
-                const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
-                if (b < B && ctile < T && lane < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + lane] = res[q];
+                    for (int q = 0; q < 4; ++q) {
+                        const int e = i * 16 + q;
+                        const uint32_t o = topk_ordered(fmaf(acc[i][j][q], inv_tau, gn[q]));
+                        top_insert<M>(ka, ke, e < nvalid ? o : 0u, e);
+                    }
+                }
+                uint64_t w[M];
+                const int32_t id0 = p.vocab_offset + vw0 + 4 * g;
+#pragma unroll
+                for (int s = 0; s < M; ++s)
+                    w[s] = ka[s] ? ((uint64_t)ka[s] << 32) | (uint64_t)(~(uint32_t)(id0 + ke[s])) : kTopkPad;
+                top_merge<M>(w, 16);
+                top_merge<M>(w, 32);
+                // all four lanes of the row hold its list now: lane group g keeps words g, g + 4
+                const int ctile = tile * Cfg::kCandTiles + wm / WPT;
+                uint64_t* dst = WPT == 1 ? p.topk_out + ((size_t)b * T + ctile) * (size_t)kt
+                                         : wave_list + ((size_t)wm * BT + bl) * M;
+                const bool live = WPT == 1 ? b < B && ctile < T : true;
+#pragma unroll
+                for (int s0 = 0; s0 < M; s0 += 4) {
+                    uint64_t mine = w[s0];
+#pragma unroll
+                    for (int t = 1; t < 4; ++t) mine = g == t ? w[s0 + t] : mine;
+                    if (live && (WPT == 2 || s0 + g < kt)) dst[s0 + g] = mine;
+                }
+                // rows are worked through one after the other: interleaved, their compare masks
+                // would not fit the scalar registers
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if constexpr (WPT == 2) {
+                __syncthreads();
+                for (int u = tid; u < BT * Cfg::kCandTiles; u += Cfg::kThreads) {
+                    const int bl = u % BT, ct = u / BT;
+                    const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
+                    const uint64_t* la = wave_list + ((size_t)(2 * ct) * BT + bl) * M;
+                    const uint64_t* lb = wave_list + ((size_t)(2 * ct + 1) * BT + bl) * M;
+                    uint64_t w[M], o[M];
+#pragma unroll
+                    for (int s = 0; s < M; ++s) { w[s] = la[s]; o[s] = lb[M - 1 - s]; }
+                    top_merge_lists<M>(w, o);
+                    if (b < B && ctile < T) {
+#pragma unroll
+                        for (int s = 0; s < M; ++s)
+                            if (s < kt) p.topk_out[((size_t)b * T + ctile) * (size_t)kt + s] = w[s];
+                    }
+                }
             }
+        };
+        using M4 = std::integral_constant<int, 4>;
+        using M8 = std::integral_constant<int, 8>;
+        if (p.topk_mode == kTopkGumbel) {
+            if (kt <= 4) rows(M4{}, std::true_type{});
+            else rows(M8{}, std::true_type{});
+        } else {
+            if (kt <= 4) rows(M4{}, std::false_type{});
+            else rows(M8{}, std::false_type{});
         }
         return;
     }

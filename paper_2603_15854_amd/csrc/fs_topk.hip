@@ -6,16 +6,17 @@
 namespace fs {
 
 // Stage 1 with the per-tile candidate epilogue, whole K steps only.  shape = 0: the split-K kernel in
-// the decode regime, two shapes of the tiled kernel up to 64 rows, its 256 x 128 shape up to 128 rows,
-// and above that the kernel with direct global -> LDS loads in the tile pick_tile_shape takes for the
-// plain path.  shape = 3, 6, 7, 12, 13 forces that shape (tuning aid and test hook).
+// the decode regime, two shapes of the tiled kernel up to 64 rows, and above that the kernel with direct
+// global -> LDS loads: 256 x 128 tiles up to 128 rows (C2 shape, B = 128: 197 us against 201 us on the
+// tiled kernel's 256 x 128 shape), then the tile pick_tile_shape takes for the plain path.
+// shape = 3, 6, 7, 12, 13 forces that shape (tuning aid and test hook).
 fs_status launch_stage1_topk(const Stage1Params& p, int shape, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
     if (shape == 0) {
         if (p.B <= 16 && p.D <= 4096) return launch_stage1_splitk_topk(p, st);
         if (p.B <= 128) {
-            shape = p.B <= 32 ? 6 : p.B <= 64 ? 7 : 3;
+            shape = p.B <= 32 ? 6 : p.B <= 64 ? 7 : 13;
         } else {
             int cus = 0;
             const fs_status ds = current_device(nullptr, &cus);

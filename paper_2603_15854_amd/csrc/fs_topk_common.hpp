@@ -210,16 +210,12 @@ __device__ __forceinline__ void top_insert(uint32_t (&ka)[M], int32_t (&ke)[M], 
     ke[0] = c[0] ? e : ke[0];
 }
 
-// w: this lane's M packed words in descending order.  Afterwards both this lane and the lane `step`
-// away (lane ^ step) hold the M largest of their 2 M words, in descending order: the elementwise
-// maximum with the partner's list reversed is the upper half as a bitonic sequence, which log2(M)
-// rounds of compare-exchange sort.  Packed words of different ids differ, so both lanes agree.
+// w and o: two lists of M packed words, w in descending and o in ASCENDING order.  Afterwards w holds
+// the M largest of the 2 M words in descending order: the elementwise maximum is the upper half of the
+// union as a bitonic sequence, which log2(M) rounds of compare-exchange sort.
 template <int M>
-__device__ __forceinline__ void top_merge(uint64_t (&w)[M], int step)
+__device__ __forceinline__ void top_merge_lists(uint64_t (&w)[M], const uint64_t (&o)[M])
 {
-    uint64_t o[M];
-#pragma unroll
-    for (int s = 0; s < M; ++s) o[s] = __shfl_xor((unsigned long long)w[M - 1 - s], step, kWave);
 #pragma unroll
     for (int s = 0; s < M; ++s) w[s] = w[s] > o[s] ? w[s] : o[s];
 #pragma unroll
@@ -231,6 +227,18 @@ __device__ __forceinline__ void top_merge(uint64_t (&w)[M], int step)
                 w[s] = hi;
                 w[s + d] = lo;
             }
+}
+
+// w: this lane's M packed words in descending order.  Afterwards both this lane and the lane `step`
+// away (lane ^ step) hold the M largest of their 2 M words, in descending order.  Packed words of
+// different ids differ, so both lanes agree.
+template <int M>
+__device__ __forceinline__ void top_merge(uint64_t (&w)[M], int step)
+{
+    uint64_t o[M];
+#pragma unroll
+    for (int s = 0; s < M; ++s) o[s] = __shfl_xor((unsigned long long)w[M - 1 - s], step, kWave);
+    top_merge_lists<M>(w, o);
 }
 
 }  // namespace fs
