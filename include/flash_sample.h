@@ -202,7 +202,7 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
  *   flags      FS_FLAG_NONE or FS_FLAG_EXACT_LOG; flash_sample_topk also takes, as a tuning aid,
  *              FS_TUNE_TILE_SHAPE(n) with n = 3, 6, 7 (tiled kernel 256 x 128, 512 x 32, 512 x 64) or
  *              12, 13 (direct-to-LDS kernel 256 x 256, 256 x 128) for its stage 1; 0 = automatic
- *              (split-K for B <= 16 and D <= 4096, 6 / 7 / 3 up to 32 / 64 / 128 rows, 12 or 13 above)
+ *              (split-K for B <= 16 and D <= 4096, 6 / 7 / 13 up to 32 / 64 / 128 rows, 12 or 13 above)
  * NaN logits count as -inf.  flash_sample_topk is the fused form: the [B, V] logits never reach device
  * memory.  Stage 1 writes the min(k, m) best candidates of every row and 128-id tile (m = 8 for
  * B <= 32, 4 above) and a selection reduces them to k per row.  For k > m a tile whose m-th candidate
