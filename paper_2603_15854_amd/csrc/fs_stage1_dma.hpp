@@ -30,6 +30,9 @@
 // v_mfma_f32_16x16x32_bf16, a lane owns four consecutive vocabulary ids of one batch row per
 // 16 x 16 block.  A wave's 128 vocabulary rows are exactly one candidate tile, so candidates go
 // from the lane-group merge straight to the candidate buffer, without a cross-wave merge.
+// TOPK (Section "Top-k, Nucleus Sampling, and Masking": per-tile candidates): the epilogue writes the
+// p.topk_k <= 8 best keys of every (batch row, 128-id tile), sorted and packed, instead of one
+// candidate.
 #pragma once
 
 #include "fs_common.hpp"
@@ -285,9 +288,8 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
                  : "+a"(acc[0][CB - 1]), "+a"(acc[1][CB - 1]), "+a"(acc[2][CB - 1]), "+a"(acc[3][CB - 1]),
                    "+a"(acc[4][CB - 1]), "+a"(acc[5][CB - 1]), "+a"(acc[6][CB - 1]), "+a"(acc[7][CB - 1]));
 
-    // acc[i][j][q] = logit of vocabulary row tile_row0 + 128 wm + 16 i + 4 g + q, batch row
-    // b0 + (BT/2) wn + 16 j + n.
-    // Epilogue.  Registers cannot be indexed by a loop variable, and the epilogue
+    // Epilogue.  acc[i][j][q] = logit of vocabulary row tile_row0 + 128 wm + 16 i + 4 g + q, batch row
+    // b0 + (BT/2) wn + 16 j + n.  Registers cannot be indexed by a loop variable, and the epilogue
     // unrolled over all 8 x CB accumulator tiles is several hundred KB of code that each wave walks
     // through once per tile (instruction fetch and spills then cost more than its arithmetic).  So
     // each wave parks its accumulators in LDS, which is free now, CJ column blocks at a time, and
