@@ -328,7 +328,7 @@ def main() -> int:
         # -------------------------------------------------------------- top-k / top-p: fused against stored logits
         if want("top_k"):
             rows_k = []
-            for Bs, kk in ((16, 50), (64, 50), (256, 50), (64, 8), (64, 64)):
+            for Bs, kk in ((16, 50), (64, 50), (128, 50), (256, 50), (64, 8), (64, 64)):
                 leg = Leg(w, Wd, Bs, want_logits=True)
                 wsk = torch.empty(fs.flash_sample_topk_workspace_bytes(Bs, V, kk), dtype=torch.uint8, device="cuda")
                 tv = torch.empty((Bs, kk), dtype=torch.float32, device="cuda")
