@@ -200,9 +200,9 @@ fs_status flash_sample_full(const void* hidden, const void* W, int B, int D, int
  *   n_kept     NULL, or int32 [B]: candidates kept by the nucleus rule (those with a key > -inf)
  *   workspace  at least flash_sample_topk_workspace_bytes(B, V, k) bytes, 256-byte aligned
  *   flags      FS_FLAG_NONE or FS_FLAG_EXACT_LOG; flash_sample_topk also takes, as a tuning aid,
- *              FS_TUNE_TILE_SHAPE(n) with n = 3, 6, 7 (tiled kernel 256 x 128, 512 x 32, 512 x 64) or
- *              12, 13 (direct-to-LDS kernel 256 x 256, 256 x 128) for its stage 1; 0 = automatic
- *              (split-K for B <= 16 and D <= 4096, 6 / 7 / 13 up to 32 / 64 / 128 rows, 12 or 13 above)
+ *              FS_TUNE_TILE_SHAPE(n) for its stage 1 (n = 1..8, 10, 12, 13: the tile shapes listed at
+ *              FS_VARIANT_TILED2 above); 0 = automatic: split-K for B <= 16 and D <= 4096, else the shape the
+ *              plain path takes, with 13 in place of 3 and 4
  * NaN logits count as -inf.  flash_sample_topk is the fused form: the [B, V] logits never reach device
  * memory.  Stage 1 writes the min(k, m) best candidates of every row and 128-id tile (m = 8 for
  * B <= 32, 4 above) and a selection reduces them to k per row.  For k > m a tile whose m-th candidate

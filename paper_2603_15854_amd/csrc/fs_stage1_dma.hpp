@@ -373,7 +373,10 @@ stage1_dma_kernel(const Stage1Params p, const int nbt)
                             uint64_t mine = w[s0];
 #pragma unroll
                             for (int t = 1; t < 4; ++t) mine = g == t ? w[s0 + t] : mine;
-                            if (s0 + g < kt) dst[s0 + g] = mine;
+                            // non-temporal: 32 bytes per (row, tile), read once by the selection.  Stored
+                            // normally these lines crowd the hidden tile out of L2 (it fills most of it at
+                            // D >= 7168): the launch took 9 % longer at D = 7168, B = 256
+                            if (s0 + g < kt) __builtin_nontemporal_store(mine, dst + s0 + g);
                         }
                     }
                 }

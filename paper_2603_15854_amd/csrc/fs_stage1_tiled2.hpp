@@ -321,15 +321,15 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
     if constexpr (TOPK) {
         // A lane holds 4 RB ids of each of its CB batch rows: it keeps a sorted list of the best m of
         // them in registers (one insertion per key, ascending ids), the four lanes that share a row
-        // merge their lists, and -- where two waves share a 128-id candidate tile -- the two waves'
-        // lists meet in LDS (the last K step ended with a barrier: the tile buffers are free).
+        // merge their lists, and -- where two or four waves share a 128-id candidate tile -- the
+        // waves' lists meet in LDS (the last K step ended with a barrier: the tile buffers are free).
         constexpr int WPT = Cfg::kWavesPerCandTile;
-        static_assert(WPT == 1 || WPT == 2, "one or two waves per candidate tile");
+        static_assert(WPT == 1 || WPT == 2 || WPT == 4, "one, two or four waves per candidate tile");
         static_assert((size_t)WM * BT * kTopkTileM * 8 <= 2 * (size_t)BUFB, "wave lists fit the tile buffers");
         const int kt = p.topk_k;
         const int vw0 = tile_row0 + wm * (16 * RB);          // first vocabulary row of this wave
         const int nvalid = vw0 + 16 * RB <= V ? 1 << 20 : V - vw0 - 4 * g;   // local ids 16 i + q below this exist
-        uint64_t* wave_list = reinterpret_cast<uint64_t*>(smem);             // [WM][BT][M], WPT == 2 only
+        uint64_t* wave_list = reinterpret_cast<uint64_t*>(smem);             // [WM][BT][M], WPT > 1 only
         // M: list length; NOISY: keys carry Gumbel noise (compile-time, so that the plain form holds no
         // generator code and every unrolled loop stays within what the compiler unrolls)
         auto rows = [&](auto mc, auto noisyc) {
@@ -376,23 +376,29 @@ stage1_tiled2_kernel(const Stage1Params p, const int nbt)
                     uint64_t mine = w[s0];
 #pragma unroll
                     for (int t = 1; t < 4; ++t) mine = g == t ? w[s0 + t] : mine;
-                    if (live && (WPT == 2 || s0 + g < kt)) dst[s0 + g] = mine;
+                    if (live && (WPT > 1 || s0 + g < kt)) dst[s0 + g] = mine;
                 }
                 // rows are worked through one after the other: interleaved, their compare masks
                 // would not fit the scalar registers
                 __builtin_amdgcn_sched_barrier(0);
             });
-            if constexpr (WPT == 2) {
+            if constexpr (WPT > 1) {
                 __syncthreads();
                 for (int u = tid; u < BT * Cfg::kCandTiles; u += Cfg::kThreads) {
                     const int bl = u % BT, ct = u / BT;
                     const int b = b0 + bl, ctile = tile * Cfg::kCandTiles + ct;
-                    const uint64_t* la = wave_list + ((size_t)(2 * ct) * BT + bl) * M;
-                    const uint64_t* lb = wave_list + ((size_t)(2 * ct + 1) * BT + bl) * M;
-                    uint64_t w[M], o[M];
+                    uint64_t w[M];
+                    const uint64_t* la = wave_list + ((size_t)(WPT * ct) * BT + bl) * M;
 #pragma unroll
-                    for (int s = 0; s < M; ++s) { w[s] = la[s]; o[s] = lb[M - 1 - s]; }
-                    top_merge_lists<M>(w, o);
+                    for (int s = 0; s < M; ++s) w[s] = la[s];
+#pragma unroll
+                    for (int x = 1; x < WPT; ++x) {
+                        const uint64_t* lb = wave_list + ((size_t)(WPT * ct + x) * BT + bl) * M;
+                        uint64_t o[M];
+#pragma unroll
+                        for (int s = 0; s < M; ++s) o[s] = lb[M - 1 - s];
+                        top_merge_lists<M>(w, o);
+                    }
                     if (b < B && ctile < T) {
 #pragma unroll
                         for (int s = 0; s < M; ++s)

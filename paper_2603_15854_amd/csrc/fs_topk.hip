@@ -6,28 +6,33 @@
 namespace fs {
 
 // Stage 1 with the per-tile candidate epilogue, whole K steps only.  shape = 0: the split-K kernel in
-// the decode regime, two shapes of the tiled kernel up to 64 rows, and above that the kernel with direct
-// global -> LDS loads: 256 x 128 tiles up to 128 rows (C2 shape, B = 128: 197 us against 201 us on the
-// tiled kernel's 256 x 128 shape), then the tile pick_tile_shape takes for the plain path.
-// shape = 3, 6, 7, 12, 13 forces that shape (tuning aid and test hook).
+// the decode regime, else the tile shape pick_tile_shape takes for the plain path (the shape decides
+// how many rounds of workgroups a launch needs: at V = 152064, B = 64 the 512 x 64 shape takes 247 us
+// and the 128 x 64 shape 199 us), except that the two 128-row shapes whose waves share candidate tiles
+// (256 x 128, 128 x 128) give way to the 256 x 128 form of the kernel with direct global -> LDS loads
+// (C2 shape, B = 128: 196 us against 209 and 234 us; D = 3584, V = 152064: 242 us against 251 and 252 us).
+// shape = 1..8, 10, 12, 13 forces that shape (tuning aid and test hook).
 fs_status launch_stage1_topk(const Stage1Params& p, int shape, hipStream_t st)
 {
     if (p.D % 64 != 0) return FS_ERR_UNSUPPORTED;
     if (shape == 0) {
         if (p.B <= 16 && p.D <= 4096) return launch_stage1_splitk_topk(p, st);
-        if (p.B <= 128) {
-            shape = p.B <= 32 ? 6 : p.B <= 64 ? 7 : 13;
-        } else {
-            int cus = 0;
-            const fs_status ds = current_device(nullptr, &cus);
-            if (ds != FS_OK) return ds;
-            shape = pick_tile_shape(p.B, p.D, p.V, cus);
-        }
+        int cus = 0;
+        const fs_status ds = current_device(nullptr, &cus);
+        if (ds != FS_OK) return ds;
+        shape = pick_tile_shape(p.B, p.D, p.V, cus);
+        if (shape == 3 || shape == 4) shape = 13;
     }
     switch (shape) {
+    case 1: return launch_tiled2<Shape1, false, 2, false, false, false, true>(p, st);   // 128 x 32
+    case 2: return launch_tiled2<Shape2, false, 2, false, false, false, true>(p, st);   // 256 x 64
+    case 3: return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);    // 256 x 128, batch tiles XCD-paired
+    case 4: return launch_tiled2<Shape4, false, 2, false, false, true, true>(p, st);    // 128 x 128
+    case 5: return launch_tiled2<Shape5, false, 2, false, false, false, true>(p, st);   // 128 x 64
     case 6: return launch_tiled2<Shape6, false, 2, false, false, false, true>(p, st);   // 512 x 32
     case 7: return launch_tiled2<Shape7, false, 2, false, false, false, true>(p, st);   // 512 x 64
-    case 3: return launch_tiled2<Shape3, false, 2, false, false, true, true>(p, st);    // 256 x 128, batch tiles XCD-paired
+    case 8: return launch_tiled2<Shape8, false, 2, false, false, false, true>(p, st);   // 256 x 32
+    case 10: return launch_tiled2<Shape10, false, 2, false, false, false, true>(p, st); // 512 x 128
     case 12: return launch_stage1_dma_topk(p, 256, st);
     case 13: return launch_stage1_dma_topk(p, 128, st);
     default: return FS_ERR_UNSUPPORTED;

@@ -120,7 +120,7 @@ def test_topk_matches_oracle(fs, orc, case, mode, fused):
     assert near <= max(2, B // 10), (exact, near)
 
 
-@pytest.mark.parametrize("shape", [3, 6, 7, 12, 13])
+@pytest.mark.parametrize("shape", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 13])
 @pytest.mark.parametrize("mode", [TRUNC, GUMBEL])
 def test_fused_topk_on_every_stage1_kernel(fs, orc, shape, mode):
     # the tile shape forced: every kernel with the per-tile candidate epilogue on batch sizes below, at and
@@ -174,11 +174,11 @@ def test_fused_and_unfused_agree_and_gumbel_first_is_the_plain_sample(fs, orc):
                                 flags=fs.FS_VARIANT(fs.FS_VARIANT_SPLITK))
     torch.cuda.synchronize()
     assert np.array_equal(pi.cpu().numpy(), f[0]) and np.array_equal(pv.cpu().numpy(), f[1])
-    # ... and at B > 16 the tiled kernel, same tile shape
+    # ... and at B > 16 the tiled kernel, same tile shape (both forced to it)
     B2 = 24
     H2, _ = wl.make_small(D=D, V=8, B=B2, data_seed=561)
     tau2 = np.full(B2, 0.9, dtype=np.float32)
-    f2 = run(fs, H2, W, tau2, k, 1.0, GUMBEL, True, seed=4)
+    f2 = run(fs, H2, W, tau2, k, 1.0, GUMBEL, True, seed=4, flags=fs.FS_TUNE_TILE_SHAPE(6))
     pi, pv = fs.flash_sample_ex(to_device_bf16(H2), to_device_bf16(W), dev(tau2, np.float32), seed=4,
                                 flags=fs.FS_VARIANT(fs.FS_VARIANT_TILED2) | fs.FS_TUNE_TILE_SHAPE(6))
     torch.cuda.synchronize()
