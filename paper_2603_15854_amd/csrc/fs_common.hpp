@@ -78,8 +78,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
         // one 32x32->64 multiply per product (v_mad_u64_u32) instead of separate high and low halves
         const uint64_t p0 = (uint64_t)M0 * (uint64_t)c0;
         const uint64_t p1 = (uint64_t)M1 * (uint64_t)c2;
-        const uint32_t t0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t t2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        // a ^ b ^ c as one three-input bit operation (truth table 0x96); the compiler emits two xors
+        const uint32_t t0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+        const uint32_t t2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
         c0 = t0; c1 = (uint32_t)p1; c2 = t2; c3 = (uint32_t)p0;
         k0 += W0; k1 += W1;
     }
