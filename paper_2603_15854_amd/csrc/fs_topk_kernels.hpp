@@ -200,16 +200,28 @@ topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32
     if (tid == 0) s_count = 0;
     __syncthreads();
     int rank = lane;                             // position of m among the 256 maxima (ties: lower wave first)
-    for (int w2 = 0; w2 < 4; ++w2) {
-        if (w2 == wave) continue;
-        const uint64_t* run = s_max + w2 * 64;
-        auto before = [&](uint64_t o) { return o > m || (o == m && w2 < wave); };
-        int cnt = 0;
+    {
+        // the three other runs are searched side by side: their LDS reads are independent chains
+        int cnt[3] = {0, 0, 0};
+        auto before = [&](int r, uint64_t o) {
+            const int w2 = r + (r >= wave ? 1 : 0);
+            return o > m || (o == m && w2 < wave);
+        };
+        auto run = [&](int r) { return s_max + (r + (r >= wave ? 1 : 0)) * 64; };
 #pragma unroll
-        for (int step = 32; step >= 1; step >>= 1)
-            if (before(run[cnt + step - 1])) cnt += step;
-        if (cnt == 63 && before(run[63])) cnt = 64;
-        rank += cnt;
+        for (int step = 32; step >= 1; step >>= 1) {
+            uint64_t o[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) o[r] = run(r)[cnt[r] + step - 1];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                if (before(r, o[r])) cnt[r] += step;
+        }
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            if (cnt[r] == 63 && before(r, run(r)[63])) cnt[r] = 64;
+            rank += cnt[r];
+        }
     }
     if (rank == k - 1) s_thr = m;
     __syncthreads();
@@ -223,7 +235,13 @@ topk_select_kernel(const void* __restrict__ in, int64_t row_stride, int N, int32
     }
     __syncthreads();
     const int n = s_count;
-    if (n <= 128) {
+    if (n <= 64) {                               // the usual case: little more than k passers
+        if (tid < kWave) {
+            uint64_t a0 = tid < n ? s_list[tid] : kTopkPad;
+            wave_sort64_desc(a0, tid);
+            s_list[tid] = a0;
+        }
+    } else if (n <= 128) {
         if (tid < kWave) {
             uint64_t a0 = tid < n ? s_list[tid] : kTopkPad;
             uint64_t a1 = tid + 64 < n ? s_list[tid + 64] : kTopkPad;
