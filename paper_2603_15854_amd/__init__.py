@@ -76,6 +76,11 @@ def lib():
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2603_15854_amd.build` "
             "(there is no fallback path)")
+    # One HIP runtime per process, and it has to be the one torch brings: the tensors this binding is
+    # handed are allocated by it.  The library names the runtime by its soname only, so whichever copy
+    # is loaded first serves both; loading this library before torch would put torch on the system's
+    # copy (every launch then fails with a HIP error).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, u32, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint32, C.c_uint64, C.c_size_t
     L.flash_sample_num_tiles.argtypes = [i32]
