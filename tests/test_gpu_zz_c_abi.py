@@ -37,3 +37,24 @@ def test_plain_c_program_matches_oracle(orc, tmp_path, shape):
     ref = orc.sample(H, W, tau, seed=77)
     v = judge(orc, H, W, tau, idx, val, ref, seed=77)
     assert v.ok, (shape, str(v), v.failures[:3], res.stdout)
+
+
+def test_binding_loaded_before_torch_is_imported():
+    # A process that loads the library first (build() followed by smoke() does) must end up with one HIP
+    # runtime serving both the library and torch: the binding imports torch before it loads the library.
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2603_15854_amd as fs\n"
+        "fs.lib()\n"
+        "import torch, numpy as np\n"
+        "import fs_workloads as wl\n"
+        "from tests.parity import to_device_bf16\n"
+        "H, W = wl.make_small(D=256, V=1000, B=4, data_seed=3)\n"
+        "idx, val = fs.flash_sample_ex(to_device_bf16(H), to_device_bf16(W), torch.ones(4, device='cuda'), seed=5)\n"
+        "torch.cuda.synchronize()\n"
+        "print('IDX', idx.cpu().tolist())\n" % root)
+    res = subprocess.run([os.sys.executable, "-c", code], capture_output=True, text=True, timeout=300, cwd=root)
+    assert res.returncode == 0 and "IDX" in res.stdout, (res.stdout[-500:], res.stderr[-1500:])
