@@ -139,6 +139,22 @@ def test_fused_topk_on_every_stage1_kernel(fs, orc, shape, mode):
         assert near <= max(2, B // 10), (shape, B, exact, near)
 
 
+@pytest.mark.parametrize("B", [8, 40, 100, 140])
+def test_gumbel_topk_with_the_library_logarithms(fs, orc, B):
+    # FS_FLAG_EXACT_LOG on every kernel that forms noisy keys (split-K, tiled, direct-to-LDS): judged against
+    # the oracle like the default mode, and the two modes pick the same ids up to near-ties
+    D, V, k = 256, 3000, 24
+    H, W = wl.make_small(D=D, V=V, B=B, data_seed=940 + B, w_row_scale=2.0)
+    tau = np.linspace(0.7, 1.4, B).astype(np.float32)
+    ref = orc.sample_topk(H, W, tau, k, top_p=1.0, mode=GUMBEL, seed=21, vocab_offset=5)
+    exact_mode = run(fs, H, W, tau, k, 1.0, GUMBEL, True, seed=21, vocab_offset=5, flags=fs.FS_FLAG_EXACT_LOG)
+    fast_mode = run(fs, H, W, tau, k, 1.0, GUMBEL, True, seed=21, vocab_offset=5)
+    e, near = judge_topk(orc, H, W, tau, k, 1.0, GUMBEL, ref, exact_mode, seed=21, vocab_offset=5)
+    assert near <= max(2, B // 10), (e, near)
+    assert (exact_mode[3] != fast_mode[3]).sum() <= max(2, B * k // 200)
+    assert np.allclose(exact_mode[2], fast_mode[2], rtol=0, atol=2e-5 * (1 + np.abs(fast_mode[2]).max()))
+
+
 def test_topk_seeded_random_shapes(fs, orc):
     # a seeded sweep over batch sizes on both sides of every kernel boundary, ragged vocabularies, k, top_p,
     # both modes and forms, and vocabulary offsets that are not multiples of the four ids of a noise block
