@@ -14,9 +14,11 @@ fs_status launch_stage1_w8(const Stage1Params& p, int variant, int tune, hipStre
     if (variant == FS_VARIANT_SPLITK && !splitk_ok) return FS_ERR_UNSUPPORTED;
     if (variant != FS_VARIANT_TILED2 && splitk_ok) {
         const int wgs = variant == FS_VARIANT_SPLITK ? tune : 0;
-        if (ksteps <= 32 * 4) {   // eight waves of 16 k-steps: 82 us against 90 us for four waves of 32
+        if (ksteps <= 32 * 4) {   // eight waves of 16 k-steps: 82 us against 90 us for four waves of 32;
+            // 8-k-step stages with two register sets in flight: 84.7 us against 85.7 us at B = 16 for one
+            // 16-k-step stage (more of the stream stays in flight across a tile's epilogue)
             const int nw = (ksteps + 15) / 16;
-            return launch_splitk<SplitKCfg<16, 16, 1, 8, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
+            return launch_splitk<SplitKCfg<16, 8, 2, 8, 1>>(p, (ksteps + nw - 1) / nw, nw, wgs, st);
         }
         // wide hidden sizes: eight waves of 32 k-steps, one register set of prefetch
         const int nw = (ksteps + 31) / 32;
